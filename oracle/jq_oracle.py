@@ -1,0 +1,139 @@
+"""ctypes wrapper around the fp64 CPU oracle (``jq_oracle.c``) -- TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the benchmark's ``cpu_baseline`` leg may
+import this module.  It never touches the HIP library and shares nothing with
+it.  Batched helpers here are plain Python loops over (layer, sequence) calling
+the single-problem C functions, following Section 4.3 of the paper one problem
+at a time.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "jq_oracle.c")
+_LIB = os.path.join(_HERE, "libjq_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math).  Returns the .so path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        u16p, f64p, i32p = (np.ctypeslib.ndpointer(dtype=t, flags="C_CONTIGUOUS") for t in (np.uint16, np.float64, np.int32))
+        lib.jqo_num_threads.restype = ctypes.c_int
+        lib.jqo_score.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p]
+        lib.jqo_pool.argtypes = [ctypes.c_long, ctypes.c_int, f64p, f64p]
+        lib.jqo_select_topk.argtypes = [ctypes.c_long, ctypes.c_long, f64p, i32p]
+        lib.jqo_compact.argtypes = [ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_long, u16p, u16p, i32p, u16p, u16p]
+        for f in (lib.jqo_score, lib.jqo_pool, lib.jqo_select_topk, lib.jqo_compact):
+            f.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().jqo_num_threads())
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError("oracle %s rejected its arguments (rc=%d)" % (what, rc))
+
+
+def score(Q: np.ndarray, K: np.ndarray, scale: float = 0.0) -> np.ndarray:
+    """Q [n_q,h_q,d], K [L,h_kv,d] bf16 bits (uint16) -> score [h_kv, L] float64."""
+    Q = np.ascontiguousarray(Q, dtype=np.uint16)
+    K = np.ascontiguousarray(K, dtype=np.uint16)
+    n_q, h_q, d = Q.shape
+    L, h_kv, d2 = K.shape
+    if d != d2:
+        raise ValueError("head dims differ")
+    out = np.empty((h_kv, L), dtype=np.float64)
+    _check(_load().jqo_score(n_q, h_q, h_kv, d, L, float(scale), Q, K, out), "score")
+    return out
+
+
+def pool(scores: np.ndarray, pool_k: int) -> np.ndarray:
+    """scores [h_kv, L] (or [L]) float64 -> pooled, same shape."""
+    s = np.ascontiguousarray(scores, dtype=np.float64)
+    flat = s.reshape(-1, s.shape[-1])
+    out = np.empty_like(flat)
+    for g in range(flat.shape[0]):
+        _check(_load().jqo_pool(flat.shape[1], int(pool_k), flat[g], out[g]), "pool")
+    return out.reshape(s.shape)
+
+
+def select_topk(pooled: np.ndarray, B: int) -> np.ndarray:
+    """pooled [h_kv, L] (or [L]) float64 -> idx [h_kv, B] (or [B]) int32, ascending."""
+    p = np.ascontiguousarray(pooled, dtype=np.float64)
+    flat = p.reshape(-1, p.shape[-1])
+    out = np.empty((flat.shape[0], int(B)), dtype=np.int32)
+    for g in range(flat.shape[0]):
+        _check(_load().jqo_select_topk(flat.shape[1], int(B), flat[g], out[g]), "select_topk")
+    return out.reshape(p.shape[:-1] + (int(B),))
+
+
+def compact(K: np.ndarray, V: np.ndarray, idx: np.ndarray):
+    """K,V [L,h_kv,d] uint16, idx [h_kv,B] int32 -> K_out,V_out [B,h_kv,d] uint16."""
+    K = np.ascontiguousarray(K, dtype=np.uint16)
+    V = np.ascontiguousarray(V, dtype=np.uint16)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    L, h_kv, d = K.shape
+    B = idx.shape[1]
+    Ko = np.empty((B, h_kv, d), dtype=np.uint16)
+    Vo = np.empty_like(Ko)
+    _check(_load().jqo_compact(L, h_kv, d, B, K, V, idx, Ko, Vo), "compact")
+    return Ko, Vo
+
+
+def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0):
+    """One (layer, sequence): score -> pool -> top-B -> gather.  Returns a dict."""
+    s = score(Q, K, scale)
+    p = pool(s, pool_k)
+    idx = select_topk(p, B)
+    Ko, Vo = compact(K, V, idx)
+    return {"scores": s, "pooled": p, "idx": idx, "K_out": Ko, "V_out": Vo}
+
+
+def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0):
+    """Layers x ragged sequences, one problem at a time.
+
+    Q [nl,n_seq,n_q,h_q,d], K/V [nl,T,h_kv,d] uint16.  Returns pooled [nl,h_kv,T],
+    scores [nl,h_kv,T], idx [nl,h_kv,TB] (sequence-local), K_out/V_out [nl,TB,h_kv,d].
+    """
+    nl, T, h_kv, d = K.shape
+    cu = [int(x) for x in cu_seqlens]
+    cb = np.concatenate([[0], np.cumsum(budgets)]).astype(np.int64)
+    TB = int(cb[-1])
+    scores = np.empty((nl, h_kv, T)); pooled = np.empty((nl, h_kv, T))
+    idx = np.empty((nl, h_kv, TB), dtype=np.int32)
+    Ko = np.empty((nl, TB, h_kv, d), dtype=np.uint16); Vo = np.empty_like(Ko)
+    for l in range(nl):
+        for s in range(len(cu) - 1):
+            r = evict(Q[l, s], K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], int(budgets[s]), pool_k, scale)
+            scores[l, :, cu[s]:cu[s + 1]] = r["scores"]
+            pooled[l, :, cu[s]:cu[s + 1]] = r["pooled"]
+            idx[l, :, cb[s]:cb[s + 1]] = r["idx"]
+            Ko[l, cb[s]:cb[s + 1]] = r["K_out"]
+            Vo[l, cb[s]:cb[s + 1]] = r["V_out"]
+    return {"scores": scores, "pooled": pooled, "idx": idx, "K_out": Ko, "V_out": Vo}
+
+
+def hit_rate(idx_cur, idx_ref) -> float:
+    """Critical-KV hit rate (Eq. 6): |I_cur & I_ref| / |I_ref| for two index sets."""
+    a, b = set(int(x) for x in np.ravel(idx_cur)), set(int(x) for x in np.ravel(idx_ref))
+    return len(a & b) / float(len(b))

@@ -1,0 +1,148 @@
+"""Pins for the oracle's pooling, top-B retention and pruned-cache gather
+(Section 4.3; pooling as in the baselines paragraph of Section 5.1), and for the
+hit-rate helper (Eq. 6)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+
+
+# ---------------------------------------------------------------- pooling
+@pytest.mark.parametrize("L", [1, 2, 3, 6, 7, 8, 40])
+def test_pool_constant_input(L):
+    c = 3.5
+    j = np.arange(L)
+    w = (np.minimum(j, 3) + np.minimum(L - 1 - j, 3) + 1) / 7.0
+    np.testing.assert_allclose(oracle.pool(np.full(L, c), 7), c * w, rtol=1e-15)
+
+
+def test_pool_constant_edges_are_4567():
+    np.testing.assert_allclose(oracle.pool(np.full(20, 7.0), 7)[:5], [4, 5, 6, 7, 7], rtol=1e-15)
+    np.testing.assert_allclose(oracle.pool(np.full(20, 7.0), 7)[-4:], [7, 6, 5, 4], rtol=1e-15)
+
+
+@pytest.mark.parametrize("j", [0, 2, 10, 18, 19])
+def test_pool_unit_impulse(j):
+    L = 20
+    x = np.zeros(L); x[j] = 1.0
+    want = np.zeros(L); want[max(0, j - 3):min(L, j + 4)] = 1.0 / 7.0
+    np.testing.assert_allclose(oracle.pool(x, 7), want, rtol=1e-15)
+
+
+def test_pool_identity_linearity_and_weights():
+    rng = np.random.default_rng(0)
+    a, b = rng.random(57), rng.random(57)
+    np.testing.assert_array_equal(oracle.pool(a, 1), a)
+    np.testing.assert_allclose(oracle.pool(a + b, 7), oracle.pool(a, 7) + oracle.pool(b, 7), rtol=1e-14)
+    j = np.arange(57)
+    w = (np.minimum(j, 3) + np.minimum(56 - j, 3) + 1) / 7.0
+    np.testing.assert_allclose(oracle.pool(a, 7).sum(), (w * a).sum(), rtol=1e-14)
+
+
+@pytest.mark.parametrize("k", [3, 5, 7, 9])
+def test_pool_matches_numpy_convolve(k):
+    rng = np.random.default_rng(1)
+    x = rng.random((3, 101))
+    want = np.stack([np.convolve(r, np.ones(k) / k, mode="same") for r in x])
+    np.testing.assert_allclose(oracle.pool(x, k), want, rtol=1e-13)
+
+
+def test_pool_rejects_even_kernel():
+    with pytest.raises(ValueError):
+        oracle.pool(np.ones(8), 4)
+
+
+# ---------------------------------------------------------------- top-B
+def test_select_exhaustive_max_mass():
+    rng = np.random.default_rng(2)
+    for L in (5, 9, 12):
+        x = rng.random(L)
+        for B in range(1, L + 1):
+            idx = oracle.select_topk(x, B)
+            best = max(itertools.combinations(range(L), B), key=lambda c: sum(x[list(c)]))
+            assert list(idx) == list(best)                                 # combinations are ascending tuples
+            assert list(idx) == sorted(set(idx)) and idx.min() >= 0 and idx.max() < L
+
+
+def test_select_special_cases():
+    x = np.array([0.1, 0.9, 0.3, 0.9, 0.2])
+    np.testing.assert_array_equal(oracle.select_topk(x, 1), [1])          # first argmax
+    np.testing.assert_array_equal(oracle.select_topk(x, 2), [1, 3])
+    np.testing.assert_array_equal(oracle.select_topk(x, 5), np.arange(5))  # B = L
+    np.testing.assert_array_equal(oracle.select_topk(np.full(10, 0.5), 4), [0, 1, 2, 3])
+
+
+def test_select_ties_prefer_lower_index():
+    x = np.array([1.0, 2.0, 2.0, 2.0, 0.5, 2.0])
+    np.testing.assert_array_equal(oracle.select_topk(x, 3), [1, 2, 3])
+    np.testing.assert_array_equal(oracle.select_topk(x, 5), [0, 1, 2, 3, 5])
+
+
+def test_select_matches_numpy_stable_sort():
+    rng = np.random.default_rng(3)
+    x = np.round(rng.random((4, 1000)), 2)                                # many exact ties
+    for B in (1, 17, 500, 1000):
+        got = oracle.select_topk(x, B)
+        for g in range(4):
+            order = np.lexsort((np.arange(1000), -x[g]))                  # score desc, index asc
+            np.testing.assert_array_equal(got[g], np.sort(order[:B]))
+
+
+def test_select_rejects_bad_budget():
+    for B in (0, 6):
+        with pytest.raises(ValueError):
+            oracle.select_topk(np.ones(5), B)
+
+
+# ---------------------------------------------------------------- gather
+def test_compact_is_a_gather():
+    rng = np.random.default_rng(4)
+    L, h_kv, d, B = 50, 3, 8, 7
+    K = rng.integers(0, 65536, (L, h_kv, d)).astype(np.uint16)
+    V = rng.integers(0, 65536, (L, h_kv, d)).astype(np.uint16)
+    idx = np.stack([np.sort(rng.choice(L, B, replace=False)) for _ in range(h_kv)]).astype(np.int32)
+    Ko, Vo = oracle.compact(K, V, idx)
+    for g in range(h_kv):
+        np.testing.assert_array_equal(Ko[:, g], np.take(K[:, g], idx[g], axis=0))
+        np.testing.assert_array_equal(Vo[:, g], np.take(V[:, g], idx[g], axis=0))
+
+
+def test_compact_full_budget_is_identity():
+    rng = np.random.default_rng(5)
+    K = rng.integers(0, 65536, (9, 2, 4)).astype(np.uint16)
+    V = rng.integers(0, 65536, (9, 2, 4)).astype(np.uint16)
+    idx = np.tile(np.arange(9, dtype=np.int32), (2, 1))
+    Ko, Vo = oracle.compact(K, V, idx)
+    np.testing.assert_array_equal(Ko, K)
+    np.testing.assert_array_equal(Vo, V)
+
+
+def test_compact_rejects_out_of_range_index():
+    K = np.zeros((4, 1, 2), dtype=np.uint16)
+    with pytest.raises(ValueError):
+        oracle.compact(K, K, np.array([[0, 4]], dtype=np.int32))
+
+
+# ---------------------------------------------------------------- composition / hit rate
+def test_evict_batch_equals_single_problems():
+    from workloads import make_workload
+    w = make_workload(1, seq_lens=[96, 40], budget=[16, 5], n_layers=2, plant="none")
+    Q, K, V = w.assemble()
+    out = oracle.evict_batch(Q, K, V, w.cu_seqlens, w.budgets, w.pool_k)
+    cu, cb = w.cu_seqlens, w.cu_budgets
+    for l in range(2):
+        for s in range(2):
+            one = oracle.evict(Q[l, s], K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], w.budgets[s], w.pool_k)
+            np.testing.assert_array_equal(out["idx"][l, :, cb[s]:cb[s + 1]], one["idx"])
+            np.testing.assert_array_equal(out["K_out"][l, cb[s]:cb[s + 1]], one["K_out"])
+            np.testing.assert_array_equal(out["pooled"][l, :, cu[s]:cu[s + 1]], one["pooled"])
+    # ragged pooling must not bleed: first pooled value of sequence 1 only sees its own 4 taps
+    np.testing.assert_allclose(out["pooled"][0, :, cu[1]], out["scores"][0, :, cu[1]:cu[1] + 4].sum(axis=1) / 7, rtol=1e-14)
+
+
+def test_hit_rate():
+    assert oracle.hit_rate([1, 2, 3, 4], [1, 2, 3, 4]) == 1.0
+    assert oracle.hit_rate([1, 2, 9, 8], [1, 2, 3, 4]) == 0.5
+    assert oracle.hit_rate([7], [1, 2]) == 0.0

@@ -1,0 +1,162 @@
+"""Pins for the oracle's importance scores (Eq. 3 / Section 4.3 of the paper).
+
+The paper prints no worked numeric example for this path, so the oracle is tied
+to closed forms, invariants of the softmax, constructions whose answer is known
+in advance, and independent brute force.  Each test is chosen so that one kind
+of plausible slip (dropped scale, wrong sign, transposed operand, wrong GQA
+mapping, missing max-subtraction, mean instead of sum) makes it fail.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from workloads import bf16_bits_to_f64, f32_to_bf16_bits
+
+
+def bits(x):
+    return f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def rand_bits(rng, shape, scale=1.0):
+    return bits(rng.standard_normal(shape).astype(np.float32) * scale)
+
+
+def test_hand_worked_three_keys(golden_dir):
+    want = np.loadtxt(os.path.join(golden_dir, "softmax_three_keys.txt"))
+    q = bits([[[2, 0, 0, 0]]])                                   # n_q=1, h_q=1, d=4  -> scale 1/2
+    k = bits([[[1, 0, 0, 0]], [[0, 1, 0, 0]], [[-1, 0, 0, 0]]])  # L=3, h_kv=1
+    got = oracle.score(q, k)
+    assert got.shape == (1, 3)
+    np.testing.assert_allclose(got[0], want, rtol=0, atol=1e-15)
+
+
+def test_explicit_scale_overrides_default():
+    # same logits (1,0,-1) reached with scale=1 and q=(1,0,0,0)
+    q = bits([[[1, 0, 0, 0]]])
+    k = bits([[[1, 0, 0, 0]], [[0, 1, 0, 0]], [[-1, 0, 0, 0]]])
+    s = math.e + 1 + 1 / math.e
+    np.testing.assert_allclose(oracle.score(q, k, scale=1.0)[0], [math.e / s, 1 / s, 1 / (math.e * s)], atol=1e-15)
+
+
+@pytest.mark.parametrize("n_q,h_q,h_kv,d,L", [(3, 4, 2, 8, 37), (16, 8, 2, 128, 300), (5, 6, 6, 16, 64)])
+def test_rows_sum_to_one(n_q, h_q, h_kv, d, L):
+    rng = np.random.default_rng(1)
+    Q, K = rand_bits(rng, (n_q, h_q, d)), rand_bits(rng, (L, h_kv, d))
+    s = oracle.score(Q, K)
+    G = h_q // h_kv
+    np.testing.assert_allclose(s.sum(axis=1), n_q * G, rtol=1e-12)
+    assert (s >= 0).all() and (s <= n_q * G).all()
+
+
+def test_single_key_gets_everything():
+    rng = np.random.default_rng(2)
+    Q, K = rand_bits(rng, (4, 4, 8)), rand_bits(rng, (1, 2, 8))
+    np.testing.assert_array_equal(oracle.score(Q, K), np.full((2, 1), 8.0))
+
+
+def test_zero_queries_and_equal_keys_are_uniform():
+    rng = np.random.default_rng(3)
+    K = rand_bits(rng, (50, 2, 16))
+    Q0 = np.zeros((3, 4, 16), dtype=np.uint16)
+    np.testing.assert_allclose(oracle.score(Q0, K), 3 * 2 / 50, rtol=1e-14)
+    Q = rand_bits(rng, (3, 4, 16))
+    Keq = np.broadcast_to(rand_bits(rng, (1, 2, 16)), (50, 2, 16)).copy()
+    np.testing.assert_allclose(oracle.score(Q, Keq), 3 * 2 / 50, rtol=1e-13)
+
+
+def test_key_shift_invariance_with_large_shift():
+    # adding one vector to every key changes each query's logits by a constant;
+    # with a big shift this only survives if the maximum is subtracted before exp
+    rng = np.random.default_rng(4)
+    n_q, h_q, h_kv, d, L = 4, 2, 1, 8, 40
+    Qf = rng.integers(-3, 4, (n_q, h_q, d)).astype(np.float32)
+    Kf = rng.integers(-3, 4, (L, h_kv, d)).astype(np.float32)
+    shift = np.full((1, 1, d), 96.0, dtype=np.float32)          # logits move by up to ~ +-800
+    a = oracle.score(bits(Qf), bits(Kf))
+    b = oracle.score(bits(Qf), bits(Kf + shift))                  # small ints + 96 are exact in bf16
+    assert np.isfinite(b).all()
+    np.testing.assert_allclose(a, b, rtol=1e-10)
+
+
+def test_permutation_and_duplication_laws():
+    rng = np.random.default_rng(5)
+    n_q, h_q, h_kv, d, L = 5, 4, 2, 16, 33
+    Q, K = rand_bits(rng, (n_q, h_q, d)), rand_bits(rng, (L, h_kv, d))
+    base = oracle.score(Q, K)
+    perm = rng.permutation(L)
+    np.testing.assert_allclose(oracle.score(Q, K[perm]), base[:, perm], rtol=1e-12)
+    np.testing.assert_allclose(oracle.score(Q[rng.permutation(n_q)], K), base, rtol=1e-12)
+    Qs = Q.copy(); Qs[:, [0, 1]] = Q[:, [1, 0]]                  # swap two heads of KV group 0
+    np.testing.assert_allclose(oracle.score(Qs, K), base, rtol=1e-12)
+    np.testing.assert_allclose(oracle.score(np.concatenate([Q, Q]), K), 2 * base, rtol=1e-12)
+
+
+def test_gqa_mapping_is_contiguous_groups():
+    # h_q=4, h_kv=2: query heads {0,1} read KV head 0, {2,3} read KV head 1.
+    # Only query head 1 is non-zero and KV head 0 has one aligned key; under an
+    # interleaved mapping (h % h_kv) head 1 would read KV head 1 instead.
+    d, L = 4, 6
+    Q = np.zeros((1, 4, d), dtype=np.float32); Q[0, 1] = [4, 0, 0, 0]      # logit = 4*k0/2
+    K = np.zeros((L, 2, d), dtype=np.float32)
+    K[2, 0] = [1, 0, 0, 0]          # KV head 0: key 2 gets logit 2, others 0
+    K[4, 1] = [1, 0, 0, 0]          # KV head 1: would light up key 4 if mapping were wrong
+    s = oracle.score(bits(Q), bits(K))
+    e2 = math.exp(2.0)
+    want0 = np.full(L, 1.0 / L) + np.where(np.arange(L) == 2, e2, 1.0) / (e2 + L - 1)
+    np.testing.assert_allclose(s[0], want0, rtol=1e-14)
+    np.testing.assert_allclose(s[1], np.full(L, 2.0 / L), rtol=1e-14)
+
+
+def test_operands_not_transposed():
+    # distinct sizes everywhere and a key that matches exactly one query row
+    d, L = 8, 5
+    Q = np.zeros((2, 1, d), dtype=np.float32); Q[0, 0, 3] = 4.0; Q[1, 0, 5] = 4.0
+    K = np.zeros((L, 1, d), dtype=np.float32); K[1, 0, 3] = 2.0; K[3, 0, 5] = -2.0
+    sc = 1.0 / math.sqrt(d)
+    a, b = math.exp(8 * sc), math.exp(-8 * sc)
+    want = np.array([1.0, a, 1.0, 1.0, 1.0]) / (a + 4) + np.array([1.0, 1.0, 1.0, b, 1.0]) / (b + 4)
+    np.testing.assert_allclose(oracle.score(bits(Q), bits(K))[0], want, rtol=1e-14)
+
+
+def test_brute_force_without_max_subtraction():
+    # independent naive loops (math.exp on raw logits, no stabilisation)
+    rng = np.random.default_rng(6)
+    n_q, h_q, h_kv, d, L = 3, 4, 2, 8, 11
+    Q, K = rand_bits(rng, (n_q, h_q, d), 0.7), rand_bits(rng, (L, h_kv, d), 0.7)
+    Qd, Kd = bf16_bits_to_f64(Q), bf16_bits_to_f64(K)
+    G = h_q // h_kv
+    want = [[0.0] * L for _ in range(h_kv)]
+    for h in range(h_q):
+        for i in range(n_q):
+            e = []
+            for j in range(L):
+                dot = 0.0
+                for c in range(d):
+                    dot += Qd[i, h, c] * Kd[j, h // G, c]
+                e.append(math.exp(dot / math.sqrt(d)))
+            z = sum(e)
+            for j in range(L):
+                want[h // G][j] += e[j] / z
+    np.testing.assert_allclose(oracle.score(Q, K), np.array(want), rtol=1e-12)
+
+
+def test_matches_numpy_softmax_on_a_medium_case():
+    rng = np.random.default_rng(7)
+    n_q, h_q, h_kv, d, L = 16, 8, 2, 128, 517
+    Q, K = rand_bits(rng, (n_q, h_q, d)), rand_bits(rng, (L, h_kv, d))
+    Qd, Kd = bf16_bits_to_f64(Q), bf16_bits_to_f64(K)
+    G = h_q // h_kv
+    logits = np.einsum("ihc,jhc->hij", Qd, np.repeat(Kd, G, axis=1)) / math.sqrt(d)
+    p = np.exp(logits - logits.max(axis=2, keepdims=True))
+    p /= p.sum(axis=2, keepdims=True)
+    want = p.sum(axis=1).reshape(h_kv, G, L).sum(axis=1)
+    np.testing.assert_allclose(oracle.score(Q, K), want, rtol=1e-11)
+
+
+def test_rejects_bad_shapes():
+    Q = np.zeros((1, 3, 4), dtype=np.uint16); K = np.zeros((2, 2, 4), dtype=np.uint16)
+    with pytest.raises(ValueError):
+        oracle.score(Q, K)                                       # 3 % 2 != 0
