@@ -1,0 +1,130 @@
+/*
+ * jq.h -- C ABI of the Judge Q KV-cache eviction hot path for AMD MI355X (gfx950).
+ *
+ * At the end of prefill the method (paper Section 4.3, "Optimizing KV Cache
+ * Eviction via Soft Tokens during Inference") scores every prompt key by the
+ * attention it receives from the appended soft-token queries (Eq. 3), keeps the
+ * key-value pairs with the top-k scores and decodes on the pruned cache.  This
+ * library is that path, per layer and per KV head, as HIP kernels:
+ *
+ *   jq_score        attention map of the soft tokens over the prompt (Eq. 3)
+ *   jq_pool         1-D average pooling of the map ("pooling configurations",
+ *                   Section 5.1, Baselines)
+ *   jq_select_topk  top-B retention per KV head (Section 4.3)
+ *   jq_compact      gather of the kept K/V rows into a dense pruned cache
+ *   jq_evict        all of the above for n_layers x n_seq problems in one call
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ * - Pointers named Q, K, V, scores, pooled, idx, K_out, V_out, ws are DEVICE
+ *   pointers on the current HIP device.  `shape`, `shape->cu_seqlens`,
+ *   `shape->budgets` and `bytes` are HOST pointers, read before the call
+ *   returns (they may be freed afterwards).
+ * - bf16 tensors are raw 16-bit patterns.  All tensors are dense, row-major:
+ *     Q       [n_layers, n_seq, n_q, h_q, d]   bf16  soft-token queries
+ *     K, V    [n_layers, T, h_kv, d]           bf16  prompt keys / values,
+ *                                                     T = cu_seqlens[n_seq]
+ *     scores  [n_layers, h_kv, T]              fp32  (unpooled or pooled)
+ *     idx     [n_layers, h_kv, TB]             int32 kept positions, local to
+ *                                                     their sequence, ascending
+ *                                                     inside each (layer, head,
+ *                                                     sequence) segment;
+ *                                                     TB = sum of budgets
+ *     K_out,  [n_layers, TB, h_kv, d]          bf16  pruned cache; sequence s
+ *     V_out                                           owns rows cu_budgets[s]..
+ * - Query head h reads KV head h / (h_q / h_kv).  The softmax runs over the L_s
+ *   prompt keys of the query's own sequence only; probabilities are summed (not
+ *   averaged) over the n_q soft tokens and the h_q/h_kv heads of the group, so
+ *   the unpooled scores of a (layer, sequence, KV head) sum to n_q * h_q / h_kv.
+ * - The caller owns every buffer.  The library allocates nothing, keeps no
+ *   state between calls, never synchronises the stream and may be called from
+ *   several host threads at once.  `stream` is a hipStream_t passed as void*
+ *   (NULL = the default stream).  Work is only enqueued; results are ready when
+ *   the stream reaches the end of the enqueued work.
+ * - Every entry point returns a jq_status.  All argument errors are detected
+ *   on the host before anything is launched; nothing is written in that case.
+ *   After JQ_ERR_LAUNCH the contents of the outputs are unspecified.
+ * - NaN or infinite inputs are not checked; results are then unspecified.
+ */
+#ifndef JQ_H_
+#define JQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum jq_status {
+    JQ_OK = 0,
+    JQ_ERR_NULL = -1,        /* a required pointer is NULL                               */
+    JQ_ERR_SHAPE = -2,       /* a dimension, pool_k, scale or cu_seqlens is malformed    */
+    JQ_ERR_BUDGET = -3,      /* some budget is outside 1..L_s                            */
+    JQ_ERR_UNSUPPORTED = -4, /* valid but not implemented (d != 128, too many sequences) */
+    JQ_ERR_WORKSPACE = -5,   /* workspace missing, misaligned (16 B) or too small        */
+    JQ_ERR_ALIAS = -6,       /* an output overlaps an input or another output            */
+    JQ_ERR_LAUNCH = -7       /* the HIP runtime refused a launch                         */
+} jq_status;
+
+#define JQ_MAX_SEQ 128 /* most sequences one call may carry */
+
+/* Problem description (host memory).  One call handles n_layers * n_seq
+ * independent (layer, sequence) problems that share every other dimension. */
+typedef struct jq_shape {
+    int32_t n_layers;          /* >= 1                                                        */
+    int32_t n_seq;             /* 1..JQ_MAX_SEQ                                               */
+    int32_t n_q;               /* soft tokens per sequence (the paper's n; 32 in its runs)    */
+    int32_t h_q;               /* query heads                                                 */
+    int32_t h_kv;              /* KV heads; h_q % h_kv == 0                                   */
+    int32_t d;                 /* head dimension; only 128 is implemented                     */
+    int32_t pool_k;            /* odd >= 1; 1 = no pooling                                    */
+    float scale;               /* logit scale; 0 selects 1/sqrt(d); must be finite and >= 0   */
+    const int32_t* cu_seqlens; /* HOST [n_seq+1]; cu[0] = 0, strictly increasing              */
+    const int32_t* budgets;    /* HOST [n_seq]; 1 <= budgets[s] <= L_s.  May be NULL for      */
+                               /* jq_score and jq_pool, which do not use it.                  */
+} jq_shape;
+
+/* Bytes of device workspace that jq_score, jq_select_topk and jq_evict need for
+ * this shape (the largest of the three; 256-byte granular).  `budgets` must be set. */
+int jq_workspace_bytes(const jq_shape* shape, size_t* bytes);
+
+/* Unpooled importance scores (Eq. 3 without the 1/n):
+ *   scores[l,g,t] = sum_{h in group g} sum_i softmax_j(scale * Q[l,s,i,h,:].K[l,j,g,:])[t]
+ * for every token t of every sequence s.  Two passes over K (softmax statistics,
+ * then normalised probabilities).  Uses `ws` as scratch. */
+int jq_score(const jq_shape* shape, const void* Q, const void* K, float* scores,
+             void* ws, size_t ws_bytes, void* stream);
+
+/* pooled[l,g,t] = (1/pool_k) * sum_{|u| <= (pool_k-1)/2} scores[l,g,t+u], taking
+ * zero for positions outside t's own sequence (divisor is always pool_k).
+ * `pooled` must not overlap `scores`. */
+int jq_pool(const jq_shape* shape, const float* scores, float* pooled, void* stream);
+
+/* For every (layer, sequence, KV head): the budgets[s] positions with the largest
+ * pooled value; equal values are resolved towards the lower position; positions
+ * are written in ascending order.  Exact for any finite fp32 input (-0 == +0).
+ * Uses `ws` as scratch. */
+int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* K_out[l, cu_budgets[s]+b, g, :] = K[l, cu_seqlens[s] + idx[l,g,cu_budgets[s]+b], g, :]
+ * and the same for V, as 16-bit patterns.  An index outside 0..L_s-1 is clamped
+ * into that range (never dereferenced out of bounds). */
+int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_t* idx,
+               void* K_out, void* V_out, void* stream);
+
+/* score -> pool -> select -> compact in one call.  `idx_out` (kept positions) and
+ * `scores_out` (POOLED scores) may each be NULL when the caller does not want
+ * them; the workspace then holds them. */
+int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V,
+             void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
+             void* ws, size_t ws_bytes, void* stream);
+
+/* Static, never-NULL description of a status code. */
+const char* jq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JQ_H_ */

@@ -1,0 +1,9 @@
+"""Judge Q KV-cache eviction hot path (arXiv 2509.10798, Section 4.3) for AMD MI355X.
+
+The work is done by hand-written HIP kernels in ``libjq.so`` (sources under
+``csrc/``, C ABI in ``include/jq.h``); this package is the thin Python binding.
+"""
+from .binding import (  # noqa: F401
+    EXPORTS, JQError, Shape, alloc_workspace, compact, evict, lib, pool, score, select_topk,
+    status_string, workspace_bytes,
+)

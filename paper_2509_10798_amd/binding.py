@@ -1,0 +1,191 @@
+"""ctypes binding of libjq.so: argument marshalling only.
+
+Every step of the eviction path (paper Section 4.3) runs in the HIP kernels of
+libjq; this module turns torch tensors into device pointers, fills the
+``jq_shape`` struct and raises on a non-zero status.  There is no CPU fallback:
+if the library cannot be loaded the import of a function fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass, field
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libjq.so")
+_lib = None
+
+JQ_MAX_SEQ = 128
+STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
+          -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_status_string")
+
+
+class JQError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s failed: %s (%s)" % (what, STATUS.get(status, status), status_string(status)))
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("n_seq", ctypes.c_int32), ("n_q", ctypes.c_int32),
+                ("h_q", ctypes.c_int32), ("h_kv", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("pool_k", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("cu_seqlens", ctypes.POINTER(ctypes.c_int32)), ("budgets", ctypes.POINTER(ctypes.c_int32))]
+
+
+def lib() -> ctypes.CDLL:
+    """Load libjq.so (building it first only when no built library is present)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import _build
+            _build.build()
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        shp = ctypes.POINTER(_CShape)
+        L.jq_workspace_bytes.argtypes = [shp, ctypes.POINTER(sz)]
+        L.jq_score.argtypes = [shp, vp, vp, vp, vp, sz, vp]
+        L.jq_pool.argtypes = [shp, vp, vp, vp]
+        L.jq_select_topk.argtypes = [shp, vp, vp, vp, sz, vp]
+        L.jq_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+        L.jq_evict.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_status_string.argtypes = [ctypes.c_int]
+        L.jq_status_string.restype = ctypes.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().jq_status_string(int(status)).decode()
+
+
+@dataclass
+class Shape:
+    """Host-side problem description; mirrors ``jq_shape`` in include/jq.h."""
+    n_layers: int
+    seq_lens: Sequence[int]
+    n_q: int
+    h_q: int
+    h_kv: int
+    d: int = 128
+    pool_k: int = 7
+    budgets: Optional[Sequence[int]] = None
+    scale: float = 0.0
+    _keep: list = field(default_factory=list, repr=False)
+
+    @property
+    def n_seq(self) -> int:
+        return len(self.seq_lens)
+
+    @property
+    def T(self) -> int:
+        return int(sum(self.seq_lens))
+
+    @property
+    def TB(self) -> int:
+        return int(sum(self.budgets)) if self.budgets is not None else 0
+
+    def c_struct(self) -> _CShape:
+        cu = np.concatenate([[0], np.cumsum(np.asarray(self.seq_lens, dtype=np.int64))]).astype(np.int32)
+        bud = None if self.budgets is None else np.ascontiguousarray(self.budgets, dtype=np.int32)
+        self._keep = [cu, bud]  # keep the host arrays alive while the struct is in use
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        return _CShape(self.n_layers, self.n_seq, self.n_q, self.h_q, self.h_kv, self.d, self.pool_k,
+                       float(self.scale), cu.ctypes.data_as(i32p),
+                       bud.ctypes.data_as(i32p) if bud is not None else ctypes.cast(None, i32p))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream) or None
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise JQError(rc, what)
+
+
+def workspace_bytes(shape: Shape) -> int:
+    n = ctypes.c_size_t(0)
+    cs = shape.c_struct()
+    _check(lib().jq_workspace_bytes(ctypes.byref(cs), ctypes.byref(n)), "jq_workspace_bytes")
+    return int(n.value)
+
+
+def alloc_workspace(shape: Shape, device="cuda"):
+    import torch
+    return torch.empty(workspace_bytes(shape), dtype=torch.uint8, device=device)
+
+
+def score(shape: Shape, Q, K, scores=None, ws=None, stream=None):
+    import torch
+    if scores is None:
+        scores = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=K.device)
+    if ws is None:
+        ws = alloc_workspace(shape, K.device)
+    cs = shape.c_struct()
+    _check(lib().jq_score(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(scores), _ptr(ws), ws.numel(), _stream(stream)), "jq_score")
+    return scores
+
+
+def pool(shape: Shape, scores, pooled=None, stream=None):
+    import torch
+    if pooled is None:
+        pooled = torch.empty_like(scores)
+    cs = shape.c_struct()
+    _check(lib().jq_pool(ctypes.byref(cs), _ptr(scores), _ptr(pooled), _stream(stream)), "jq_pool")
+    return pooled
+
+
+def select_topk(shape: Shape, pooled, idx=None, ws=None, stream=None):
+    import torch
+    if idx is None:
+        idx = torch.empty((shape.n_layers, shape.h_kv, shape.TB), dtype=torch.int32, device=pooled.device)
+    if ws is None:
+        ws = alloc_workspace(shape, pooled.device)
+    cs = shape.c_struct()
+    _check(lib().jq_select_topk(ctypes.byref(cs), _ptr(pooled), _ptr(idx), _ptr(ws), ws.numel(), _stream(stream)), "jq_select_topk")
+    return idx
+
+
+def compact(shape: Shape, K, V, idx, K_out=None, V_out=None, stream=None):
+    import torch
+    if K_out is None:
+        K_out = torch.empty((shape.n_layers, shape.TB, shape.h_kv, shape.d), dtype=K.dtype, device=K.device)
+    if V_out is None:
+        V_out = torch.empty_like(K_out)
+    cs = shape.c_struct()
+    _check(lib().jq_compact(ctypes.byref(cs), _ptr(K), _ptr(V), _ptr(idx), _ptr(K_out), _ptr(V_out), _stream(stream)), "jq_compact")
+    return K_out, V_out
+
+
+def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_out=None, ws=None, stream=None,
+          want_idx=True, want_scores=True):
+    """Fused score -> pool -> top-B -> gather.  Returns (K_out, V_out, idx_out, pooled scores)."""
+    import torch
+    dev = K.device
+    if K_out is None:
+        K_out = torch.empty((shape.n_layers, shape.TB, shape.h_kv, shape.d), dtype=K.dtype, device=dev)
+    if V_out is None:
+        V_out = torch.empty_like(K_out)
+    if idx_out is None and want_idx:
+        idx_out = torch.empty((shape.n_layers, shape.h_kv, shape.TB), dtype=torch.int32, device=dev)
+    if scores_out is None and want_scores:
+        scores_out = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = alloc_workspace(shape, dev)
+    cs = shape.c_struct()
+    _check(lib().jq_evict(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(idx_out),
+                          _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict")
+    return K_out, V_out, idx_out, scores_out

@@ -1,0 +1,238 @@
+// C ABI of libjq: argument validation, planning (chunking, workspace layout) and the launch
+// sequences.  Everything here runs on the host; no HIP call is made before validation succeeds.
+#include <cmath>
+#include <cstdlib>
+
+#include "jq_common.h"
+
+namespace jq {
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+// Validates `shape` and derives the plan.  `need_budgets`: the entry point uses budgets.
+int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
+    if (!sh || !sh->cu_seqlens) return JQ_ERR_NULL;
+    if (need_budgets && !sh->budgets) return JQ_ERR_NULL;
+    if (sh->n_layers < 1 || sh->n_seq < 1 || sh->n_q < 1 || sh->h_q < 1 || sh->h_kv < 1 || sh->d < 1) return JQ_ERR_SHAPE;
+    if (sh->h_q % sh->h_kv != 0) return JQ_ERR_SHAPE;
+    if (sh->pool_k < 1 || sh->pool_k % 2 == 0) return JQ_ERR_SHAPE;
+    if (!std::isfinite(sh->scale) || sh->scale < 0.0f) return JQ_ERR_SHAPE;
+    if (sh->n_seq > JQ_MAX_SEQ) return JQ_ERR_UNSUPPORTED;
+    if (sh->d != kHeadDim) return JQ_ERR_UNSUPPORTED;
+    if (sh->n_layers > 65535 || sh->h_kv > 65535) return JQ_ERR_UNSUPPORTED;
+    if (sh->cu_seqlens[0] != 0) return JQ_ERR_SHAPE;
+    for (int s = 0; s < sh->n_seq; ++s)
+        if (sh->cu_seqlens[s + 1] <= sh->cu_seqlens[s]) return JQ_ERR_SHAPE;
+
+    Plan p{};
+    p.n_layers = sh->n_layers; p.n_seq = sh->n_seq; p.n_q = sh->n_q; p.h_q = sh->h_q; p.h_kv = sh->h_kv;
+    p.d = sh->d; p.group = sh->h_q / sh->h_kv; p.pool_k = sh->pool_k;
+    p.scale = sh->scale > 0.0f ? sh->scale : (float)(1.0 / std::sqrt((double)sh->d));
+    const int64_t rows = (int64_t)p.n_q * p.group;
+    if (rows > (1 << 20)) return JQ_ERR_UNSUPPORTED;
+    p.rows = (int32_t)rows;
+    p.row_tiles = (p.rows + kRowTile - 1) / kRowTile;
+    p.row_groups = (p.row_tiles + kMaxRowTiles - 1) / kMaxRowTiles;
+    p.T = sh->cu_seqlens[sh->n_seq];
+    p.tab.n_seq = sh->n_seq;
+    int64_t tb = 0;
+    for (int s = 0; s <= sh->n_seq; ++s) p.tab.cu_seq[s] = sh->cu_seqlens[s];
+    p.tab.cu_bud[0] = 0;
+    for (int s = 0; s < sh->n_seq; ++s) {
+        int32_t b = 1;
+        if (sh->budgets) {
+            b = sh->budgets[s];
+            const int32_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
+            if (need_budgets && (b < 1 || b > L)) return JQ_ERR_BUDGET;
+            if (b < 1 || b > L) b = 1;  // entry points that ignore budgets still get a sane table
+        }
+        tb += b;
+        if (tb > INT32_MAX) return JQ_ERR_UNSUPPORTED;
+        p.tab.cu_bud[s + 1] = (int32_t)tb;
+    }
+    p.TB = tb;
+
+    // One wave streams `chunk_keys` keys of one head.  Aim at about one wave per hardware slot
+    // (256 CUs x 8 waves) for small calls and cap the chunk so that big calls run in several rounds.
+    int64_t chunk = ((int64_t)p.n_layers * p.h_kv * p.T + 2047) / 2048;
+    chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
+    if (chunk < 64) chunk = 64;
+    if (chunk > 1024) chunk = 1024;
+    if (const char* env = std::getenv("JQ_CHUNK_KEYS")) {  // ablation knob
+        const long v = std::atol(env);
+        if (v >= kKeyTile && v <= 65536 && v % kKeyTile == 0) chunk = v;
+    }
+    p.chunk_keys = (int32_t)chunk;
+    int64_t nc = 0;
+    p.tab.cu_chunk[0] = 0;
+    for (int s = 0; s < sh->n_seq; ++s) {
+        const int64_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
+        nc += (L + chunk - 1) / chunk;
+        p.tab.cu_chunk[s + 1] = (int32_t)nc;
+    }
+    p.n_chunks = (int32_t)nc;
+    if ((int64_t)p.n_layers * nc * p.h_kv / kScoreWaves >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
+
+    const size_t RP = (size_t)p.row_tiles * kRowTile;
+    size_t off = 0;
+    p.off_stats = off;  off += align_up((size_t)p.n_layers * nc * 2 * p.h_kv * RP * sizeof(float2));
+    p.off_aug = off;    off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * RP * sizeof(uint2));
+    p.off_hist = off;   off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * kHistBins * sizeof(uint32_t));
+    p.off_scores = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));
+    p.off_pooled = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));
+    p.off_idx = off;    off += align_up((size_t)p.n_layers * p.h_kv * p.TB * sizeof(int32_t));
+    p.ws_bytes = off;
+    *out = p;
+    return JQ_OK;
+}
+
+int check_ws(const Plan& p, const void* ws, size_t ws_bytes) {
+    if (!ws) return JQ_ERR_NULL;
+    if (misaligned(ws, 16) || ws_bytes < p.ws_bytes) return JQ_ERR_WORKSPACE;
+    return JQ_OK;
+}
+
+size_t kv_bytes(const Plan& p) { return (size_t)p.n_layers * p.T * p.h_kv * p.d * 2; }
+size_t kv_out_bytes(const Plan& p) { return (size_t)p.n_layers * p.TB * p.h_kv * p.d * 2; }
+size_t q_bytes(const Plan& p) { return (size_t)p.n_layers * p.n_seq * p.n_q * p.h_q * p.d * 2; }
+size_t score_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.T * 4; }
+size_t idx_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.TB * 4; }
+
+inline int launch_status(hipError_t e) { return e == hipSuccess ? JQ_OK : JQ_ERR_LAUNCH; }
+
+}  // namespace
+}  // namespace jq
+
+using namespace jq;
+
+extern "C" {
+
+int jq_workspace_bytes(const jq_shape* shape, size_t* bytes) {
+    if (!bytes) return JQ_ERR_NULL;
+    Plan p;
+    const int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    *bytes = p.ws_bytes;
+    return JQ_OK;
+}
+
+int jq_score(const jq_shape* shape, const void* Q, const void* K, float* scores, void* ws, size_t ws_bytes,
+             void* stream) {
+    Plan p;
+    int rc = make_plan(shape, false, &p);
+    if (rc != JQ_OK) return rc;
+    if (!Q || !K || !scores) return JQ_ERR_NULL;
+    if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(scores, 4)) return JQ_ERR_UNSUPPORTED;
+    if (overlaps(scores, score_bytes(p), K, kv_bytes(p)) || overlaps(scores, score_bytes(p), Q, q_bytes(p)) ||
+        overlaps(scores, score_bytes(p), ws, p.ws_bytes))
+        return JQ_ERR_ALIAS;
+    return launch_status(launch_score(p, Q, K, scores, (char*)ws, (hipStream_t)stream));
+}
+
+int jq_pool(const jq_shape* shape, const float* scores, float* pooled, void* stream) {
+    Plan p;
+    const int rc = make_plan(shape, false, &p);
+    if (rc != JQ_OK) return rc;
+    if (!scores || !pooled) return JQ_ERR_NULL;
+    if (misaligned(scores, 4) || misaligned(pooled, 4)) return JQ_ERR_UNSUPPORTED;
+    if (overlaps(scores, score_bytes(p), pooled, score_bytes(p))) return JQ_ERR_ALIAS;
+    return launch_status(launch_pool(p, scores, pooled, nullptr, (hipStream_t)stream));
+}
+
+int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx, void* ws, size_t ws_bytes,
+                   void* stream) {
+    Plan p;
+    int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if (!pooled || !idx) return JQ_ERR_NULL;
+    if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
+    if (misaligned(pooled, 4) || misaligned(idx, 4)) return JQ_ERR_UNSUPPORTED;
+    if (overlaps(idx, idx_bytes(p), pooled, score_bytes(p)) || overlaps(idx, idx_bytes(p), ws, p.ws_bytes) ||
+        overlaps(pooled, score_bytes(p), ws, p.ws_bytes))
+        return JQ_ERR_ALIAS;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t* hist = (uint32_t*)((char*)ws + p.off_hist);
+    hipError_t e = launch_fill_u32(hist, (size_t)p.n_layers * p.n_seq * p.h_kv * kHistBins, 0u, st);
+    if (e == hipSuccess) e = launch_hist(p, pooled, hist, st);
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, idx, st);
+    return launch_status(e);
+}
+
+int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
+               void* stream) {
+    Plan p;
+    const int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if (!K || !V || !idx || !K_out || !V_out) return JQ_ERR_NULL;
+    if (misaligned(K, 16) || misaligned(V, 16) || misaligned(K_out, 16) || misaligned(V_out, 16) || misaligned(idx, 4))
+        return JQ_ERR_UNSUPPORTED;
+    const size_t nin = kv_bytes(p), nout = kv_out_bytes(p);
+    if (overlaps(K_out, nout, K, nin) || overlaps(K_out, nout, V, nin) || overlaps(V_out, nout, K, nin) ||
+        overlaps(V_out, nout, V, nin) || overlaps(K_out, nout, V_out, nout) || overlaps(K_out, nout, idx, idx_bytes(p)) ||
+        overlaps(V_out, nout, idx, idx_bytes(p)))
+        return JQ_ERR_ALIAS;
+    return launch_status(launch_compact(p, K, V, idx, K_out, V_out, (hipStream_t)stream));
+}
+
+int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
+             int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+    Plan p;
+    int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if (!Q || !K || !V || !K_out || !V_out) return JQ_ERR_NULL;
+    if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(K_out, 16) || misaligned(V_out, 16) ||
+        (idx_out && misaligned(idx_out, 4)) || (scores_out && misaligned(scores_out, 4)))
+        return JQ_ERR_UNSUPPORTED;
+    const size_t nin = kv_bytes(p), nout = kv_out_bytes(p);
+    const void* ins[3] = {Q, K, V};
+    const size_t in_bytes[3] = {q_bytes(p), nin, nin};
+    const void* outs[5] = {K_out, V_out, idx_out, scores_out, ws};
+    const size_t out_bytes[5] = {nout, nout, idx_bytes(p), score_bytes(p), p.ws_bytes};
+    for (int o = 0; o < 5; ++o) {
+        if (!outs[o]) continue;
+        for (int i = 0; i < 3; ++i)
+            if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return JQ_ERR_ALIAS;
+        for (int o2 = o + 1; o2 < 5; ++o2)
+            if (outs[o2] && overlaps(outs[o], out_bytes[o], outs[o2], out_bytes[o2])) return JQ_ERR_ALIAS;
+    }
+
+    hipStream_t st = (hipStream_t)stream;
+    char* w = (char*)ws;
+    uint32_t* hist = (uint32_t*)(w + p.off_hist);
+    float* raw = (float*)(w + p.off_scores);
+    float* pooled = scores_out ? scores_out : (float*)(w + p.off_pooled);
+    int32_t* idx = idx_out ? idx_out : (int32_t*)(w + p.off_idx);
+    hipError_t e = launch_fill_u32(hist, (size_t)p.n_layers * p.n_seq * p.h_kv * kHistBins, 0u, st);
+    if (e == hipSuccess) e = launch_score(p, Q, K, raw, w, st);
+    if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, st);
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, idx, st);
+    if (e == hipSuccess) e = launch_compact(p, K, V, idx, K_out, V_out, st);
+    return launch_status(e);
+}
+
+const char* jq_status_string(int status) {
+    switch (status) {
+        case JQ_OK: return "ok";
+        case JQ_ERR_NULL: return "a required pointer is NULL";
+        case JQ_ERR_SHAPE: return "malformed shape (dimension, pool_k, scale or cu_seqlens)";
+        case JQ_ERR_BUDGET: return "a budget is outside 1..L";
+        case JQ_ERR_UNSUPPORTED: return "valid but unsupported (d != 128, too many sequences, or misaligned tensor)";
+        case JQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case JQ_ERR_ALIAS: return "an output overlaps an input or another output";
+        case JQ_ERR_LAUNCH: return "the HIP runtime refused a launch";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

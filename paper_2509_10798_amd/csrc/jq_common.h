@@ -1,0 +1,68 @@
+// Internal declarations shared by the HIP sources of libjq (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "jq.h"
+
+namespace jq {
+
+constexpr int kKeyTile = 32;        // keys per MFMA tile (one 32x32 block column)
+constexpr int kRowTile = 32;        // query rows per MFMA tile
+constexpr int kMaxRowTiles = 4;     // query-row tiles one wave keeps in registers (128 rows)
+constexpr int kHeadDim = 128;
+constexpr int kScoreWaves = 4;      // waves per workgroup in the score kernels
+constexpr int kHistBins = 2048;     // level-1 radix bins (top 11 bits of the sortable key)
+constexpr int kSelectThreads = 1024;
+
+// Per-call sequence table, passed to kernels by value (about 1.5 KiB of kernarg).
+struct SeqTab {
+    int32_t n_seq;
+    int32_t cu_seq[JQ_MAX_SEQ + 1];    // token offsets
+    int32_t cu_bud[JQ_MAX_SEQ + 1];    // kept-row offsets
+    int32_t cu_chunk[JQ_MAX_SEQ + 1];  // score-chunk offsets (chunk = `chunk_keys` keys of one sequence)
+};
+
+// Everything the host derives from a jq_shape.
+struct Plan {
+    int32_t n_layers, n_seq, n_q, h_q, h_kv, d, group, pool_k;
+    int32_t rows;         // n_q * group: query rows that share one KV head
+    int32_t row_tiles;    // ceil(rows / 32)
+    int32_t row_groups;   // ceil(row_tiles / 4): passes of the score kernels over K
+    int32_t chunk_keys;   // keys one wave streams (multiple of 32)
+    int32_t n_chunks;     // chunks per layer, over all sequences
+    float scale;          // logit scale actually used
+    int64_t T, TB;
+    SeqTab tab;
+    // workspace layout (byte offsets, 256-aligned)
+    size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, ws_bytes;
+};
+
+// Largest s with cu[s] <= v (cu[0] = 0, strictly increasing, v < cu[n]).
+__host__ __device__ inline int find_seq(const int32_t* cu, int n, int64_t v) {
+    int lo = 0, hi = n;  // answer in [lo, hi)
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if ((int64_t)cu[mid] <= v) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Order-preserving map from fp32 to uint32 (larger float <=> larger key); -0 is folded onto +0.
+__device__ inline uint32_t sortable_key(float x) {
+    uint32_t b = __float_as_uint(x + 0.0f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Stage launchers (enqueue only).  Each returns a hipError_t from the launch.
+hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st);
+hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st);
+hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st);
+hipError_t launch_select(const Plan& p, const float* pooled, const uint32_t* hist, int32_t* idx, hipStream_t st);
+hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
+                          hipStream_t st);
+
+}  // namespace jq

@@ -1,0 +1,57 @@
+// Pruned KV cache (paper Section 4.3: decoding continues on the pruned cache): gather the kept
+// rows of K and V into dense [TB, h_kv, d] tensors.  Pure copy, 16 bytes per lane, 16 lanes per
+// 256-byte head row; consecutive lanes/waves write consecutive output bytes.
+#include "jq_common.h"
+
+namespace jq {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct CompactArgs {
+    const char* K; const char* V;
+    char* K_out; char* V_out;
+    const int32_t* idx;  // [n_layers][h_kv][TB], sequence-local
+    int32_t n_layers, h_kv;
+    int64_t T, TB;
+    SeqTab tab;
+};
+
+constexpr int kCompactThreads = 256;
+constexpr int kLanesPerRow = kHeadDim * 2 / 16;  // 16
+
+__global__ __launch_bounds__(kCompactThreads) void jq_compact_kernel(CompactArgs a) {
+    // item = (layer, kept row tb, head g), g fastest: the output is written front to back
+    const int64_t n_items = (int64_t)a.n_layers * a.TB * a.h_kv;
+    const int64_t item = ((int64_t)blockIdx.x * kCompactThreads + threadIdx.x) / kLanesPerRow;
+    if (item >= n_items) return;
+    const int part = threadIdx.x % kLanesPerRow;
+    const int g = (int)(item % a.h_kv);
+    const int64_t rest = item / a.h_kv;
+    const int64_t tb = rest % a.TB;
+    const int layer = (int)(rest / a.TB);
+    const int s = find_seq(a.tab.cu_bud, a.tab.n_seq, tb);
+    const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
+    int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
+    j = min(max(j, 0), L - 1);  // never read outside the sequence
+    const int64_t src = ((((int64_t)layer * a.T + a.tab.cu_seq[s] + j) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
+    const int64_t dst = item * (kHeadDim * 2) + part * 16;
+    const u32x4 kv = *(const u32x4*)(a.K + src);
+    const u32x4 vv = *(const u32x4*)(a.V + src);
+    *(u32x4*)(a.K_out + dst) = kv;
+    *(u32x4*)(a.V_out + dst) = vv;
+}
+
+hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
+                          hipStream_t st) {
+    CompactArgs a;
+    a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
+    a.idx = idx;
+    a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
+    a.tab = p.tab;
+    const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
+    hipLaunchKernelGGL(jq_compact_kernel, dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads)),
+                       dim3(kCompactThreads), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace jq

@@ -1,0 +1,114 @@
+// 1-D average pooling of the importance scores (the "pooling configurations" the paper's
+// Section 5.1 shares with its baselines), fused with the first radix histogram that the top-B
+// selection needs, plus two small helpers (fill, standalone histogram).
+//
+//   pooled[l,g,t] = (1/k) * sum_{|u| <= (k-1)/2} scores[l,g,t+u],  zero outside t's own sequence.
+//
+// Memory-bound and tiny next to the K passes: one thread per position, taps re-read through L1/L2.
+#include "jq_common.h"
+
+namespace jq {
+
+constexpr int kPoolThreads = 256;
+constexpr int kPoolPerThread = 4;
+constexpr int kPoolBlockPos = kPoolThreads * kPoolPerThread;
+
+struct PoolArgs {
+    const float* in;   // [n_layers][h_kv][T]
+    float* out;        // same shape (may be null for the histogram-only kernel)
+    uint32_t* hist;    // [n_layers][n_seq][h_kv][kHistBins] or null
+    int32_t n_layers, h_kv, pool_k;
+    float inv_k;
+    int64_t T;
+    SeqTab tab;
+};
+
+// Block-level histogram: LDS bins when the whole block lies in one sequence, global atomics otherwise.
+template <bool POOL>
+__global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
+    __shared__ uint32_t bins[kHistBins];
+    const int g = blockIdx.y, layer = blockIdx.z;
+    const int64_t row = ((int64_t)layer * a.h_kv + g) * a.T;
+    const float* in = a.in + row;
+    const int64_t p0 = (int64_t)blockIdx.x * kPoolBlockPos;
+    const int64_t p1 = min(a.T, p0 + kPoolBlockPos);
+    const int s_first = find_seq(a.tab.cu_seq, a.tab.n_seq, p0);
+    const int s_last = find_seq(a.tab.cu_seq, a.tab.n_seq, p1 - 1);
+    const bool one_seq = (s_first == s_last);  // uniform over the block
+    const bool do_hist = a.hist != nullptr;
+    if (do_hist && one_seq) {
+        for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) bins[b] = 0;
+        __syncthreads();
+    }
+    const int r = (a.pool_k - 1) / 2;
+#pragma unroll
+    for (int e = 0; e < kPoolPerThread; ++e) {
+        const int64_t p = p0 + e * kPoolThreads + threadIdx.x;
+        if (p >= p1) continue;
+        const int s = one_seq ? s_first : find_seq(a.tab.cu_seq, a.tab.n_seq, p);
+        float v;
+        if (POOL) {
+            const int64_t lo = max((int64_t)a.tab.cu_seq[s], p - r);
+            const int64_t hi = min((int64_t)a.tab.cu_seq[s + 1] - 1, p + r);
+            float acc = 0.f;
+            for (int64_t q = lo; q <= hi; ++q) acc += in[q];
+            v = acc * a.inv_k;
+            a.out[row + p] = v;
+        } else {
+            v = in[p];
+        }
+        if (do_hist) {
+            const uint32_t bin = sortable_key(v) >> 21;
+            if (one_seq) atomicAdd(&bins[bin], 1u);
+            else atomicAdd(a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistBins + bin, 1u);
+        }
+    }
+    if (do_hist && one_seq) {
+        __syncthreads();
+        uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s_first) * a.h_kv + g) * kHistBins;
+        for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) {
+            const uint32_t c = bins[b];
+            if (c) atomicAdd(gh + b, c);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void jq_fill_u32_kernel(uint32_t* dst, size_t n, uint32_t v) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = v;
+}
+
+static PoolArgs make_args(const Plan& p, const float* in, float* out, uint32_t* hist) {
+    PoolArgs a;
+    a.in = in; a.out = out; a.hist = hist;
+    a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.pool_k = p.pool_k;
+    a.inv_k = 1.0f / (float)p.pool_k;
+    a.T = p.T;
+    a.tab = p.tab;
+    return a;
+}
+
+hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st) {
+    const PoolArgs a = make_args(p, scores, pooled, hist_or_null);
+    dim3 grid((unsigned)((p.T + kPoolBlockPos - 1) / kPoolBlockPos), p.h_kv, p.n_layers);
+    hipLaunchKernelGGL(jq_pool_kernel<true>, grid, dim3(kPoolThreads), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st) {
+    const PoolArgs a = make_args(p, pooled, nullptr, hist);
+    dim3 grid((unsigned)((p.T + kPoolBlockPos - 1) / kPoolBlockPos), p.h_kv, p.n_layers);
+    hipLaunchKernelGGL(jq_pool_kernel<false>, grid, dim3(kPoolThreads), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    const size_t want = (n + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 1024 ? want : 1024);
+    hipLaunchKernelGGL(jq_fill_u32_kernel, dim3(blocks), dim3(256), 0, st, dst, n, v);
+    return hipGetLastError();
+}
+
+}  // namespace jq

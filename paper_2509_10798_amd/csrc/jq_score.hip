@@ -1,0 +1,440 @@
+// Importance scores of the prompt keys under the soft-token queries
+// (paper Section 4.3, Eq. 3), as two K-streaming MFMA passes for gfx950.
+//
+//   pass 1 (stats):  per query row r, the running maximum m_r and Z_r = sum_j 2^(t_rj - m_r) of its
+//                    base-2 logits t_rj = c * q_r.k_j, c = scale * log2(e); one partial per
+//                    (chunk of keys, lane half).
+//   combine:         beta_r = m_r + log2 Z_r over a sequence's partials, stored as -beta_r / c split
+//                    into three bf16 terms.
+//   pass 2 (score):  score_j = sum_r 2^(c * (q_r.k_j - beta_r / c)).  The -beta_r/c term enters
+//                    through one extra MFMA step whose key-side operand is 1.0, so the epilogue is one
+//                    multiply, one exp2 and one add per logit.
+//
+// One wave owns one (layer, sequence, chunk of keys, KV head) and keeps that head's (up to) 128
+// query rows in registers as MFMA operands.  Key tiles of 32 keys x 128 channels are fetched
+// asynchronously, straight from global memory into a private, XOR-swizzled 8 KiB LDS slot (buffer
+// loads with the LDS modifier, 16 B per lane, 16 lanes per 256-byte key row, so every 128-byte
+// line is requested whole), double buffered, and read back in MFMA operand order without bank
+// conflicts.  Waves never share LDS, so no workgroup barrier is needed; the only synchronisation is
+// the wave's own s_waitcnt on its outstanding loads.
+//
+// MFMA 32x32x16 bf16 operand layout used here: lane l supplies row/column (l & 31) and the 8
+// contraction elements selected by (l >> 5); both operands use the same element order, so any
+// fixed channel permutation cancels.  Result: lane l holds column (l & 31), register v holds row
+// 8*(v/4) + 4*(l>>5) + (v&3).
+#include "jq_common.h"
+
+namespace jq {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct ScoreArgs {
+    const uint16_t* Q;
+    const uint16_t* K;
+    float2* stats;    // [n_layers][n_chunks][2 halves][h_kv][RP]
+    uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
+    float* scores;    // [n_layers][h_kv][T]
+    int32_t n_layers, n_seq, n_q, h_q, h_kv, group, rows, RP, chunk_keys, n_chunks;
+    int32_t row_tile0;   // first query-row tile of this launch
+    int32_t accumulate;  // pass 2: add to `scores` instead of overwriting
+    float c;             // scale * log2(e)
+    int64_t T;
+    SeqTab tab;
+};
+
+constexpr int kSlotBytes = kKeyTile * kHeadDim * 2;  // 8 KiB
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// s_waitcnt vmcnt(0) only (expcnt and lgkmcnt fields left at "no wait"), then keep the compiler
+// from moving LDS reads above it: the loads-to-LDS are invisible to its own dependency tracking.
+__device__ __forceinline__ void wait_tile_landed() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+}
+
+// Which (layer, sequence, key range, head) this wave owns.
+struct WaveItem {
+    int layer, seq, g, chunk_global;
+    int k_begin, k_end;  // sequence-local key range
+    int64_t tok0;        // first token of the sequence in the flattened T axis
+};
+
+__device__ __forceinline__ bool wave_item(const ScoreArgs& a, bool reverse, WaveItem& w) {
+    const int64_t total = (int64_t)a.n_layers * a.n_chunks * a.h_kv;
+    // readfirstlane makes the wave index (and everything derived from it) a scalar for the compiler
+    int64_t wid = (int64_t)blockIdx.x * kScoreWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (wid >= total) return false;
+    if (reverse) wid = total - 1 - wid;
+    w.g = (int)(wid % a.h_kv);
+    int64_t rest = wid / a.h_kv;
+    w.chunk_global = (int)(rest % a.n_chunks);
+    w.layer = (int)(rest / a.n_chunks);
+    w.seq = find_seq(a.tab.cu_chunk, a.tab.n_seq, w.chunk_global);
+    const int L = a.tab.cu_seq[w.seq + 1] - a.tab.cu_seq[w.seq];
+    w.k_begin = (w.chunk_global - a.tab.cu_chunk[w.seq]) * a.chunk_keys;
+    w.k_end = min(L, w.k_begin + a.chunk_keys);
+    w.tok0 = a.tab.cu_seq[w.seq];
+    return true;
+}
+
+// Query rows of the wave's KV head as MFMA operands (row r = i * group + hh  <->  Q[i, g*group + hh]).
+template <int NQT>
+__device__ __forceinline__ void load_q(const ScoreArgs& a, const WaveItem& w, int lane, bf16x8 (&qf)[NQT][8]) {
+    const int half = lane >> 5;
+    const char* qbase = (const char*)a.Q + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q) * a.h_q * kHeadDim * 2;
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
+        const bool valid = row < a.rows;
+        const int i = valid ? row / a.group : 0;
+        const int hh = valid ? row % a.group : 0;
+        const char* qp = qbase + ((int64_t)i * a.h_q + (w.g * a.group + hh)) * kHeadDim * 2 + half * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            u32x4 v = *(const u32x4*)(qp + ks * 32);  // row 0 of the head when !valid: in bounds, then zeroed
+            if (!valid) v = u32x4{0u, 0u, 0u, 0u};
+            qf[qt][ks] = as_bf16x8(v);
+        }
+    }
+}
+
+// ---- key tiles: global -> LDS -------------------------------------------------------------------
+// A tile is 32 key rows of 256 B.  Load i (0..7) of a wave moves rows 4i..4i+3: lane l fetches 16 B
+// of row r = 4i + (l >> 4), and the hardware stores them at slot + 1024 i + 16 l, i.e. at row r,
+// physical 16-byte chunk (l & 15).  To realise the swizzle "logical chunk c lives at physical chunk
+// c ^ (r & 15)" the lane therefore fetches logical chunk (l & 15) ^ (r & 15) from global memory.
+// With (r & 15) = 4 (i & 3) + (l >> 4) the lane's byte offset takes four values over the 8 loads;
+// the rest of the address is wave-uniform (buffer resource + scalar offset).
+struct TileLanes {
+    uint32_t voff[4];  // (l >> 4) * row_bytes + 16 * (((l & 15) ^ (l >> 4)) ^ 4 j),  j = i & 3
+};
+
+__device__ __forceinline__ TileLanes tile_lanes(int lane, uint32_t row_bytes) {
+    TileLanes tl;
+    const uint32_t a = lane >> 4, x = (lane & 15) ^ a;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tl.voff[j] = a * row_bytes + ((x ^ (4u * j)) << 4);
+    return tl;
+}
+
+__device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t rsrc, char* dst, uint32_t voff, uint32_t soff) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)dst, 16, (int)voff,
+                                             (int)soff, 0, 0);
+}
+
+// `tile_off` = byte offset of the tile's first key row inside the wave's chunk (uniform).
+__device__ __forceinline__ void fetch_tile(__amdgpu_buffer_rsrc_t rsrc, char* slot, uint32_t tile_off,
+                                           uint32_t row_bytes, int valid, const TileLanes& tl, int lane) {
+    if (valid >= kKeyTile) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lds_dma16(rsrc, slot + 1024 * i, tl.voff[i & 3], tile_off + 4 * i * row_bytes);
+    } else {  // last, partial tile of a sequence: rows past the end re-read the last valid key (masked later)
+        asm volatile("" : "+v"(lane));  // keep this rarely taken path's address arithmetic out of the caller's loop
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + (lane >> 4);
+            const uint32_t voff = (uint32_t)min(r, valid - 1) * row_bytes + (((lane & 15) ^ (r & 15)) << 4);
+            lds_dma16(rsrc, slot + 1024 * i, voff, tile_off);
+        }
+    }
+}
+
+// MFMA operand fragments of the tile in `slot`: lane l takes key row (l & 31), logical chunks
+// 2 ks + (l >> 5), ks = 0..7.  The 16 lanes of a quarter wave hit 16 distinct physical chunks.
+__device__ __forceinline__ void lds_get_frags(const char* slot, bf16x8 (&kf)[8], int lane) {
+    const int r = lane & 31;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const int chunk = 2 * ks + (lane >> 5);
+        kf[ks] = as_bf16x8(*(const u32x4*)(slot + r * 256 + ((chunk ^ (r & 15)) << 4)));
+    }
+}
+
+struct KeyStream {
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t row_bytes;
+    int n_keys, n_tiles;
+};
+
+__device__ __forceinline__ KeyStream key_stream(const ScoreArgs& a, const WaveItem& w) {
+    KeyStream ks;
+    ks.row_bytes = (uint32_t)a.h_kv * kHeadDim * 2;
+    ks.n_keys = w.k_end - w.k_begin;
+    ks.n_tiles = (ks.n_keys + kKeyTile - 1) / kKeyTile;
+    const char* kchunk =
+        (const char*)a.K + (((int64_t)w.layer * a.T + w.tok0 + w.k_begin) * a.h_kv + w.g) * kHeadDim * 2;
+    // the resource covers exactly this head's rows of the chunk; every generated offset stays inside it
+    const uint32_t bytes = (uint32_t)(ks.n_keys - 1) * ks.row_bytes + kHeadDim * 2;
+    ks.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kchunk, 0, (int)bytes, 0x00020000);
+    return ks;
+}
+
+// ------------------------------------------------------------------------------------------------
+// pass 1: softmax statistics
+// ------------------------------------------------------------------------------------------------
+// One 32-key tile against the wave's query rows: rows of the MFMA result are keys, columns are
+// query rows, so each lane updates the running (m, Z) of its own query column from its 16 keys.
+// MASKED is only used for the last, partial tile of a sequence (keys >= valid do not exist).
+template <int NQT, bool MASKED>
+__device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (&qf)[NQT][8], float (&m)[NQT],
+                                           float (&z)[NQT], float c, int valid, int half) {
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k8 = 0; k8 < 8; ++k8) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k8], qf[qt][k8], acc, 0, 0, 0);
+        if (MASKED) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (8 * (v >> 2) + 4 * half + (v & 3) >= valid) acc[v] = -INFINITY;
+        }
+        float tmax = fmaxf(acc[0], acc[1]);
+#pragma unroll
+        for (int v = 2; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
+        const float mnew = fmaxf(m[qt], tmax * c);
+        float s0 = __builtin_amdgcn_exp2f(fmaf(acc[0], c, -mnew));
+        float s1 = __builtin_amdgcn_exp2f(fmaf(acc[1], c, -mnew));
+        float s2 = __builtin_amdgcn_exp2f(fmaf(acc[2], c, -mnew));
+        float s3 = __builtin_amdgcn_exp2f(fmaf(acc[3], c, -mnew));
+#pragma unroll
+        for (int v = 4; v < 16; v += 4) {
+            s0 += __builtin_amdgcn_exp2f(fmaf(acc[v + 0], c, -mnew));
+            s1 += __builtin_amdgcn_exp2f(fmaf(acc[v + 1], c, -mnew));
+            s2 += __builtin_amdgcn_exp2f(fmaf(acc[v + 2], c, -mnew));
+            s3 += __builtin_amdgcn_exp2f(fmaf(acc[v + 3], c, -mnew));
+        }
+        z[qt] = z[qt] * __builtin_amdgcn_exp2f(m[qt] - mnew) + ((s0 + s1) + (s2 + s3));
+        m[qt] = mnew;
+        __builtin_amdgcn_sched_barrier(0);  // one live accumulator tile at a time (register budget)
+    }
+}
+
+template <int NQT>
+__global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs a) {
+    __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
+    WaveItem w;
+    if (!wave_item(a, false, w)) return;
+    const int lane = threadIdx.x & 63;
+    const int half = lane >> 5;
+    char* slots = &lds[__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))][0][0];
+
+    const KeyStream ks = key_stream(a, w);
+    const TileLanes tl = tile_lanes(lane, ks.row_bytes);
+    fetch_tile(ks.rsrc, slots, 0u, ks.row_bytes, ks.n_keys, tl, lane);
+
+    bf16x8 qf[NQT][8];
+    load_q<NQT>(a, w, lane, qf);
+    const float c = a.c;
+
+    float m[NQT], z[NQT];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
+
+    const int n_full = ks.n_keys / kKeyTile;
+    for (int t = 0; t < n_full; ++t) {
+        wait_tile_landed();
+        bf16x8 kf[8];
+        lds_get_frags(slots + (t & 1) * kSlotBytes, kf, lane);
+        // the other slot was last read one iteration ago; refill it while this tile is computed
+        if (t + 1 < ks.n_tiles)
+            fetch_tile(ks.rsrc, slots + ((t + 1) & 1) * kSlotBytes, (uint32_t)(t + 1) * kKeyTile * ks.row_bytes,
+                       ks.row_bytes, ks.n_keys - (t + 1) * kKeyTile, tl, lane);
+        stats_tile<NQT, false>(kf, qf, m, z, c, kKeyTile, half);
+    }
+    if (n_full < ks.n_tiles) {  // partial last tile
+        wait_tile_landed();
+        bf16x8 kf[8];
+        lds_get_frags(slots + (n_full & 1) * kSlotBytes, kf, lane);
+        stats_tile<NQT, true>(kf, qf, m, z, c, ks.n_keys - n_full * kKeyTile, half);
+    }
+
+    float2* out = a.stats + ((((int64_t)w.layer * a.n_chunks + w.chunk_global) * 2 + half) * a.h_kv + w.g) * a.RP +
+                  a.row_tile0 * kRowTile + (lane & 31);
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) out[qt * kRowTile] = make_float2(m[qt], z[qt]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// combine: per (layer, sequence, head, row) merge the partials into -beta/c as three bf16 terms
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void jq_combine_kernel(ScoreArgs a) {
+    const int64_t n = (int64_t)a.n_layers * a.n_seq * a.h_kv * a.RP;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid >= n) return;
+    const int r = (int)(tid % a.RP);
+    int64_t rest = tid / a.RP;
+    const int g = (int)(rest % a.h_kv);
+    rest /= a.h_kv;
+    const int s = (int)(rest % a.n_seq);
+    const int layer = (int)(rest / a.n_seq);
+
+    float x = -1.0e30f;  // padded rows: 2^(c*x) = 0
+    if (r < a.rows) {
+        const int c0 = a.tab.cu_chunk[s], c1 = a.tab.cu_chunk[s + 1];
+        const float2* p = a.stats + (((int64_t)layer * a.n_chunks + c0) * 2 * a.h_kv + g) * a.RP + r;
+        const int64_t step = (int64_t)a.h_kv * a.RP;
+        const int n_part = (c1 - c0) * 2;
+        float M = -1.0e30f;
+        for (int k = 0; k < n_part; ++k) M = fmaxf(M, p[k * step].x);
+        float Z = 0.f;
+        for (int k = 0; k < n_part; ++k) {
+            const float2 mz = p[k * step];
+            Z += mz.y * __builtin_amdgcn_exp2f(mz.x - M);
+        }
+        x = -(M + __log2f(Z)) / a.c;
+    }
+    const uint32_t hi = __float_as_uint(x) & 0xFFFF0000u;
+    const float r1 = x - __uint_as_float(hi);
+    const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
+    const float r2 = r1 - __uint_as_float(mid);
+    const uint32_t lo = __float_as_uint(r2) & 0xFFFF0000u;
+    a.aug[tid] = make_uint2((hi >> 16) | mid, lo >> 16);
+}
+
+// ------------------------------------------------------------------------------------------------
+// pass 2: normalised probabilities summed over the query rows
+// ------------------------------------------------------------------------------------------------
+template <int NQT>
+__global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs a) {
+    __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
+    WaveItem w;
+    if (!wave_item(a, true, w)) return;  // reversed order: the keys pass 1 read last are fetched first
+    const int lane = threadIdx.x & 63;
+    const int half = lane >> 5;
+    char* slots = &lds[__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))][0][0];
+
+    const KeyStream ks = key_stream(a, w);
+    const TileLanes tl = tile_lanes(lane, ks.row_bytes);
+    fetch_tile(ks.rsrc, slots, 0u, ks.row_bytes, ks.n_keys, tl, lane);
+
+    bf16x8 qf[NQT][8];
+    load_q<NQT>(a, w, lane, qf);
+    bf16x8 qaug[NQT];
+    {
+        const uint2* ap = a.aug + ((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP +
+                          a.row_tile0 * kRowTile + (lane & 31);
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            const uint2 t = ap[qt * kRowTile];
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (half == 0) { v[0] = t.x; v[1] = t.y; }
+            qaug[qt] = as_bf16x8(v);
+        }
+    }
+    u32x4 ones_bits = {0u, 0u, 0u, 0u};
+    if (half == 0) { ones_bits[0] = 0x3F803F80u; ones_bits[1] = 0x00003F80u; }  // 1.0 at elements 0..2
+    const bf16x8 ones = as_bf16x8(ones_bits);
+
+    float* out = a.scores + ((int64_t)w.layer * a.h_kv + w.g) * a.T + w.tok0 + w.k_begin;
+    const float c = a.c;
+    float pending = 0.f;  // previous tile's result, stored one iteration late so that the store has a
+                          // whole tile of compute to retire before the next wait on outstanding loads
+
+    for (int t = 0; t < ks.n_tiles; ++t) {
+        const int valid = ks.n_keys - t * kKeyTile;
+        wait_tile_landed();
+        bf16x8 kf[8];
+        lds_get_frags(slots + (t & 1) * kSlotBytes, kf, lane);
+        if (t + 1 < ks.n_tiles)
+            fetch_tile(ks.rsrc, slots + ((t + 1) & 1) * kSlotBytes, (uint32_t)(t + 1) * kKeyTile * ks.row_bytes,
+                       ks.row_bytes, valid - kKeyTile, tl, lane);
+        if (t > 0 && lane < 32) {  // tile t-1 was full (only the last tile can be partial)
+            float* o = out + (t - 1) * kKeyTile + lane;
+            *o = a.accumulate ? *o + pending : pending;
+        }
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k8 = 0; k8 < 8; ++k8)  // rows = query rows, columns = keys
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[qt][k8], kf[k8], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qaug[qt], ones, acc, 0, 0, 0);  // - beta_r / c
+#pragma unroll
+            for (int v = 0; v < 16; v += 4) {
+                s0 += __builtin_amdgcn_exp2f(acc[v + 0] * c);
+                s1 += __builtin_amdgcn_exp2f(acc[v + 1] * c);
+                s2 += __builtin_amdgcn_exp2f(acc[v + 2] * c);
+                s3 += __builtin_amdgcn_exp2f(acc[v + 3] * c);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // one live accumulator tile at a time (register budget)
+        }
+        float s = (s0 + s1) + (s2 + s3);
+        s += __shfl_xor(s, 32);  // the two lane halves hold complementary query rows of the same key
+        pending = s;
+    }
+    {
+        const int t = ks.n_tiles - 1;
+        const int valid = ks.n_keys - t * kKeyTile;
+        if (lane < 32 && lane < valid) {
+            float* o = out + t * kKeyTile + lane;
+            *o = a.accumulate ? *o + pending : pending;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+static hipError_t launch_stats_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st) {
+    dim3 block(kScoreWaves * 64);
+    switch (nqt) {
+        case 1: hipLaunchKernelGGL(jq_stats_kernel<1>, grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL(jq_stats_kernel<2>, grid, block, 0, st, a); break;
+        case 3: hipLaunchKernelGGL(jq_stats_kernel<3>, grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL(jq_stats_kernel<4>, grid, block, 0, st, a); break;
+    }
+    return hipGetLastError();
+}
+
+static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st) {
+    dim3 block(kScoreWaves * 64);
+    switch (nqt) {
+        case 1: hipLaunchKernelGGL(jq_score_kernel<1>, grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL(jq_score_kernel<2>, grid, block, 0, st, a); break;
+        case 3: hipLaunchKernelGGL(jq_score_kernel<3>, grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL(jq_score_kernel<4>, grid, block, 0, st, a); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st) {
+    ScoreArgs a;
+    a.Q = (const uint16_t*)Q;
+    a.K = (const uint16_t*)K;
+    a.stats = (float2*)(ws + p.off_stats);
+    a.aug = (uint2*)(ws + p.off_aug);
+    a.scores = scores;
+    a.n_layers = p.n_layers; a.n_seq = p.n_seq; a.n_q = p.n_q; a.h_q = p.h_q; a.h_kv = p.h_kv;
+    a.group = p.group; a.rows = p.rows; a.RP = p.row_tiles * kRowTile;
+    a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
+    a.row_tile0 = 0; a.accumulate = 0;
+    a.c = p.scale * 1.4426950408889634f;
+    a.T = p.T;
+    a.tab = p.tab;
+
+    const int64_t waves = (int64_t)p.n_layers * p.n_chunks * p.h_kv;
+    dim3 grid((unsigned)((waves + kScoreWaves - 1) / kScoreWaves));
+    hipError_t e;
+    for (int rg = 0; rg < p.row_groups; ++rg) {
+        a.row_tile0 = rg * kMaxRowTiles;
+        const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
+        if ((e = launch_stats_n(nqt, a, grid, st)) != hipSuccess) return e;
+    }
+    const int64_t n_rows = (int64_t)p.n_layers * p.n_seq * p.h_kv * a.RP;
+    hipLaunchKernelGGL(jq_combine_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    for (int rg = 0; rg < p.row_groups; ++rg) {
+        a.row_tile0 = rg * kMaxRowTiles;
+        a.accumulate = rg > 0;
+        const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
+        if ((e = launch_score_n(nqt, a, grid, st)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace jq

@@ -1,0 +1,95 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+malformed arguments on the host before touching a GPU (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2509_10798_amd as jq
+from paper_2509_10798_amd.binding import _CShape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_header_symbols_are_exported():
+    header = open(os.path.join(ROOT, "include", "jq.h")).read()
+    declared = set(re.findall(r"\b(jq_[a-z_]+)\s*\(", header))
+    assert declared == set(jq.EXPORTS)
+    L = jq.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings():
+    for code in range(0, -8, -1):
+        assert jq.status_string(code) and jq.status_string(code) != "unknown status"
+    assert jq.status_string(5) == "unknown status"
+
+
+def shape(**kw):
+    base = dict(n_layers=1, seq_lens=[64], n_q=4, h_q=4, h_kv=2, d=128, pool_k=7, budgets=[8])
+    base.update(kw)
+    return jq.Shape(**base)
+
+
+def ws_status(sh):
+    try:
+        jq.workspace_bytes(sh)
+        return 0
+    except jq.JQError as e:
+        return e.status
+
+
+def test_workspace_size_grows_with_problem():
+    a = jq.workspace_bytes(shape())
+    b = jq.workspace_bytes(shape(seq_lens=[4096], budgets=[8]))
+    assert 0 < a < b and a % 256 == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(h_q=3), -2), (dict(pool_k=4), -2), (dict(pool_k=0), -2), (dict(n_q=0), -2), (dict(n_layers=0), -2),
+    (dict(scale=-1.0), -2), (dict(scale=float("nan")), -2),
+    (dict(d=64), -4), (dict(seq_lens=[8] * 129, budgets=[1] * 129), -4),
+    (dict(budgets=[0]), -3), (dict(budgets=[65]), -3),
+    (dict(seq_lens=[64, 0], budgets=[8, 1]), -2),
+])
+def test_shape_errors(kw, code):
+    assert ws_status(shape(**kw)) == code
+
+
+def test_null_and_alias_errors_come_before_any_launch():
+    L = jq.lib()
+    sh = shape()
+    cs = sh.c_struct()
+    n = ctypes.c_size_t()
+    assert L.jq_workspace_bytes(None, ctypes.byref(n)) == -1
+    assert L.jq_workspace_bytes(ctypes.byref(cs), None) == -1
+    assert L.jq_score(ctypes.byref(cs), None, None, None, None, 0, None) == -1
+    assert L.jq_evict(ctypes.byref(cs), None, None, None, None, None, None, None, None, 0, None) == -1
+    # fake, never dereferenced device addresses: validation is pure pointer arithmetic
+    big = 1 << 40
+    Q, K, V, Ko, Vo, ws = big, big + (1 << 30), big + (2 << 30), big + (3 << 30), big + (4 << 30), big + (5 << 30)
+    need = jq.workspace_bytes(sh)
+    assert L.jq_evict(ctypes.byref(cs), Q, K, V, Ko, Vo, None, None, ws, need - 1, None) == -5     # too small
+    assert L.jq_evict(ctypes.byref(cs), Q, K, V, Ko, Vo, None, None, ws + 4, need, None) == -5     # misaligned
+    assert L.jq_evict(ctypes.byref(cs), Q, K, V, K + 256, Vo, None, None, ws, need, None) == -6    # K_out inside K
+    assert L.jq_evict(ctypes.byref(cs), Q, K, V, Ko, Ko, None, None, ws, need, None) == -6         # outputs overlap
+    assert L.jq_evict(ctypes.byref(cs), Q + 2, K, V, Ko, Vo, None, None, ws, need, None) == -4     # misaligned Q
+    assert L.jq_compact(ctypes.byref(cs), K, V, ws, V, Vo, None) == -6
+    assert L.jq_pool(ctypes.byref(cs), K, K, None) == -6
+    cs2 = shape(budgets=None).c_struct()
+    assert L.jq_compact(ctypes.byref(cs2), K, V, ws, Ko, Vo, None) == -1                           # budgets required
+    bad = _CShape(1, 1, 4, 4, 2, 128, 7, 0.0, ctypes.cast(None, ctypes.POINTER(ctypes.c_int32)),
+                  ctypes.cast(None, ctypes.POINTER(ctypes.c_int32)))
+    assert L.jq_pool(ctypes.byref(bad), K, V, None) == -1                                          # cu_seqlens NULL
+
+
+def test_cu_seqlens_must_start_at_zero():
+    L = jq.lib()
+    cu = np.array([1, 65], dtype=np.int32); bud = np.array([8], dtype=np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    cs = _CShape(1, 1, 4, 4, 2, 128, 7, 0.0, cu.ctypes.data_as(i32p), bud.ctypes.data_as(i32p))
+    n = ctypes.c_size_t()
+    assert L.jq_workspace_bytes(ctypes.byref(cs), ctypes.byref(n)) == -2

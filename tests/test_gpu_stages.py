@@ -1,0 +1,194 @@
+"""GPU parity, stage by stage, through the C ABI: each HIP stage against the matching oracle
+stage on identical seeded inputs, at sizes that span several tiles, chunks and ragged tails."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2509_10798_amd as jq
+from parity import assert_kept_set_ok, assert_scores_close, from_dev_bf16, to_dev_bf16
+from workloads import f32_to_bf16_bits, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def torch_():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def run_score_case(n_layers, seq_lens, n_q, h_q, h_kv, seed, scale=0.0, spread=1.0):
+    torch = torch_()
+    rng = np.random.default_rng(seed)
+    T, d = sum(seq_lens), 128
+    Q = f32_to_bf16_bits(rng.standard_normal((n_layers, len(seq_lens), n_q, h_q, d)).astype(np.float32) * spread)
+    K = f32_to_bf16_bits(rng.standard_normal((n_layers, T, h_kv, d)).astype(np.float32) * spread)
+    sh = jq.Shape(n_layers=n_layers, seq_lens=seq_lens, n_q=n_q, h_q=h_q, h_kv=h_kv, scale=scale)
+    got = jq.score(sh, to_dev_bf16(Q), to_dev_bf16(K))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    G = h_q // h_kv
+    worst = 0.0
+    for l in range(n_layers):
+        for s, L in enumerate(seq_lens):
+            ref = oracle.score(Q[l, s], K[l, cu[s]:cu[s + 1]], scale)
+            seg = got[l, :, cu[s]:cu[s + 1]]
+            worst = max(worst, assert_scores_close(seg, ref, n_q * G / L, "layer %d seq %d" % (l, s)))
+            np.testing.assert_allclose(seg.sum(axis=1), n_q * G, rtol=1e-4)
+    return worst
+
+
+@pytest.mark.parametrize("n_layers,seq_lens,n_q,h_q,h_kv", [
+    (1, [2048], 16, 8, 2),            # the tiny named workload's shape: 64 query rows, 2 row tiles
+    (1, [1], 4, 4, 2),                # a single key
+    (1, [31], 4, 4, 2),               # less than one tile
+    (1, [33], 8, 8, 2),               # one full tile and a one-key tail
+    (1, [1000], 32, 32, 8),           # 128 query rows (4 row tiles), ragged tail
+    (2, [517, 64, 3001], 10, 8, 2),   # layers x ragged batch, 40 query rows (padded row tile)
+    (1, [700], 40, 8, 2),             # 160 query rows: two passes over K
+    (1, [300], 3, 6, 6),              # no grouping (G = 1), 3 query rows
+])
+def test_score_matches_oracle(n_layers, seq_lens, n_q, h_q, h_kv):
+    print("score case", n_layers, seq_lens, n_q, h_q, h_kv, flush=True)
+    worst = run_score_case(n_layers, seq_lens, n_q, h_q, h_kv, seed=11)
+    assert worst < 1.0
+
+
+def test_score_with_peaked_softmax_and_custom_scale():
+    # large logits: exercises the running-maximum rescaling and the split of -beta/c
+    print("score peaked", flush=True)
+    run_score_case(1, [1500], 16, 8, 2, seed=12, scale=0.35, spread=1.5)
+
+
+def test_score_several_chunks_per_sequence(monkeypatch):
+    # force 64-key chunks so that one sequence is split over many waves and partial statistics merge
+    print("score chunked", flush=True)
+    monkeypatch.setenv("JQ_CHUNK_KEYS", "64")
+    run_score_case(1, [1111, 95], 16, 8, 2, seed=13)
+
+
+def test_score_is_deterministic():
+    torch = torch_()
+    w = make_workload(1)
+    Q, K, _ = w.assemble()
+    sh = jq.Shape(n_layers=1, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv)
+    Qd, Kd = to_dev_bf16(Q), to_dev_bf16(K)
+    a = jq.score(sh, Qd, Kd).clone()
+    b = jq.score(sh, Qd, Kd)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("seq_lens,k", [([1], 7), ([5], 7), ([4096], 7), ([100, 3, 2000], 7), ([777], 1), ([777], 5), ([50], 31)])
+def test_pool_matches_oracle(seq_lens, k):
+    torch = torch_()
+    rng = np.random.default_rng(21)
+    T, h_kv, nl = sum(seq_lens), 3, 2
+    x = rng.random((nl, h_kv, T)).astype(np.float32) * np.float32(3.0)
+    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, pool_k=k)
+    got = jq.pool(sh, torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    for s in range(len(seq_lens)):
+        ref = oracle.pool(x[:, :, cu[s]:cu[s + 1]].astype(np.float64), k)
+        np.testing.assert_allclose(got[:, :, cu[s]:cu[s + 1]], ref, rtol=2e-6, atol=0)
+
+
+def run_select_case(x, seq_lens, budgets):
+    torch = torch_()
+    nl, h_kv, T = x.shape
+    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, budgets=budgets)
+    idx = jq.select_topk(sh, torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    idx = idx.cpu().numpy()
+    cu = np.concatenate([[0], np.cumsum(seq_lens)]); cb = np.concatenate([[0], np.cumsum(budgets)])
+    for s in range(len(seq_lens)):
+        ref = oracle.select_topk(x[:, :, cu[s]:cu[s + 1]].astype(np.float64), budgets[s])
+        np.testing.assert_array_equal(idx[:, :, cb[s]:cb[s + 1]], ref)
+
+
+@pytest.mark.parametrize("seq_lens,budgets", [([1], [1]), ([7], [7]), ([100], [1]), ([5000], [256]),
+                                               ([4097, 33, 9000], [512, 33, 1]), ([70000], [2048])])
+def test_select_is_exact_on_random_scores(seq_lens, budgets):
+    rng = np.random.default_rng(31)
+    x = rng.random((2, 3, sum(seq_lens))).astype(np.float32)
+    run_select_case(x, seq_lens, budgets)
+
+
+def test_select_with_heavy_ties_and_special_values():
+    rng = np.random.default_rng(32)
+    x = np.round(rng.random((1, 4, 6000)).astype(np.float32), 2)       # ~100 distinct values
+    x[0, 1] = 0.5                                                      # all equal -> first B positions
+    x[0, 2, ::3] = 0.0; x[0, 2, 1::7] = -0.0                           # signed zeros compare equal
+    x[0, 3] = -x[0, 3]                                                 # negative scores are legal input
+    run_select_case(x, [6000], [1000])
+    run_select_case(x, [2500, 3500], [2500, 17])                       # B = L for the first sequence
+
+
+def test_select_narrow_value_range():
+    # all values inside one level-1 and one level-2 radix bin: only the last 10 bits differ
+    base = np.float32(1.0).view(np.uint32)
+    rng = np.random.default_rng(33)
+    bits = (base + rng.integers(0, 1024, (1, 2, 9000)).astype(np.uint32)).astype(np.uint32)
+    run_select_case(bits.view(np.float32), [9000], [700])
+
+
+def test_compact_is_bit_exact():
+    torch = torch_()
+    rng = np.random.default_rng(41)
+    nl, seq_lens, budgets, h_kv, d = 2, [300, 41], [64, 41], 4, 128
+    T, TB = sum(seq_lens), sum(budgets)
+    K = rng.integers(0, 65536, (nl, T, h_kv, d)).astype(np.uint16)
+    V = rng.integers(0, 65536, (nl, T, h_kv, d)).astype(np.uint16)
+    idx = np.empty((nl, h_kv, TB), dtype=np.int32)
+    cu = np.concatenate([[0], np.cumsum(seq_lens)]); cb = np.concatenate([[0], np.cumsum(budgets)])
+    for l in range(nl):
+        for g in range(h_kv):
+            for s in range(2):
+                idx[l, g, cb[s]:cb[s + 1]] = np.sort(rng.choice(seq_lens[s], budgets[s], replace=False))
+    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, budgets=budgets)
+    Ko, Vo = jq.compact(sh, to_dev_bf16(K), to_dev_bf16(V), torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    Ko, Vo = from_dev_bf16(Ko), from_dev_bf16(Vo)
+    for l in range(nl):
+        for s in range(2):
+            rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], idx[l, :, cb[s]:cb[s + 1]])
+            np.testing.assert_array_equal(Ko[l, cb[s]:cb[s + 1]], rk)
+            np.testing.assert_array_equal(Vo[l, cb[s]:cb[s + 1]], rv)
+
+
+def test_evict_equals_stage_composition_and_oracle():
+    torch = torch_()
+    w = make_workload(1, seq_lens=[1500, 700], budget=[200, 64], n_layers=2)
+    Q, K, V = w.assemble()
+    sh = jq.Shape(n_layers=2, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    Qd, Kd, Vd = to_dev_bf16(Q), to_dev_bf16(K), to_dev_bf16(V)
+    Ko, Vo, idx, pooled = jq.evict(sh, Qd, Kd, Vd)
+    s1 = jq.score(sh, Qd, Kd)
+    p1 = jq.pool(sh, s1)
+    i1 = jq.select_topk(sh, p1)
+    Ko1, Vo1 = jq.compact(sh, Kd, Vd, i1)
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, p1) and torch.equal(idx, i1) and torch.equal(Ko.view(torch.int16), Ko1.view(torch.int16))
+    assert torch.equal(Vo.view(torch.int16), Vo1.view(torch.int16))
+    # outputs may also be left in the workspace
+    Ko2, Vo2, none_idx, none_sc = jq.evict(sh, Qd, Kd, Vd, want_idx=False, want_scores=False)
+    torch.cuda.synchronize()
+    assert none_idx is None and none_sc is None and torch.equal(Ko2.view(torch.int16), Ko.view(torch.int16))
+
+    ref = oracle.evict_batch(Q, K, V, w.cu_seqlens, w.budgets, w.pool_k)
+    pooled_h, idx_h = pooled.cpu().numpy(), idx.cpu().numpy()
+    Ko_h, Vo_h = from_dev_bf16(Ko), from_dev_bf16(Vo)
+    cu, cb = w.cu_seqlens, w.cu_budgets
+    for l in range(2):
+        for s in range(2):
+            L = w.seq_lens[s]
+            assert_scores_close(pooled_h[l, :, cu[s]:cu[s + 1]], ref["pooled"][l, :, cu[s]:cu[s + 1]], w.n_q * w.group / L)
+            for g in range(w.h_kv):
+                assert_kept_set_ok(ref["pooled"][l, g, cu[s]:cu[s + 1]], ref["idx"][l, g, cb[s]:cb[s + 1]],
+                                   idx_h[l, g, cb[s]:cb[s + 1]], "l%d s%d g%d" % (l, s, g))
+            rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], idx_h[l, :, cb[s]:cb[s + 1]])
+            np.testing.assert_array_equal(Ko_h[l, cb[s]:cb[s + 1]], rk)
+            np.testing.assert_array_equal(Vo_h[l, cb[s]:cb[s + 1]], rv)
