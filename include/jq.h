@@ -86,7 +86,8 @@ typedef struct jq_shape {
 } jq_shape;
 
 /* Bytes of device workspace that jq_score, jq_select_topk and jq_evict need for
- * this shape (the largest of the three; 256-byte granular).  `budgets` must be set. */
+ * this shape (one size serves all three; 256-byte granular).  With `budgets` NULL
+ * the size only serves jq_score. */
 int jq_workspace_bytes(const jq_shape* shape, size_t* bytes);
 
 /* Unpooled importance scores (Eq. 3 without the 1/n):

@@ -41,6 +41,9 @@ def lib() -> ctypes.CDLL:
     """Load libjq.so (building it first only when no built library is present)."""
     global _lib
     if _lib is None:
+        # PyTorch provides device memory and streams, and ships its own HIP runtime: it must be in the
+        # process before libjq so that both resolve to that one runtime (same SONAME) instead of two.
+        import torch  # noqa: F401
         if not os.path.exists(_LIB_PATH):
             from . import _build
             _build.build()

@@ -1,6 +1,7 @@
 // C ABI of libjq: argument validation, planning (chunking, workspace layout) and the launch
 // sequences.  Everything here runs on the host; no HIP call is made before validation succeeds.
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 
 #include "jq_common.h"
@@ -107,7 +108,11 @@ size_t q_bytes(const Plan& p) { return (size_t)p.n_layers * p.n_seq * p.n_q * p.
 size_t score_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.T * 4; }
 size_t idx_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.TB * 4; }
 
-inline int launch_status(hipError_t e) { return e == hipSuccess ? JQ_OK : JQ_ERR_LAUNCH; }
+inline int launch_status(hipError_t e) {
+    if (e == hipSuccess) return JQ_OK;
+    if (std::getenv("JQ_LOG")) std::fprintf(stderr, "libjq: launch failed: %s\n", hipGetErrorString(e));
+    return JQ_ERR_LAUNCH;
+}
 
 }  // namespace
 }  // namespace jq
@@ -119,7 +124,7 @@ extern "C" {
 int jq_workspace_bytes(const jq_shape* shape, size_t* bytes) {
     if (!bytes) return JQ_ERR_NULL;
     Plan p;
-    const int rc = make_plan(shape, true, &p);
+    const int rc = make_plan(shape, shape && shape->budgets, &p);
     if (rc != JQ_OK) return rc;
     *bytes = p.ws_bytes;
     return JQ_OK;

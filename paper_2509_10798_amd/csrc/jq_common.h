@@ -56,6 +56,14 @@ __device__ inline uint32_t sortable_key(float x) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+// Launch through hipLaunchKernel so that the status belongs to this launch alone (the sticky
+// "last error" of the runtime may hold an unrelated, earlier code from the host application).
+template <typename Kernel, typename... Args>
+inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_t st, Args... args) {
+    void* ptrs[] = {(void*)&args...};
+    return hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, st);
+}
+
 // Stage launchers (enqueue only).  Each returns a hipError_t from the launch.
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st);
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st);

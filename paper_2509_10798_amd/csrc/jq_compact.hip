@@ -49,9 +49,8 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
-    hipLaunchKernelGGL(jq_compact_kernel, dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads)),
-                       dim3(kCompactThreads), 0, st, a);
-    return hipGetLastError();
+    return launch_kernel(jq_compact_kernel, dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads)),
+                         dim3(kCompactThreads), st, a);
 }
 
 }  // namespace jq

@@ -92,23 +92,20 @@ static PoolArgs make_args(const Plan& p, const float* in, float* out, uint32_t* 
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st) {
     const PoolArgs a = make_args(p, scores, pooled, hist_or_null);
     dim3 grid((unsigned)((p.T + kPoolBlockPos - 1) / kPoolBlockPos), p.h_kv, p.n_layers);
-    hipLaunchKernelGGL(jq_pool_kernel<true>, grid, dim3(kPoolThreads), 0, st, a);
-    return hipGetLastError();
+    return launch_kernel(jq_pool_kernel<true>, grid, dim3(kPoolThreads), st, a);
 }
 
 hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st) {
     const PoolArgs a = make_args(p, pooled, nullptr, hist);
     dim3 grid((unsigned)((p.T + kPoolBlockPos - 1) / kPoolBlockPos), p.h_kv, p.n_layers);
-    hipLaunchKernelGGL(jq_pool_kernel<false>, grid, dim3(kPoolThreads), 0, st, a);
-    return hipGetLastError();
+    return launch_kernel(jq_pool_kernel<false>, grid, dim3(kPoolThreads), st, a);
 }
 
 hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st) {
     if (n == 0) return hipSuccess;
     const size_t want = (n + 255) / 256;
     const unsigned blocks = (unsigned)(want < 1024 ? want : 1024);
-    hipLaunchKernelGGL(jq_fill_u32_kernel, dim3(blocks), dim3(256), 0, st, dst, n, v);
-    return hipGetLastError();
+    return launch_kernel(jq_fill_u32_kernel, dim3(blocks), dim3(256), st, dst, n, v);
 }
 
 }  // namespace jq

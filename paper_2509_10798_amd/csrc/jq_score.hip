@@ -383,23 +383,21 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
 static hipError_t launch_stats_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st) {
     dim3 block(kScoreWaves * 64);
     switch (nqt) {
-        case 1: hipLaunchKernelGGL(jq_stats_kernel<1>, grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL(jq_stats_kernel<2>, grid, block, 0, st, a); break;
-        case 3: hipLaunchKernelGGL(jq_stats_kernel<3>, grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL(jq_stats_kernel<4>, grid, block, 0, st, a); break;
+        case 1: return launch_kernel(jq_stats_kernel<1>, grid, block, st, a);
+        case 2: return launch_kernel(jq_stats_kernel<2>, grid, block, st, a);
+        case 3: return launch_kernel(jq_stats_kernel<3>, grid, block, st, a);
+        default: return launch_kernel(jq_stats_kernel<4>, grid, block, st, a);
     }
-    return hipGetLastError();
 }
 
 static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st) {
     dim3 block(kScoreWaves * 64);
     switch (nqt) {
-        case 1: hipLaunchKernelGGL(jq_score_kernel<1>, grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL(jq_score_kernel<2>, grid, block, 0, st, a); break;
-        case 3: hipLaunchKernelGGL(jq_score_kernel<3>, grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL(jq_score_kernel<4>, grid, block, 0, st, a); break;
+        case 1: return launch_kernel(jq_score_kernel<1>, grid, block, st, a);
+        case 2: return launch_kernel(jq_score_kernel<2>, grid, block, st, a);
+        case 3: return launch_kernel(jq_score_kernel<3>, grid, block, st, a);
+        default: return launch_kernel(jq_score_kernel<4>, grid, block, st, a);
     }
-    return hipGetLastError();
 }
 
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st) {
@@ -426,8 +424,8 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         if ((e = launch_stats_n(nqt, a, grid, st)) != hipSuccess) return e;
     }
     const int64_t n_rows = (int64_t)p.n_layers * p.n_seq * p.h_kv * a.RP;
-    hipLaunchKernelGGL(jq_combine_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st, a);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    e = launch_kernel(jq_combine_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), st, a);
+    if (e != hipSuccess) return e;
     for (int rg = 0; rg < p.row_groups; ++rg) {
         a.row_tile0 = rg * kMaxRowTiles;
         a.accumulate = rg > 0;

@@ -141,7 +141,10 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_kernel(SelectArgs a)
         for (int e = 0; e < 4; ++e) {
             if (j0 + e >= L) break;
             const bool is_gt = kk[e] > tau, is_eq = kk[e] == tau;
-            if (is_gt || (is_eq && eq_before < need)) out[gt_before + min(eq_before, need)] = j0 + e;
+            if (is_gt || (is_eq && eq_before < need)) {
+                const uint32_t slot = gt_before + min(eq_before, need);
+                if (slot < B) out[slot] = j0 + e;  // always true for consistent histograms; guards NaN-poisoned input
+            }
             gt_before += is_gt;
             eq_before += is_eq;
         }
@@ -157,8 +160,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, const uint32_t* his
     a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.tab = p.tab;
     const unsigned n_prob = (unsigned)((int64_t)p.n_layers * p.n_seq * p.h_kv);
-    hipLaunchKernelGGL(jq_select_kernel, dim3(n_prob), dim3(kSelectThreads), 0, st, a);
-    return hipGetLastError();
+    return launch_kernel(jq_select_kernel, dim3(n_prob), dim3(kSelectThreads), st, a);
 }
 
 }  // namespace jq
