@@ -21,7 +21,10 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_status_string")
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced",
+           "jq_status_string")
+TRACE_MARKS = 7
+TRACE_STAGES = ("stats_pass", "stats_merge", "score_pass", "pool", "select", "compact")
 
 
 class JQError(RuntimeError):
@@ -56,6 +59,7 @@ def lib() -> ctypes.CDLL:
         L.jq_select_topk.argtypes = [shp, vp, vp, vp, sz, vp]
         L.jq_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp]
         L.jq_evict.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_evict_traced.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp), ctypes.c_int]
         L.jq_status_string.argtypes = [ctypes.c_int]
         L.jq_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -174,8 +178,11 @@ def compact(shape: Shape, K, V, idx, K_out=None, V_out=None, stream=None):
 
 
 def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_out=None, ws=None, stream=None,
-          want_idx=True, want_scores=True):
-    """Fused score -> pool -> top-B -> gather.  Returns (K_out, V_out, idx_out, pooled scores)."""
+          want_idx=True, want_scores=True, marks=None):
+    """Fused score -> pool -> top-B -> gather.  Returns (K_out, V_out, idx_out, pooled scores).
+
+    `marks`: optional list of TRACE_MARKS torch.cuda.Event(enable_timing=True) objects that have been
+    recorded once (so that their handles exist); they are re-recorded at the stage boundaries."""
     import torch
     dev = K.device
     if K_out is None:
@@ -189,6 +196,12 @@ def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_ou
     if ws is None:
         ws = alloc_workspace(shape, dev)
     cs = shape.c_struct()
+    if marks is not None:
+        arr = (ctypes.c_void_p * len(marks))(*[int(ev.cuda_event) for ev in marks])
+        _check(lib().jq_evict_traced(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out),
+                                     _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream), arr,
+                                     len(marks)), "jq_evict_traced")
+        return K_out, V_out, idx_out, scores_out
     _check(lib().jq_evict(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(idx_out),
                           _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict")
     return K_out, V_out, idx_out, scores_out

@@ -82,15 +82,18 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     }
     p.n_chunks = (int32_t)nc;
     if ((int64_t)p.n_layers * nc * p.h_kv / kScoreWaves >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
+    if ((int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
 
     const size_t RP = (size_t)p.row_tiles * kRowTile;
     size_t off = 0;
-    p.off_stats = off;  off += align_up((size_t)p.n_layers * nc * 2 * p.h_kv * RP * sizeof(float2));
+    p.off_stats = off;  off += align_up((size_t)p.n_layers * nc * p.h_kv * RP * sizeof(float2));
     p.off_aug = off;    off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * RP * sizeof(uint2));
-    p.off_hist = off;   off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * kHistBins * sizeof(uint32_t));
+    p.off_hist = off;   off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride * sizeof(uint32_t));
     p.off_scores = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));
     p.off_pooled = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));
     p.off_idx = off;    off += align_up((size_t)p.n_layers * p.h_kv * p.TB * sizeof(int32_t));
+    p.off_sure = off;   off += align_up((size_t)p.n_layers * p.h_kv * p.TB * sizeof(int32_t));
+    p.off_cand = off;   off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(uint2));
     p.ws_bytes = off;
     *out = p;
     return JQ_OK;
@@ -167,9 +170,9 @@ int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx, voi
         return JQ_ERR_ALIAS;
     hipStream_t st = (hipStream_t)stream;
     uint32_t* hist = (uint32_t*)((char*)ws + p.off_hist);
-    hipError_t e = launch_fill_u32(hist, (size_t)p.n_layers * p.n_seq * p.h_kv * kHistBins, 0u, st);
+    hipError_t e = launch_fill_u32(hist, (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride, 0u, st);
     if (e == hipSuccess) e = launch_hist(p, pooled, hist, st);
-    if (e == hipSuccess) e = launch_select(p, pooled, hist, idx, st);
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, (char*)ws, idx, st);
     return launch_status(e);
 }
 
@@ -189,8 +192,9 @@ int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_
     return launch_status(launch_compact(p, K, V, idx, K_out, V_out, (hipStream_t)stream));
 }
 
-int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
-             int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
+                      int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream,
+                      void* const* marks) {
     Plan p;
     int rc = make_plan(shape, true, &p);
     if (rc != JQ_OK) return rc;
@@ -218,12 +222,32 @@ int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V,
     float* raw = (float*)(w + p.off_scores);
     float* pooled = scores_out ? scores_out : (float*)(w + p.off_pooled);
     int32_t* idx = idx_out ? idx_out : (int32_t*)(w + p.off_idx);
-    hipError_t e = launch_fill_u32(hist, (size_t)p.n_layers * p.n_seq * p.h_kv * kHistBins, 0u, st);
-    if (e == hipSuccess) e = launch_score(p, Q, K, raw, w, st);
+    auto mark = [&](int i) { return marks ? hipEventRecord((hipEvent_t)marks[i], st) : hipSuccess; };
+    hipError_t e = launch_fill_u32(hist, (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride, 0u, st);
+    if (e == hipSuccess) e = mark(0);
+    if (e == hipSuccess) e = launch_score(p, Q, K, raw, w, st, marks ? marks + 1 : nullptr);  // marks 1..3
     if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, st);
-    if (e == hipSuccess) e = launch_select(p, pooled, hist, idx, st);
+    if (e == hipSuccess) e = mark(4);
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, (char*)ws, idx, st);
+    if (e == hipSuccess) e = mark(5);
     if (e == hipSuccess) e = launch_compact(p, K, V, idx, K_out, V_out, st);
+    if (e == hipSuccess) e = mark(6);
     return launch_status(e);
+}
+
+int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
+             int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+    return evict_impl(shape, Q, K, V, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
+}
+
+int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
+                    int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream,
+                    void* const* marks, int n_marks) {
+    if (!marks) return JQ_ERR_NULL;
+    if (n_marks != JQ_TRACE_MARKS) return JQ_ERR_SHAPE;
+    for (int i = 0; i < n_marks; ++i)
+        if (!marks[i]) return JQ_ERR_NULL;
+    return evict_impl(shape, Q, K, V, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, marks);
 }
 
 const char* jq_status_string(int status) {

@@ -15,6 +15,7 @@ constexpr int kMaxRowTiles = 4;     // query-row tiles one wave keeps in registe
 constexpr int kHeadDim = 128;
 constexpr int kScoreWaves = 4;      // waves per workgroup in the score kernels
 constexpr int kHistBins = 2048;     // level-1 radix bins (top 11 bits of the sortable key)
+constexpr int kHistStride = kHistBins + 16;  // per problem: the bins, then [0] #sure and [1] #candidate counters
 constexpr int kSelectThreads = 1024;
 
 // Per-call sequence table, passed to kernels by value (about 1.5 KiB of kernarg).
@@ -37,7 +38,7 @@ struct Plan {
     int64_t T, TB;
     SeqTab tab;
     // workspace layout (byte offsets, 256-aligned)
-    size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, ws_bytes;
+    size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
 };
 
 // Largest s with cu[s] <= v (cu[0] = 0, strictly increasing, v < cu[n]).
@@ -65,11 +66,13 @@ inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_
 }
 
 // Stage launchers (enqueue only).  Each returns a hipError_t from the launch.
-hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st);
+// `marks` (nullable): three events recorded after the statistics pass, the combine step and the score pass.
+hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
+                        void* const* marks = nullptr);
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st);
 hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st);
-hipError_t launch_select(const Plan& p, const float* pooled, const uint32_t* hist, int32_t* idx, hipStream_t st);
+hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st);
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
                           hipStream_t st);
 

@@ -16,12 +16,27 @@ constexpr int kPoolBlockPos = kPoolThreads * kPoolPerThread;
 struct PoolArgs {
     const float* in;   // [n_layers][h_kv][T]
     float* out;        // same shape (may be null for the histogram-only kernel)
-    uint32_t* hist;    // [n_layers][n_seq][h_kv][kHistBins] or null
+    uint32_t* hist;    // [n_layers][n_seq][h_kv][kHistStride] or null
     int32_t n_layers, h_kv, pool_k;
     float inv_k;
     int64_t T;
     SeqTab tab;
 };
+
+// Neighbouring scores mostly share a bin: count each distinct bin of the wave once instead of
+// letting 64 lanes serialise on the same LDS word.  Must be called by all 64 lanes (pass
+// `active` = false for lanes without an element).
+__device__ __forceinline__ void wave_hist_add(uint32_t* bins, uint32_t bin, bool active = true) {
+    const int lane = threadIdx.x & 63;
+    uint64_t todo = __ballot(active);
+    while (todo) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t lb = __shfl(bin, leader);
+        const uint64_t same = __ballot(active && bin == lb);
+        if (lane == leader) atomicAdd(&bins[lb], (uint32_t)__popcll(same));
+        todo &= ~same;
+    }
+}
 
 // Block-level histogram: LDS bins when the whole block lies in one sequence, global atomics otherwise.
 template <bool POOL>
@@ -29,7 +44,7 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
     __shared__ uint32_t bins[kHistBins];
     const int g = blockIdx.y, layer = blockIdx.z;
     const int64_t row = ((int64_t)layer * a.h_kv + g) * a.T;
-    const float* in = a.in + row;
+    const float* in_row = a.in + row;
     const int64_t p0 = (int64_t)blockIdx.x * kPoolBlockPos;
     const int64_t p1 = min(a.T, p0 + kPoolBlockPos);
     const int s_first = find_seq(a.tab.cu_seq, a.tab.n_seq, p0);
@@ -44,28 +59,31 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
 #pragma unroll
     for (int e = 0; e < kPoolPerThread; ++e) {
         const int64_t p = p0 + e * kPoolThreads + threadIdx.x;
-        if (p >= p1) continue;
-        const int s = one_seq ? s_first : find_seq(a.tab.cu_seq, a.tab.n_seq, p);
-        float v;
-        if (POOL) {
-            const int64_t lo = max((int64_t)a.tab.cu_seq[s], p - r);
-            const int64_t hi = min((int64_t)a.tab.cu_seq[s + 1] - 1, p + r);
-            float acc = 0.f;
-            for (int64_t q = lo; q <= hi; ++q) acc += in[q];
-            v = acc * a.inv_k;
-            a.out[row + p] = v;
-        } else {
-            v = in[p];
+        const bool in = p < p1;
+        int s = s_first;
+        float v = 0.f;
+        if (in) {
+            if (!one_seq) s = find_seq(a.tab.cu_seq, a.tab.n_seq, p);
+            if (POOL) {
+                const int64_t lo = max((int64_t)a.tab.cu_seq[s], p - r);
+                const int64_t hi = min((int64_t)a.tab.cu_seq[s + 1] - 1, p + r);
+                float acc = 0.f;
+                for (int64_t q = lo; q <= hi; ++q) acc += in_row[q];
+                v = acc * a.inv_k;
+                a.out[row + p] = v;
+            } else {
+                v = in_row[p];
+            }
         }
-        if (do_hist) {
+        if (do_hist) {  // uniform
             const uint32_t bin = sortable_key(v) >> 21;
-            if (one_seq) atomicAdd(&bins[bin], 1u);
-            else atomicAdd(a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistBins + bin, 1u);
+            if (one_seq) wave_hist_add(bins, bin, in);  // uniform branch, all lanes take part
+            else if (in) atomicAdd(a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride + bin, 1u);
         }
     }
     if (do_hist && one_seq) {
         __syncthreads();
-        uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s_first) * a.h_kv + g) * kHistBins;
+        uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s_first) * a.h_kv + g) * kHistStride;
         for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) {
             const uint32_t c = bins[b];
             if (c) atomicAdd(gh + b, c);

@@ -3,7 +3,7 @@
 //
 //   pass 1 (stats):  per query row r, the running maximum m_r and Z_r = sum_j 2^(t_rj - m_r) of its
 //                    base-2 logits t_rj = c * q_r.k_j, c = scale * log2(e); one partial per
-//                    (chunk of keys, lane half).
+//                    chunk of keys.
 //   combine:         beta_r = m_r + log2 Z_r over a sequence's partials, stored as -beta_r / c split
 //                    into three bf16 terms.
 //   pass 2 (score):  score_j = sum_r 2^(c * (q_r.k_j - beta_r / c)).  The -beta_r/c term enters
@@ -33,7 +33,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct ScoreArgs {
     const uint16_t* Q;
     const uint16_t* K;
-    float2* stats;    // [n_layers][n_chunks][2 halves][h_kv][RP]
+    float2* stats;    // [n_layers][n_chunks][h_kv][RP]: (m, Z) per chunk of keys
     uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
     float* scores;    // [n_layers][h_kv][T]
     int32_t n_layers, n_seq, n_q, h_q, h_kv, group, rows, RP, chunk_keys, n_chunks;
@@ -252,47 +252,62 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         stats_tile<NQT, true>(kf, qf, m, z, c, ks.n_keys - n_full * kKeyTile, half);
     }
 
-    float2* out = a.stats + ((((int64_t)w.layer * a.n_chunks + w.chunk_global) * 2 + half) * a.h_kv + w.g) * a.RP +
+    // lanes l and l+32 hold the same query rows over complementary keys: merge, then one partial per chunk
+    float2* out = a.stats + (((int64_t)w.layer * a.n_chunks + w.chunk_global) * a.h_kv + w.g) * a.RP +
                   a.row_tile0 * kRowTile + (lane & 31);
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) out[qt * kRowTile] = make_float2(m[qt], z[qt]);
+    for (int qt = 0; qt < NQT; ++qt) {
+        const float mo = __shfl_xor(m[qt], 32), zo = __shfl_xor(z[qt], 32);
+        const float mm = fmaxf(m[qt], mo);
+        const float zz = z[qt] * __builtin_amdgcn_exp2f(m[qt] - mm) + zo * __builtin_amdgcn_exp2f(mo - mm);
+        if (half == 0) out[qt * kRowTile] = make_float2(mm, zz);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
 // combine: per (layer, sequence, head, row) merge the partials into -beta/c as three bf16 terms
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void jq_combine_kernel(ScoreArgs a) {
-    const int64_t n = (int64_t)a.n_layers * a.n_seq * a.h_kv * a.RP;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid >= n) return;
-    const int r = (int)(tid % a.RP);
-    int64_t rest = tid / a.RP;
-    const int g = (int)(rest % a.h_kv);
+constexpr int kCombineLanes = 32;  // partial-lanes per query row
+__global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(ScoreArgs a) {
+    // one workgroup per (layer, sequence, head, tile of 32 rows); thread = (row r, partial-lane kl)
+    __shared__ float2 part[kCombineLanes][kRowTile];
+    const int r = threadIdx.x & (kRowTile - 1), kl = threadIdx.x / kRowTile;
+    const int tiles = a.RP / kRowTile;
+    const int rt = blockIdx.x % tiles;
+    int rest = blockIdx.x / tiles;
+    const int g = rest % a.h_kv;
     rest /= a.h_kv;
-    const int s = (int)(rest % a.n_seq);
-    const int layer = (int)(rest / a.n_seq);
+    const int s = rest % a.n_seq;
+    const int layer = rest / a.n_seq;
+    const int row = rt * kRowTile + r;
 
-    float x = -1.0e30f;  // padded rows: 2^(c*x) = 0
-    if (r < a.rows) {
-        const int c0 = a.tab.cu_chunk[s], c1 = a.tab.cu_chunk[s + 1];
-        const float2* p = a.stats + (((int64_t)layer * a.n_chunks + c0) * 2 * a.h_kv + g) * a.RP + r;
-        const int64_t step = (int64_t)a.h_kv * a.RP;
-        const int n_part = (c1 - c0) * 2;
-        float M = -1.0e30f;
-        for (int k = 0; k < n_part; ++k) M = fmaxf(M, p[k * step].x);
-        float Z = 0.f;
-        for (int k = 0; k < n_part; ++k) {
-            const float2 mz = p[k * step];
-            Z += mz.y * __builtin_amdgcn_exp2f(mz.x - M);
-        }
-        x = -(M + __log2f(Z)) / a.c;
+    const int c0 = a.tab.cu_chunk[s], c1 = a.tab.cu_chunk[s + 1];
+    const float2* p = a.stats + (((int64_t)layer * a.n_chunks + c0) * a.h_kv + g) * a.RP + row;
+    const int64_t step = (int64_t)a.h_kv * a.RP;
+    float M = -1.0e30f, Z = 0.f;
+    for (int k = kl; k < c1 - c0; k += kCombineLanes) {
+        const float2 mz = p[k * step];
+        const float mm = fmaxf(M, mz.x);
+        Z = Z * __builtin_amdgcn_exp2f(M - mm) + mz.y * __builtin_amdgcn_exp2f(mz.x - mm);
+        M = mm;
     }
+    part[kl][r] = make_float2(M, Z);
+    __syncthreads();
+    if (kl != 0) return;
+    for (int k = 1; k < kCombineLanes; ++k) {  // fixed order: deterministic
+        const float2 mz = part[k][r];
+        const float mm = fmaxf(M, mz.x);
+        Z = Z * __builtin_amdgcn_exp2f(M - mm) + mz.y * __builtin_amdgcn_exp2f(mz.x - mm);
+        M = mm;
+    }
+    // padded rows (row >= rows) get 2^(c*x) = 0
+    const float x = row < a.rows ? -(M + __log2f(Z)) / a.c : -1.0e30f;
     const uint32_t hi = __float_as_uint(x) & 0xFFFF0000u;
     const float r1 = x - __uint_as_float(hi);
     const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
     const float r2 = r1 - __uint_as_float(mid);
     const uint32_t lo = __float_as_uint(r2) & 0xFFFF0000u;
-    a.aug[tid] = make_uint2((hi >> 16) | mid, lo >> 16);
+    a.aug[((int64_t)(layer * a.n_seq + s) * a.h_kv + g) * a.RP + row] = make_uint2((hi >> 16) | mid, lo >> 16);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -400,7 +415,8 @@ static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStre
     }
 }
 
-hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st) {
+hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
+                        void* const* marks) {
     ScoreArgs a;
     a.Q = (const uint16_t*)Q;
     a.K = (const uint16_t*)K;
@@ -423,15 +439,18 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
         if ((e = launch_stats_n(nqt, a, grid, st)) != hipSuccess) return e;
     }
-    const int64_t n_rows = (int64_t)p.n_layers * p.n_seq * p.h_kv * a.RP;
-    e = launch_kernel(jq_combine_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), st, a);
+    if (marks && (e = hipEventRecord((hipEvent_t)marks[0], st)) != hipSuccess) return e;
+    const int64_t n_row_tiles = (int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles;
+    e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), st, a);
     if (e != hipSuccess) return e;
+    if (marks && (e = hipEventRecord((hipEvent_t)marks[1], st)) != hipSuccess) return e;
     for (int rg = 0; rg < p.row_groups; ++rg) {
         a.row_tile0 = rg * kMaxRowTiles;
         a.accumulate = rg > 0;
         const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
         if ((e = launch_score_n(nqt, a, grid, st)) != hipSuccess) return e;
     }
+    if (marks && (e = hipEventRecord((hipEvent_t)marks[2], st)) != hipSuccess) return e;
     return hipSuccess;
 }
 

@@ -1,31 +1,39 @@
 // Top-B retention per (layer, sequence, KV head) -- "retain the key-value pairs corresponding to
-// the top-k highest scores" (paper Section 4.3) -- as an exact three-level radix select on the
-// order-preserving 32-bit key of the pooled fp32 score, followed by an ordered compaction.
+// the top-k highest scores" (paper Section 4.3) -- as an exact radix select on the order-preserving
+// 32-bit key of the pooled fp32 score.  Ties go to the lower position; output is ascending.
 //
-//   level 1: bits 31..21 (histogram supplied by the pooling kernel)   -> bin b1
-//   level 2: bits 20..10 of the elements in b1                         -> bin b2
-//   level 3: bits  9..0  of the elements in (b1, b2)                   -> threshold key tau
-//   final:   keep key > tau, plus the first (B - #greater) positions with key == tau, writing
-//            positions in ascending order (block-wide prefix sums over position order).
+//   level 1: bits 31..21, histogram supplied by the pooling kernel                    -> bin b1
+//   level 2: bits 20..10 of the elements in b1                                         -> bin b2
+//   level 3: bits  9..0  of the elements in (b1, b2)                                   -> threshold key tau
+//   result : every key > tau, plus the first (B - #greater) positions with key == tau
 //
-// One workgroup of 1024 threads per problem; the score row is streamed from L2 three times.
+// Fast path (every sequence of the call fits the LDS bitmaps):
+//   scatter  -- the whole GPU streams the scores once; positions above bin b1 go to a "sure"
+//               list, (key, position) pairs inside b1 to a candidate list (wave-aggregated
+//               appends, arbitrary order);
+//   finalize -- one workgroup per problem resolves levels 2 and 3 on the candidates in LDS,
+//               marks sure / chosen positions in an L-bit LDS bitmap, trims the tie group to
+//               its lowest positions and emits the set bits in ascending order.
+// General path (very long sequences): one workgroup per problem streams the row three times.
 #include "jq_common.h"
 
 namespace jq {
 
 struct SelectArgs {
-    const float* pooled;   // [n_layers][h_kv][T]
-    const uint32_t* hist;  // [n_layers][n_seq][h_kv][kHistBins]
-    int32_t* idx;          // [n_layers][h_kv][TB]
-    int32_t h_kv;
+    const float* pooled;  // [n_layers][h_kv][T]
+    uint32_t* hist;       // [n_layers][n_seq][h_kv][kHistStride]: level-1 bins, then the two list counters
+    int32_t* sure;        // [n_layers][h_kv][TB]   positions above bin b1 (unordered)
+    uint2* cand;          // [n_layers][h_kv][T]    (key, position) inside bin b1 (unordered)
+    int32_t* idx;         // [n_layers][h_kv][TB]
+    int32_t n_layers, h_kv;
     int64_t T, TB;
     SeqTab tab;
 };
 
-constexpr int kWaves = kSelectThreads / 64;
-
-// Inclusive prefix sum over the block (thread order); `tmp` holds kWaves + 1 words.
+// Inclusive prefix sum over a block of THREADS threads (thread order); `tmp` holds THREADS/64 + 1 words.
+template <int THREADS>
 __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* tmp, uint32_t* total) {
+    constexpr int kW = THREADS / 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t x = v;
 #pragma unroll
@@ -37,63 +45,85 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* tmp, u
     if (lane == 63) tmp[wave] = x;
     __syncthreads();
     if (wave == 0) {
-        uint32_t w = lane < kWaves ? tmp[lane] : 0u;
+        const uint32_t w = lane < kW ? tmp[lane] : 0u;
         uint32_t wi = w;
 #pragma unroll
-        for (int d = 1; d < kWaves; d <<= 1) {
+        for (int d = 1; d < kW; d <<= 1) {
             const uint32_t y = __shfl_up(wi, d);
             if (lane >= d) wi += y;
         }
-        if (lane < kWaves) tmp[lane] = wi - w;  // exclusive wave offsets
-        if (lane == kWaves - 1) tmp[kWaves] = wi;
+        if (lane < kW) tmp[lane] = wi - w;  // exclusive wave offsets
+        if (lane == kW - 1) tmp[kW] = wi;
     }
     __syncthreads();
-    *total = tmp[kWaves];
+    *total = tmp[kW];
     return x + tmp[wave];
 }
 
-// Given bins[0..n_bins) (LDS), find the bin b such that (#elements in bins > b) < need <=
-// (#elements in bins >= b).  Returns b and writes that count of strictly greater elements.
-// n_bins must be a multiple of kSelectThreads or smaller; uses two bins per thread at most.
-__device__ __forceinline__ uint32_t pick_bin(const uint32_t* bins, int n_bins, uint32_t need, uint32_t* tmp,
-                                             uint32_t* result /* LDS: [0]=bin, [1]=above */) {
-    // thread t owns the bins (n_bins-1-2t) and (n_bins-2-2t): descending order
-    const int b_hi = n_bins - 1 - 2 * (int)threadIdx.x, b_lo = b_hi - 1;
-    const uint32_t c_hi = b_hi >= 0 ? bins[b_hi] : 0u;
-    const uint32_t c_lo = b_lo >= 0 ? bins[b_lo] : 0u;
+// bins[0..n_bins): find the bin b with (#elements in bins > b) < need <= (#elements in bins >= b).
+// Thread t owns PER consecutive bins, highest bins first.  result[0] = b, result[1] = #elements above.
+template <int THREADS, int PER, typename BinPtr>
+__device__ __forceinline__ void pick_bin(BinPtr bins, int n_bins, uint32_t need, uint32_t* tmp, uint32_t* result) {
+    uint32_t c[PER];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int b = n_bins - 1 - (PER * (int)threadIdx.x + e);
+        c[e] = b >= 0 ? bins[b] : 0u;
+        sum += c[e];
+    }
     uint32_t total;
-    const uint32_t incl = block_scan_incl(c_hi + c_lo, tmp, &total);
-    const uint32_t before = incl - (c_hi + c_lo);  // elements in bins above b_hi
-    if (before < need && need <= before + c_hi) { result[0] = (uint32_t)b_hi; result[1] = before; }
-    else if (before + c_hi < need && need <= incl) { result[0] = (uint32_t)b_lo; result[1] = before + c_hi; }
+    const uint32_t incl = block_scan_incl<THREADS>(sum, tmp, &total);
+    uint32_t before = incl - sum;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        if (before < need && need <= before + c[e]) {
+            result[0] = (uint32_t)(n_bins - 1 - (PER * (int)threadIdx.x + e));
+            result[1] = before;
+        }
+        before += c[e];
+    }
     __syncthreads();
-    return result[0];
 }
 
-__global__ __launch_bounds__(kSelectThreads) void jq_select_kernel(SelectArgs a) {
+struct Problem {
+    int layer, s, g, L;
+    uint32_t B;
+    const float* x;
+    int32_t* out;
+    uint32_t* hist;
+};
+
+__device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
+    Problem p;
+    p.g = prob % a.h_kv;
+    p.s = (prob / a.h_kv) % a.tab.n_seq;
+    p.layer = prob / (a.h_kv * a.tab.n_seq);
+    p.L = a.tab.cu_seq[p.s + 1] - a.tab.cu_seq[p.s];
+    p.B = (uint32_t)(a.tab.cu_bud[p.s + 1] - a.tab.cu_bud[p.s]);
+    p.x = a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s];
+    p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
+    p.hist = a.hist + (((int64_t)p.layer * a.tab.n_seq + p.s) * a.h_kv + p.g) * kHistStride;
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------------
+// general path: one workgroup streams its row three times
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelectThreads) void jq_select_stream_kernel(SelectArgs a) {
     __shared__ uint32_t bins[kHistBins];
-    __shared__ uint32_t tmp[kWaves + 1];
+    __shared__ uint32_t tmp[kSelectThreads / 64 + 1];
     __shared__ uint32_t res[2];
+    const Problem p = problem_of(a, blockIdx.x);
+    const float* x = p.x;
+    const int L = p.L;
 
-    const int prob = blockIdx.x;
-    const int g = prob % a.h_kv;
-    const int s = (prob / a.h_kv) % a.tab.n_seq;
-    const int layer = prob / (a.h_kv * a.tab.n_seq);
-    const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
-    const uint32_t B = (uint32_t)(a.tab.cu_bud[s + 1] - a.tab.cu_bud[s]);
-    const float* x = a.pooled + ((int64_t)layer * a.h_kv + g) * a.T + a.tab.cu_seq[s];
-    int32_t* out = a.idx + ((int64_t)layer * a.h_kv + g) * a.TB + a.tab.cu_bud[s];
-    const uint32_t* h1 = a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistBins;
-
-    // ---- level 1 -----------------------------------------------------------------------------
-    for (int b = threadIdx.x; b < kHistBins; b += kSelectThreads) bins[b] = h1[b];
-    __syncthreads();
-    uint32_t need = B;
-    const uint32_t b1 = pick_bin(bins, kHistBins, need, tmp, res);
+    uint32_t need = p.B;
+    pick_bin<kSelectThreads, 2>(p.hist, kHistBins, need, tmp, res);
+    const uint32_t b1 = res[0];
     need -= res[1];
     __syncthreads();
 
-    // ---- level 2 -----------------------------------------------------------------------------
     for (int b = threadIdx.x; b < kHistBins; b += kSelectThreads) bins[b] = 0;
     __syncthreads();
     for (int j = threadIdx.x; j < L; j += kSelectThreads) {
@@ -101,12 +131,11 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_kernel(SelectArgs a)
         if ((k >> 21) == b1) atomicAdd(&bins[(k >> 10) & 2047u], 1u);
     }
     __syncthreads();
-    const uint32_t b2 = pick_bin(bins, 2048, need, tmp, res);
+    pick_bin<kSelectThreads, 2>(bins, 2048, need, tmp, res);
+    const uint32_t prefix22 = (b1 << 11) | res[0];
     need -= res[1];
     __syncthreads();
 
-    // ---- level 3 -----------------------------------------------------------------------------
-    const uint32_t prefix22 = (b1 << 11) | b2;
     for (int b = threadIdx.x; b < 1024; b += kSelectThreads) bins[b] = 0;
     __syncthreads();
     for (int j = threadIdx.x; j < L; j += kSelectThreads) {
@@ -114,27 +143,26 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_kernel(SelectArgs a)
         if ((k >> 10) == prefix22) atomicAdd(&bins[k & 1023u], 1u);
     }
     __syncthreads();
-    const uint32_t b3 = pick_bin(bins, 1024, need, tmp, res);
+    pick_bin<kSelectThreads, 1>(bins, 1024, need, tmp, res);
+    const uint32_t tau = (prefix22 << 10) | res[0];
     need -= res[1];  // how many elements equal to tau are kept
     __syncthreads();
-    const uint32_t tau = (prefix22 << 10) | b3;
 
-    // ---- ordered compaction ------------------------------------------------------------------
-    // Each thread takes 4 consecutive positions per round, so thread order is position order.
-    uint32_t gt_done = 0, eq_done = 0;  // kept-so-far counts before this round (uniform)
+    // ordered compaction: each thread takes 4 consecutive positions per round
+    uint32_t gt_done = 0, eq_done = 0;
     for (int base = 0; base < L; base += kSelectThreads * 4) {
         const int j0 = base + threadIdx.x * 4;
         uint32_t kk[4];
         uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            kk[e] = (j0 + e < L) ? sortable_key(x[j0 + e]) : 0u;  // key 0 is below every real key
+            kk[e] = (j0 + e < L) ? sortable_key(x[j0 + e]) : 0u;
             n_gt += (j0 + e < L) && kk[e] > tau;
             n_eq += (j0 + e < L) && kk[e] == tau;
         }
         uint32_t total;
         const uint32_t packed = n_gt | (n_eq << 16);  // at most 4096 per field and round
-        const uint32_t incl = block_scan_incl(packed, tmp, &total);
+        const uint32_t incl = block_scan_incl<kSelectThreads>(packed, tmp, &total);
         uint32_t gt_before = gt_done + ((incl - packed) & 0xFFFFu);
         uint32_t eq_before = eq_done + ((incl - packed) >> 16);
 #pragma unroll
@@ -143,24 +171,188 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_kernel(SelectArgs a)
             const bool is_gt = kk[e] > tau, is_eq = kk[e] == tau;
             if (is_gt || (is_eq && eq_before < need)) {
                 const uint32_t slot = gt_before + min(eq_before, need);
-                if (slot < B) out[slot] = j0 + e;  // always true for consistent histograms; guards NaN-poisoned input
+                if (slot < p.B) p.out[slot] = j0 + e;  // always true for consistent histograms
             }
             gt_before += is_gt;
             eq_before += is_eq;
         }
         gt_done += total & 0xFFFFu;
         eq_done += total >> 16;
-        if (gt_done + min(eq_done, need) >= B) break;  // uniform: everything kept already
+        if (gt_done + min(eq_done, need) >= p.B) break;  // uniform: everything kept already
     }
 }
 
-hipError_t launch_select(const Plan& p, const float* pooled, const uint32_t* hist, int32_t* idx, hipStream_t st) {
+// ------------------------------------------------------------------------------------------------
+// fast path, step 1: scatter positions above / inside the level-1 threshold bin
+// ------------------------------------------------------------------------------------------------
+constexpr int kScatterThreads = 256;
+constexpr int kScatterPerThread = 16;
+constexpr int kScatterBlockPos = kScatterThreads * kScatterPerThread;
+
+// Appends one item per lane with `pred` set; one global atomic per wave.  Returns the slot or -1.
+__device__ __forceinline__ int wave_append(bool pred, uint32_t* counter) {
+    const uint64_t mask = __ballot(pred);
+    if (mask == 0) return -1;
+    const int lane = threadIdx.x & 63;
+    const int leader = __ffsll((unsigned long long)mask) - 1;
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(mask));
+    base = __shfl(base, leader);
+    return pred ? (int)(base + __popcll(mask & ((1ull << lane) - 1ull))) : -1;
+}
+
+__global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(SelectArgs a) {
+    __shared__ uint32_t tmp[kScatterThreads / 64 + 1];
+    __shared__ uint32_t res[2];
+    const int g = blockIdx.y, layer = blockIdx.z;
+    const int64_t p0 = (int64_t)blockIdx.x * kScatterBlockPos;
+    const int64_t p1 = min(a.T, p0 + kScatterBlockPos);
+    const int s_first = find_seq(a.tab.cu_seq, a.tab.n_seq, p0);
+    const int s_last = find_seq(a.tab.cu_seq, a.tab.n_seq, p1 - 1);
+    const float* row = a.pooled + ((int64_t)layer * a.h_kv + g) * a.T;
+    for (int s = s_first; s <= s_last; ++s) {  // almost always a single sequence
+        uint32_t* hist = a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride;
+        const uint32_t B = (uint32_t)(a.tab.cu_bud[s + 1] - a.tab.cu_bud[s]);
+        const int Ls = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
+        pick_bin<kScatterThreads, kHistBins / kScatterThreads>(hist, kHistBins, B, tmp, res);
+        const uint32_t b1 = res[0];
+        __syncthreads();
+        const int64_t q0 = max(p0, (int64_t)a.tab.cu_seq[s]), q1 = min(p1, (int64_t)a.tab.cu_seq[s + 1]);
+        int32_t* sure = a.sure + ((int64_t)layer * a.h_kv + g) * a.TB + a.tab.cu_bud[s];
+        uint2* cand = a.cand + ((int64_t)layer * a.h_kv + g) * a.T + a.tab.cu_seq[s];
+#pragma unroll 4
+        for (int e = 0; e < kScatterPerThread; ++e) {
+            const int64_t p = p0 + e * kScatterThreads + threadIdx.x;
+            const bool in = p >= q0 && p < q1;
+            const uint32_t k = in ? sortable_key(row[p]) : 0u;
+            const uint32_t bin = k >> 21;
+            const int j = (int)(p - a.tab.cu_seq[s]);
+            const int slot_s = wave_append(in && bin > b1, hist + kHistBins);
+            if (slot_s >= 0 && (uint32_t)slot_s < B) sure[slot_s] = j;
+            const int slot_c = wave_append(in && bin == b1, hist + kHistBins + 1);
+            if (slot_c >= 0 && slot_c < Ls) cand[slot_c] = make_uint2(k, (uint32_t)j);
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// fast path, step 2: resolve the candidates and emit ascending positions
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelectThreads) void jq_select_finalize_kernel(SelectArgs a, int words_cap) {
+    extern __shared__ uint32_t lds[];
+    uint32_t* bins = lds;                         // kHistBins
+    uint32_t* tmp = bins + kHistBins;             // kSelectThreads / 64 + 1 (padded to 32)
+    uint32_t* res = tmp + 32;                     // 2 (padded to 32)
+    uint32_t* keep = res + 32;                    // words_cap: bitmap of kept positions
+    uint32_t* ties = keep + words_cap;            // words_cap: bitmap of positions with key == tau
+
+    const Problem p = problem_of(a, blockIdx.x);
+    const int words = (p.L + 31) >> 5;
+    const uint32_t n_sure = min(p.hist[kHistBins], p.B);
+    const uint32_t n_cand = min(p.hist[kHistBins + 1], (uint32_t)p.L);
+    const int32_t* sure = a.sure + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
+    const uint2* cand = a.cand + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s];
+
+    for (int w = threadIdx.x; w < words; w += kSelectThreads) { keep[w] = 0; ties[w] = 0; }
+    for (int b = threadIdx.x; b < kHistBins; b += kSelectThreads) bins[b] = 0;
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < n_sure; i += kSelectThreads) {
+        const uint32_t j = (uint32_t)sure[i];
+        if (j < (uint32_t)p.L) atomicOr(&keep[j >> 5], 1u << (j & 31));
+    }
+    uint32_t need = p.B - n_sure;  // >= 1: the threshold bin always contributes
+
+    // level 2 on the candidates
+    for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) atomicAdd(&bins[(cand[i].x >> 10) & 2047u], 1u);
+    __syncthreads();
+    pick_bin<kSelectThreads, 2>(bins, 2048, need, tmp, res);
+    const uint32_t b2 = res[0];
+    need -= res[1];
+    __syncthreads();
+    // level 3
+    for (int b = threadIdx.x; b < 1024; b += kSelectThreads) bins[b] = 0;
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) {
+        const uint32_t k = cand[i].x;
+        if (((k >> 10) & 2047u) == b2) atomicAdd(&bins[k & 1023u], 1u);
+    }
+    __syncthreads();
+    pick_bin<kSelectThreads, 1>(bins, 1024, need, tmp, res);
+    const uint32_t low21 = (b2 << 10) | res[0];
+    need -= res[1];  // how many positions with key == tau are kept
+    __syncthreads();
+
+    for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) {
+        const uint2 c = cand[i];
+        const uint32_t k21 = c.x & 0x1FFFFFu;
+        if (c.y < (uint32_t)p.L) {
+            if (k21 > low21) atomicOr(&keep[c.y >> 5], 1u << (c.y & 31));
+            else if (k21 == low21) atomicOr(&ties[c.y >> 5], 1u << (c.y & 31));
+        }
+    }
+    __syncthreads();
+
+    // thread t owns a contiguous run of words, so thread order is position order
+    const int wpt = (words + kSelectThreads - 1) / kSelectThreads;
+    const int w0 = threadIdx.x * wpt, w1 = min(words, w0 + wpt);
+    uint32_t n_t = 0;
+    for (int w = w0; w < w1; ++w) n_t += __popc(ties[w]);
+    uint32_t total;
+    uint32_t before = block_scan_incl<kSelectThreads>(n_t, tmp, &total) - n_t;
+    for (int w = w0; w < w1 && before < need; ++w) {  // the lowest `need` tie positions join the kept set
+        uint32_t t = ties[w];
+        const uint32_t cnt = __popc(t);
+        uint32_t take = min(cnt, need - before);
+        before += cnt;
+        uint32_t add = 0;
+        while (take--) { const uint32_t low = t & (0u - t); add |= low; t ^= low; }
+        keep[w] |= add;  // only this thread touches word w here
+    }
+    __syncthreads();
+    uint32_t n_k = 0;
+    for (int w = w0; w < w1; ++w) n_k += __popc(keep[w]);
+    uint32_t slot = block_scan_incl<kSelectThreads>(n_k, tmp, &total) - n_k;
+    for (int w = w0; w < w1; ++w) {
+        uint32_t k = keep[w];
+        while (k) {
+            const int bit = __ffs(k) - 1;
+            k &= k - 1;
+            if (slot < p.B) p.out[slot] = (w << 5) + bit;
+            ++slot;
+        }
+    }
+}
+
+constexpr int kFinalizeFixedWords = kHistBins + 32 + 32;
+constexpr size_t kMaxLds = 160 * 1024;
+
+hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st) {
     SelectArgs a;
     a.pooled = pooled; a.hist = hist; a.idx = idx;
-    a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
+    a.sure = (int32_t*)(ws + p.off_sure);
+    a.cand = (uint2*)(ws + p.off_cand);
+    a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.tab = p.tab;
     const unsigned n_prob = (unsigned)((int64_t)p.n_layers * p.n_seq * p.h_kv);
-    return launch_kernel(jq_select_kernel, dim3(n_prob), dim3(kSelectThreads), st, a);
+
+    int max_len = 0;
+    for (int s = 0; s < p.n_seq; ++s) max_len = max(max_len, p.tab.cu_seq[s + 1] - p.tab.cu_seq[s]);
+    int words_cap = (max_len + 31) / 32;
+    const size_t lds_bytes = ((size_t)kFinalizeFixedWords + 2 * (size_t)words_cap) * sizeof(uint32_t);
+    if (lds_bytes > kMaxLds - 1024)  // bitmaps do not fit: stream instead
+        return launch_kernel(jq_select_stream_kernel, dim3(n_prob), dim3(kSelectThreads), st, a);
+
+    dim3 grid((unsigned)((p.T + kScatterBlockPos - 1) / kScatterBlockPos), p.h_kv, p.n_layers);
+    hipError_t e = launch_kernel(jq_select_scatter_kernel, grid, dim3(kScatterThreads), st, a);
+    if (e != hipSuccess) return e;
+    if (lds_bytes > 64 * 1024) {
+        e = hipFuncSetAttribute((const void*)jq_select_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    void* args[] = {(void*)&a, (void*)&words_cap};
+    return hipLaunchKernel((const void*)jq_select_finalize_kernel, dim3(n_prob), dim3(kSelectThreads), args, lds_bytes, st);
 }
 
 }  // namespace jq
