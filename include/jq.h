@@ -122,16 +122,17 @@ int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V,
              void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
              void* ws, size_t ws_bytes, void* stream);
 
-/* jq_evict with stage timing (the measurement hook of the benchmark): `marks` is a
- * HOST array of JQ_TRACE_MARKS hipEvent_t (passed as void*), created by the caller,
- * which are recorded on `stream` at these points:
- *   [0] before the first K pass       [1] after the statistics pass (first pass over K)
- *   [2] after the statistics merge    [3] after the score pass (second pass over K)
- *   [4] after pooling                 [5] after top-B selection
- *   [6] after the gather
- * so that elapsed(marks[i], marks[i+1]) brackets one stage.  Results are those of
- * jq_evict; recording events between kernels costs a little launch overlap. */
-#define JQ_TRACE_MARKS 7
+/* jq_evict with kernel timing (the measurement hook of the benchmark): `marks` is a
+ * HOST array of JQ_TRACE_MARKS hipEvent_t (passed as void*), created by the caller.
+ * Kernel i of the sequence below is launched with marks[2i] / marks[2i+1] as its
+ * start / stop events, so that hipEventElapsedTime(marks[2i], marks[2i+1]) is the
+ * duration of that dispatch alone:
+ *   0 statistics pass over K   1 statistics merge        2 score pass over K
+ *   3 pooling (+ histogram)    4 selection: scatter      5 selection: finalize
+ *   6 gather
+ * (when a stage needs several launches the last one is reported).  Results are
+ * those of jq_evict. */
+#define JQ_TRACE_MARKS 14
 int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const void* V,
                     void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
                     void* ws, size_t ws_bytes, void* stream, void* const* marks, int n_marks);

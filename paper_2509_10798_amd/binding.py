@@ -23,8 +23,9 @@ STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET"
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
 EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced",
            "jq_status_string")
-TRACE_MARKS = 7
-TRACE_STAGES = ("stats_pass", "stats_merge", "score_pass", "pool", "select", "compact")
+TRACE_KERNELS = ("jq_stats_kernel", "jq_combine_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel",
+                 "jq_select_finalize_kernel", "jq_compact_kernel")
+TRACE_MARKS = 2 * len(TRACE_KERNELS)
 
 
 class JQError(RuntimeError):
@@ -182,7 +183,8 @@ def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_ou
     """Fused score -> pool -> top-B -> gather.  Returns (K_out, V_out, idx_out, pooled scores).
 
     `marks`: optional list of TRACE_MARKS torch.cuda.Event(enable_timing=True) objects that have been
-    recorded once (so that their handles exist); they are re-recorded at the stage boundaries."""
+    recorded once (so that their handles exist); events 2i / 2i+1 receive the start / stop time of
+    kernel TRACE_KERNELS[i]."""
     import torch
     dev = K.device
     if K_out is None:

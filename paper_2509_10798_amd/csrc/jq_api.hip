@@ -222,16 +222,12 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
     float* raw = (float*)(w + p.off_scores);
     float* pooled = scores_out ? scores_out : (float*)(w + p.off_pooled);
     int32_t* idx = idx_out ? idx_out : (int32_t*)(w + p.off_idx);
-    auto mark = [&](int i) { return marks ? hipEventRecord((hipEvent_t)marks[i], st) : hipSuccess; };
-    hipError_t e = launch_fill_u32(hist, (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride, 0u, st);
-    if (e == hipSuccess) e = mark(0);
-    if (e == hipSuccess) e = launch_score(p, Q, K, raw, w, st, marks ? marks + 1 : nullptr);  // marks 1..3
+    p.marks = marks;
+    const size_t zero_words = (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride;
+    hipError_t e = launch_score(p, Q, K, raw, w, st, hist, zero_words);  // also clears the selection histograms
     if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, st);
-    if (e == hipSuccess) e = mark(4);
-    if (e == hipSuccess) e = launch_select(p, pooled, hist, (char*)ws, idx, st);
-    if (e == hipSuccess) e = mark(5);
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st);
     if (e == hipSuccess) e = launch_compact(p, K, V, idx, K_out, V_out, st);
-    if (e == hipSuccess) e = mark(6);
     return launch_status(e);
 }
 

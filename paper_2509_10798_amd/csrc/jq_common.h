@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -37,6 +38,7 @@ struct Plan {
     float scale;          // logit scale actually used
     int64_t T, TB;
     SeqTab tab;
+    void* const* marks;   // host only: nullptr, or 2 * kTraceKernels events (start, stop) for jq_evict_traced
     // workspace layout (byte offsets, 256-aligned)
     size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
 };
@@ -57,18 +59,27 @@ __device__ inline uint32_t sortable_key(float x) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+// Kernels whose start/stop timestamps jq_evict_traced reports, in launch order.
+enum TraceKernel { kTrStats = 0, kTrCombine, kTrScore, kTrPool, kTrScatter, kTrFinalize, kTrCompact, kTraceKernels };
+
 // Launch through hipLaunchKernel so that the status belongs to this launch alone (the sticky
 // "last error" of the runtime may hold an unrelated, earlier code from the host application).
+// With `marks` set, the launch carries the (start, stop) events of slot `tr`, which receive the
+// dispatch's own begin/end timestamps.
 template <typename Kernel, typename... Args>
-inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_t st, Args... args) {
+inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st,
+                                void* const* marks, int tr, Args... args) {
     void* ptrs[] = {(void*)&args...};
-    return hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, st);
+    if (marks && tr >= 0)
+        return hipExtLaunchKernel((const void*)kernel, grid, block, ptrs, lds_bytes, st, (hipEvent_t)marks[2 * tr],
+                                  (hipEvent_t)marks[2 * tr + 1], 0);
+    return hipLaunchKernel((const void*)kernel, grid, block, ptrs, lds_bytes, st);
 }
 
 // Stage launchers (enqueue only).  Each returns a hipError_t from the launch.
-// `marks` (nullable): three events recorded after the statistics pass, the combine step and the score pass.
+// `zero_words` words at `zero` (nullable) are cleared on the way (between the two K passes).
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
-                        void* const* marks = nullptr);
+                        uint32_t* zero = nullptr, size_t zero_words = 0);
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st);
 hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st);

@@ -41,6 +41,8 @@ struct ScoreArgs {
     int32_t accumulate;  // pass 2: add to `scores` instead of overwriting
     float c;             // scale * log2(e)
     int64_t T;
+    uint32_t* zero;      // combine: words to clear for the later selection stage (nullable)
+    uint64_t zero_words;
     SeqTab tab;
 };
 
@@ -48,10 +50,22 @@ constexpr int kSlotBytes = kKeyTile * kHeadDim * 2;  // 8 KiB
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// s_waitcnt vmcnt(0) only (expcnt and lgkmcnt fields left at "no wait"), then keep the compiler
-// from moving LDS reads above it: the loads-to-LDS are invisible to its own dependency tracking.
-__device__ __forceinline__ void wait_tile_landed() {
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+// Key tiles arrive through loads that write LDS directly; the compiler does not track them, so the
+// waits are explicit.  Loads complete in issue order, and every tile is exactly 8 loads, hence
+// "at most 8 outstanding" means: everything older than the newest tile has landed.
+// (s_waitcnt immediates: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; unused fields = no wait.)
+__device__ __forceinline__ void wait_tile_landed(bool newer_tile_in_flight) {
+    if (newer_tile_in_flight) __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+}
+
+// The fragments just read from an LDS slot must be in registers before the slot is refilled.
+__device__ __forceinline__ void wait_frags_read() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("" ::: "memory");
 }
@@ -224,7 +238,10 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 
     const KeyStream ks = key_stream(a, w);
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
+    // two tiles in flight from the start; a slot is refilled as soon as its fragments are in registers
     fetch_tile(ks.rsrc, slots, 0u, ks.row_bytes, ks.n_keys, tl, lane);
+    if (ks.n_tiles > 1)
+        fetch_tile(ks.rsrc, slots + kSlotBytes, kKeyTile * ks.row_bytes, ks.row_bytes, ks.n_keys - kKeyTile, tl, lane);
 
     bf16x8 qf[NQT][8];
     load_q<NQT>(a, w, lane, qf);
@@ -233,20 +250,23 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     float m[NQT], z[NQT];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
+    // the Q loads above are older than the tile loads only in part: drain everything once
+    __builtin_amdgcn_s_waitcnt(0x0F70);
 
     const int n_full = ks.n_keys / kKeyTile;
     for (int t = 0; t < n_full; ++t) {
-        wait_tile_landed();
+        if (t > 0) wait_tile_landed(t + 1 < ks.n_tiles);
         bf16x8 kf[8];
         lds_get_frags(slots + (t & 1) * kSlotBytes, kf, lane);
-        // the other slot was last read one iteration ago; refill it while this tile is computed
-        if (t + 1 < ks.n_tiles)
-            fetch_tile(ks.rsrc, slots + ((t + 1) & 1) * kSlotBytes, (uint32_t)(t + 1) * kKeyTile * ks.row_bytes,
-                       ks.row_bytes, ks.n_keys - (t + 1) * kKeyTile, tl, lane);
+        if (t + 2 < ks.n_tiles) {
+            wait_frags_read();
+            fetch_tile(ks.rsrc, slots + (t & 1) * kSlotBytes, (uint32_t)(t + 2) * kKeyTile * ks.row_bytes, ks.row_bytes,
+                       ks.n_keys - (t + 2) * kKeyTile, tl, lane);
+        }
         stats_tile<NQT, false>(kf, qf, m, z, c, kKeyTile, half);
     }
     if (n_full < ks.n_tiles) {  // partial last tile
-        wait_tile_landed();
+        if (n_full > 0) wait_tile_landed(false);
         bf16x8 kf[8];
         lds_get_frags(slots + (n_full & 1) * kSlotBytes, kf, lane);
         stats_tile<NQT, true>(kf, qf, m, z, c, ks.n_keys - n_full * kKeyTile, half);
@@ -280,6 +300,12 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
     const int s = rest % a.n_seq;
     const int layer = rest / a.n_seq;
     const int row = rt * kRowTile + r;
+
+    if (a.zero) {  // clear the selection histograms and counters while we are here
+        const uint64_t per = (a.zero_words + gridDim.x - 1) / gridDim.x;
+        const uint64_t z0 = per * blockIdx.x, z1 = z0 + per < a.zero_words ? z0 + per : a.zero_words;
+        for (uint64_t i = z0 + threadIdx.x; i < z1; i += blockDim.x) a.zero[i] = 0u;
+    }
 
     const int c0 = a.tab.cu_chunk[s], c1 = a.tab.cu_chunk[s + 1];
     const float2* p = a.stats + (((int64_t)layer * a.n_chunks + c0) * a.h_kv + g) * a.RP + row;
@@ -325,6 +351,8 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     const KeyStream ks = key_stream(a, w);
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
     fetch_tile(ks.rsrc, slots, 0u, ks.row_bytes, ks.n_keys, tl, lane);
+    if (ks.n_tiles > 1)
+        fetch_tile(ks.rsrc, slots + kSlotBytes, kKeyTile * ks.row_bytes, ks.row_bytes, ks.n_keys - kKeyTile, tl, lane);
 
     bf16x8 qf[NQT][8];
     load_q<NQT>(a, w, lane, qf);
@@ -349,17 +377,19 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     float pending = 0.f;  // previous tile's result, stored one iteration late so that the store has a
                           // whole tile of compute to retire before the next wait on outstanding loads
 
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // Q, the -beta/c terms and the first two tiles are in
     for (int t = 0; t < ks.n_tiles; ++t) {
-        const int valid = ks.n_keys - t * kKeyTile;
-        wait_tile_landed();
+        if (t > 0) wait_tile_landed(t + 1 < ks.n_tiles);
         bf16x8 kf[8];
         lds_get_frags(slots + (t & 1) * kSlotBytes, kf, lane);
-        if (t + 1 < ks.n_tiles)
-            fetch_tile(ks.rsrc, slots + ((t + 1) & 1) * kSlotBytes, (uint32_t)(t + 1) * kKeyTile * ks.row_bytes,
-                       ks.row_bytes, valid - kKeyTile, tl, lane);
         if (t > 0 && lane < 32) {  // tile t-1 was full (only the last tile can be partial)
             float* o = out + (t - 1) * kKeyTile + lane;
             *o = a.accumulate ? *o + pending : pending;
+        }
+        if (t + 2 < ks.n_tiles) {  // issued after the store: only these 8 loads are newer than tile t+1
+            wait_frags_read();
+            fetch_tile(ks.rsrc, slots + (t & 1) * kSlotBytes, (uint32_t)(t + 2) * kKeyTile * ks.row_bytes, ks.row_bytes,
+                       ks.n_keys - (t + 2) * kKeyTile, tl, lane);
         }
         float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
@@ -395,28 +425,29 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-static hipError_t launch_stats_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st) {
+static hipError_t launch_stats_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st, void* const* marks) {
     dim3 block(kScoreWaves * 64);
     switch (nqt) {
-        case 1: return launch_kernel(jq_stats_kernel<1>, grid, block, st, a);
-        case 2: return launch_kernel(jq_stats_kernel<2>, grid, block, st, a);
-        case 3: return launch_kernel(jq_stats_kernel<3>, grid, block, st, a);
-        default: return launch_kernel(jq_stats_kernel<4>, grid, block, st, a);
+        case 1: return launch_kernel(jq_stats_kernel<1>, grid, block, 0, st, marks, kTrStats, a);
+        case 2: return launch_kernel(jq_stats_kernel<2>, grid, block, 0, st, marks, kTrStats, a);
+        case 3: return launch_kernel(jq_stats_kernel<3>, grid, block, 0, st, marks, kTrStats, a);
+        default: return launch_kernel(jq_stats_kernel<4>, grid, block, 0, st, marks, kTrStats, a);
     }
 }
 
-static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st) {
+static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st, void* const* marks) {
     dim3 block(kScoreWaves * 64);
     switch (nqt) {
-        case 1: return launch_kernel(jq_score_kernel<1>, grid, block, st, a);
-        case 2: return launch_kernel(jq_score_kernel<2>, grid, block, st, a);
-        case 3: return launch_kernel(jq_score_kernel<3>, grid, block, st, a);
-        default: return launch_kernel(jq_score_kernel<4>, grid, block, st, a);
+        case 1: return launch_kernel(jq_score_kernel<1>, grid, block, 0, st, marks, kTrScore, a);
+        case 2: return launch_kernel(jq_score_kernel<2>, grid, block, 0, st, marks, kTrScore, a);
+        case 3: return launch_kernel(jq_score_kernel<3>, grid, block, 0, st, marks, kTrScore, a);
+        default: return launch_kernel(jq_score_kernel<4>, grid, block, 0, st, marks, kTrScore, a);
     }
 }
 
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
-                        void* const* marks) {
+                        uint32_t* zero, size_t zero_words) {
+    void* const* marks = p.marks;
     ScoreArgs a;
     a.Q = (const uint16_t*)Q;
     a.K = (const uint16_t*)K;
@@ -429,6 +460,7 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.row_tile0 = 0; a.accumulate = 0;
     a.c = p.scale * 1.4426950408889634f;
     a.T = p.T;
+    a.zero = zero; a.zero_words = zero_words;
     a.tab = p.tab;
 
     const int64_t waves = (int64_t)p.n_layers * p.n_chunks * p.h_kv;
@@ -437,20 +469,17 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     for (int rg = 0; rg < p.row_groups; ++rg) {
         a.row_tile0 = rg * kMaxRowTiles;
         const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
-        if ((e = launch_stats_n(nqt, a, grid, st)) != hipSuccess) return e;
+        if ((e = launch_stats_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
     }
-    if (marks && (e = hipEventRecord((hipEvent_t)marks[0], st)) != hipSuccess) return e;
     const int64_t n_row_tiles = (int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles;
-    e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), st, a);
+    e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a);
     if (e != hipSuccess) return e;
-    if (marks && (e = hipEventRecord((hipEvent_t)marks[1], st)) != hipSuccess) return e;
     for (int rg = 0; rg < p.row_groups; ++rg) {
         a.row_tile0 = rg * kMaxRowTiles;
         a.accumulate = rg > 0;
         const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
-        if ((e = launch_score_n(nqt, a, grid, st)) != hipSuccess) return e;
+        if ((e = launch_score_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
     }
-    if (marks && (e = hipEventRecord((hipEvent_t)marks[2], st)) != hipSuccess) return e;
     return hipSuccess;
 }
 

@@ -9,8 +9,8 @@
 //
 // Fast path (every sequence of the call fits the LDS bitmaps):
 //   scatter  -- the whole GPU streams the scores once; positions above bin b1 go to a "sure"
-//               list, (key, position) pairs inside b1 to a candidate list (wave-aggregated
-//               appends, arbitrary order);
+//               list, (key, position) pairs inside b1 to a candidate list (block-aggregated
+//               appends; the order between blocks is arbitrary);
 //   finalize -- one workgroup per problem resolves levels 2 and 3 on the candidates in LDS,
 //               marks sure / chosen positions in an L-bit LDS bitmap, trims the tie group to
 //               its lowest positions and emits the set bits in ascending order.
@@ -189,48 +189,55 @@ constexpr int kScatterThreads = 256;
 constexpr int kScatterPerThread = 16;
 constexpr int kScatterBlockPos = kScatterThreads * kScatterPerThread;
 
-// Appends one item per lane with `pred` set; one global atomic per wave.  Returns the slot or -1.
-__device__ __forceinline__ int wave_append(bool pred, uint32_t* counter) {
-    const uint64_t mask = __ballot(pred);
-    if (mask == 0) return -1;
-    const int lane = threadIdx.x & 63;
-    const int leader = __ffsll((unsigned long long)mask) - 1;
-    uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(mask));
-    base = __shfl(base, leader);
-    return pred ? (int)(base + __popcll(mask & ((1ull << lane) - 1ull))) : -1;
-}
-
 __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(SelectArgs a) {
     __shared__ uint32_t tmp[kScatterThreads / 64 + 1];
     __shared__ uint32_t res[2];
+    __shared__ uint32_t base[2];
     const int g = blockIdx.y, layer = blockIdx.z;
     const int64_t p0 = (int64_t)blockIdx.x * kScatterBlockPos;
     const int64_t p1 = min(a.T, p0 + kScatterBlockPos);
     const int s_first = find_seq(a.tab.cu_seq, a.tab.n_seq, p0);
     const int s_last = find_seq(a.tab.cu_seq, a.tab.n_seq, p1 - 1);
     const float* row = a.pooled + ((int64_t)layer * a.h_kv + g) * a.T;
+    // thread t owns kScatterPerThread consecutive positions
+    const int64_t t0 = p0 + (int64_t)threadIdx.x * kScatterPerThread;
+    uint32_t key[kScatterPerThread];
+#pragma unroll
+    for (int e = 0; e < kScatterPerThread; ++e) key[e] = (t0 + e < p1) ? sortable_key(row[t0 + e]) : 0u;
+
     for (int s = s_first; s <= s_last; ++s) {  // almost always a single sequence
         uint32_t* hist = a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride;
         const uint32_t B = (uint32_t)(a.tab.cu_bud[s + 1] - a.tab.cu_bud[s]);
         const int Ls = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
         pick_bin<kScatterThreads, kHistBins / kScatterThreads>(hist, kHistBins, B, tmp, res);
         const uint32_t b1 = res[0];
-        __syncthreads();
         const int64_t q0 = max(p0, (int64_t)a.tab.cu_seq[s]), q1 = min(p1, (int64_t)a.tab.cu_seq[s + 1]);
+        uint32_t n_s = 0, n_c = 0;
+#pragma unroll
+        for (int e = 0; e < kScatterPerThread; ++e) {
+            const bool in = t0 + e >= q0 && t0 + e < q1;
+            n_s += in && (key[e] >> 21) > b1;
+            n_c += in && (key[e] >> 21) == b1;
+        }
+        // one pair of global atomics per block: prefix sums inside the block, then a block base
+        uint32_t total;
+        const uint32_t packed = n_s | (n_c << 16);  // at most 4096 per field
+        const uint32_t excl = block_scan_incl<kScatterThreads>(packed, tmp, &total) - packed;
+        if (threadIdx.x == 0) {
+            base[0] = (total & 0xFFFFu) ? atomicAdd(hist + kHistBins, total & 0xFFFFu) : 0u;
+            base[1] = (total >> 16) ? atomicAdd(hist + kHistBins + 1, total >> 16) : 0u;
+        }
+        __syncthreads();
+        uint32_t slot_s = base[0] + (excl & 0xFFFFu), slot_c = base[1] + (excl >> 16);
         int32_t* sure = a.sure + ((int64_t)layer * a.h_kv + g) * a.TB + a.tab.cu_bud[s];
         uint2* cand = a.cand + ((int64_t)layer * a.h_kv + g) * a.T + a.tab.cu_seq[s];
-#pragma unroll 4
+#pragma unroll
         for (int e = 0; e < kScatterPerThread; ++e) {
-            const int64_t p = p0 + e * kScatterThreads + threadIdx.x;
-            const bool in = p >= q0 && p < q1;
-            const uint32_t k = in ? sortable_key(row[p]) : 0u;
-            const uint32_t bin = k >> 21;
-            const int j = (int)(p - a.tab.cu_seq[s]);
-            const int slot_s = wave_append(in && bin > b1, hist + kHistBins);
-            if (slot_s >= 0 && (uint32_t)slot_s < B) sure[slot_s] = j;
-            const int slot_c = wave_append(in && bin == b1, hist + kHistBins + 1);
-            if (slot_c >= 0 && slot_c < Ls) cand[slot_c] = make_uint2(k, (uint32_t)j);
+            const bool in = t0 + e >= q0 && t0 + e < q1;
+            const uint32_t bin = key[e] >> 21;
+            const uint32_t j = (uint32_t)(t0 + e - a.tab.cu_seq[s]);
+            if (in && bin > b1) { if (slot_s < B) sure[slot_s] = (int32_t)j; ++slot_s; }
+            if (in && bin == b1) { if (slot_c < (uint32_t)Ls) cand[slot_c] = make_uint2(key[e], j); ++slot_c; }
         }
         __syncthreads();
     }
@@ -263,8 +270,22 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_finalize_kernel(Sele
     }
     uint32_t need = p.B - n_sure;  // >= 1: the threshold bin always contributes
 
+    // The candidate list is read from global memory once: each thread keeps up to kCache of its
+    // entries in registers; anything beyond (rare: huge tie groups) is re-read in every pass.
+    constexpr int kCache = 8;
+    uint2 cc[kCache];
+#pragma unroll
+    for (int e = 0; e < kCache; ++e) {
+        const uint32_t i = threadIdx.x + e * kSelectThreads;
+        cc[e] = i < n_cand ? cand[i] : make_uint2(0u, 0xFFFFFFFFu);  // position 0xFFFFFFFF marks "none"
+    }
+    const uint32_t spill0 = kCache * kSelectThreads;
+
     // level 2 on the candidates
-    for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) atomicAdd(&bins[(cand[i].x >> 10) & 2047u], 1u);
+#pragma unroll
+    for (int e = 0; e < kCache; ++e)
+        if (cc[e].y != 0xFFFFFFFFu) atomicAdd(&bins[(cc[e].x >> 10) & 2047u], 1u);
+    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kSelectThreads) atomicAdd(&bins[(cand[i].x >> 10) & 2047u], 1u);
     __syncthreads();
     pick_bin<kSelectThreads, 2>(bins, 2048, need, tmp, res);
     const uint32_t b2 = res[0];
@@ -273,7 +294,10 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_finalize_kernel(Sele
     // level 3
     for (int b = threadIdx.x; b < 1024; b += kSelectThreads) bins[b] = 0;
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) {
+#pragma unroll
+    for (int e = 0; e < kCache; ++e)
+        if (cc[e].y != 0xFFFFFFFFu && ((cc[e].x >> 10) & 2047u) == b2) atomicAdd(&bins[cc[e].x & 1023u], 1u);
+    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kSelectThreads) {
         const uint32_t k = cand[i].x;
         if (((k >> 10) & 2047u) == b2) atomicAdd(&bins[k & 1023u], 1u);
     }
@@ -283,14 +307,16 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_finalize_kernel(Sele
     need -= res[1];  // how many positions with key == tau are kept
     __syncthreads();
 
-    for (uint32_t i = threadIdx.x; i < n_cand; i += kSelectThreads) {
-        const uint2 c = cand[i];
+    auto classify = [&](uint2 c) {
         const uint32_t k21 = c.x & 0x1FFFFFu;
         if (c.y < (uint32_t)p.L) {
             if (k21 > low21) atomicOr(&keep[c.y >> 5], 1u << (c.y & 31));
             else if (k21 == low21) atomicOr(&ties[c.y >> 5], 1u << (c.y & 31));
         }
-    }
+    };
+#pragma unroll
+    for (int e = 0; e < kCache; ++e) classify(cc[e]);
+    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kSelectThreads) classify(cand[i]);
     __syncthreads();
 
     // thread t owns a contiguous run of words, so thread order is position order
@@ -341,18 +367,18 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     int words_cap = (max_len + 31) / 32;
     const size_t lds_bytes = ((size_t)kFinalizeFixedWords + 2 * (size_t)words_cap) * sizeof(uint32_t);
     if (lds_bytes > kMaxLds - 1024)  // bitmaps do not fit: stream instead
-        return launch_kernel(jq_select_stream_kernel, dim3(n_prob), dim3(kSelectThreads), st, a);
+        return launch_kernel(jq_select_stream_kernel, dim3(n_prob), dim3(kSelectThreads), 0, st, p.marks, kTrFinalize, a);
 
     dim3 grid((unsigned)((p.T + kScatterBlockPos - 1) / kScatterBlockPos), p.h_kv, p.n_layers);
-    hipError_t e = launch_kernel(jq_select_scatter_kernel, grid, dim3(kScatterThreads), st, a);
+    hipError_t e = launch_kernel(jq_select_scatter_kernel, grid, dim3(kScatterThreads), 0, st, p.marks, kTrScatter, a);
     if (e != hipSuccess) return e;
     if (lds_bytes > 64 * 1024) {
         e = hipFuncSetAttribute((const void*)jq_select_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
-    void* args[] = {(void*)&a, (void*)&words_cap};
-    return hipLaunchKernel((const void*)jq_select_finalize_kernel, dim3(n_prob), dim3(kSelectThreads), args, lds_bytes, st);
+    return launch_kernel(jq_select_finalize_kernel, dim3(n_prob), dim3(kSelectThreads), lds_bytes, st, p.marks, kTrFinalize, a,
+                         words_cap);
 }
 
 }  // namespace jq
