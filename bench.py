@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--buffers", type=int, default=4, help="distinct K/V sets rotated over")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--trace-steps", type=int, default=50)
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="only run the plain 256 MiB copy kernel a few times (reference for profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path needs no communication); use --gpus 1", file=sys.stderr)
@@ -59,6 +61,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.probe_copy:
+        src = torch.randint(0, 255, (256 << 20,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            jq.copy_probe(src, dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "jq_copy_probe_kernel", "bytes_read": src.numel(), "bytes_written": src.numel(), "launches": 10}))
+        return
     w = make_workload(args.config, budget=args.budget)
     if w.n_layers > 1:
         w.n_layers = min(w.n_layers, 8)  # keep host generation bounded; per-layer work is identical
@@ -128,8 +138,15 @@ def main():
                   "jq_score_kernel": (ab["K"] + ab["Q"] + ab["scores"] // 2) * w.n_layers}
     dom = max(pass_bytes, key=lambda k: kernels_us[k])
     achieved = pass_bytes[dom] / (kernels_us[dom] * 1e-6) / 1e9
+    # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc summary (calibrated FETCH_SIZE + WRITE_SIZE)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "jq_evict_hbm_traffic_%s.json" % w.name)
+    if os.path.exists(tpath) and w.n_layers == 1:
+        rec = json.load(open(tpath)).get("kernels", {}).get(dom)
+        if rec:
+            traffic = rec["read_bytes"] + rec["written_bytes"]
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": pass_bytes[dom], "us_per_launch": kernels_us[dom]}
 
     out = {

@@ -137,6 +137,11 @@ int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const v
                     void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
                     void* ws, size_t ws_bytes, void* stream, void* const* marks, int n_marks);
 
+/* Measurement aid, not part of the method: a plain device-to-device copy kernel of
+ * `bytes` bytes (a multiple of 16; 16-byte aligned, non-overlapping DEVICE buffers).
+ * Profilers read its known traffic to calibrate their HBM byte counters. */
+int jq_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Static, never-NULL description of a status code. */
 const char* jq_status_string(int status);
 

@@ -22,7 +22,7 @@ JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
 EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced",
-           "jq_status_string")
+           "jq_copy_probe", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_combine_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel",
                  "jq_select_finalize_kernel", "jq_compact_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
@@ -61,6 +61,7 @@ def lib() -> ctypes.CDLL:
         L.jq_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp]
         L.jq_evict.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_traced.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp), ctypes.c_int]
+        L.jq_copy_probe.argtypes = [vp, vp, sz, vp]
         L.jq_status_string.argtypes = [ctypes.c_int]
         L.jq_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -207,3 +208,10 @@ def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_ou
     _check(lib().jq_evict(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(idx_out),
                           _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict")
     return K_out, V_out, idx_out, scores_out
+
+
+def copy_probe(src, dst, stream=None):
+    """Plain copy of src into dst (same byte size): the known-size kernel used to calibrate traffic counters."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().jq_copy_probe(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "jq_copy_probe")
+    return dst

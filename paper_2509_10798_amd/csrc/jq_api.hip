@@ -246,6 +246,14 @@ int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const v
     return evict_impl(shape, Q, K, V, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, marks);
 }
 
+int jq_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst) return JQ_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return JQ_ERR_SHAPE;
+    if (misaligned(src, 16) || misaligned(dst, 16)) return JQ_ERR_UNSUPPORTED;
+    if (overlaps(src, bytes, dst, bytes)) return JQ_ERR_ALIAS;
+    return launch_status(launch_copy_probe(src, dst, bytes, (hipStream_t)stream));
+}
+
 const char* jq_status_string(int status) {
     switch (status) {
         case JQ_OK: return "ok";

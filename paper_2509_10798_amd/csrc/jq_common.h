@@ -87,4 +87,6 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
                           hipStream_t st);
 
+hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
+
 }  // namespace jq

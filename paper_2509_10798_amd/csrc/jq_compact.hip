@@ -53,4 +53,20 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
                          dim3(kCompactThreads), 0, st, p.marks, kTrCompact, a);
 }
 
+// Plain streaming copy, 16 bytes per lane: the known-size reference against which hardware traffic
+// counters are calibrated.
+__global__ __launch_bounds__(256) void jq_copy_probe_kernel(const u32x4* src, u32x4* dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st) {
+    const size_t n16 = bytes / 16;
+    const size_t want = (n16 + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 256 * 64 ? want : 256 * 64);
+    return launch_kernel(jq_copy_probe_kernel, dim3(blocks), dim3(256), 0, st, nullptr, -1, (const u32x4*)src, (u32x4*)dst,
+                         n16);
+}
+
 }  // namespace jq
