@@ -4,18 +4,20 @@
 //
 //   pooled[l,g,t] = (1/k) * sum_{|u| <= (k-1)/2} scores[l,g,t+u],  zero outside t's own sequence.
 //
-// Memory-bound and tiny next to the K passes.  Device-scope atomics are the expensive part on a
-// multi-die GPU, so blocks are large (8192 positions) and flush one LDS histogram each.  A block stages its span plus halo in LDS (zeros
+// Memory-bound and tiny next to the K passes.  A block stages its span plus halo in LDS (zeros
 // where the sequence ends), so every score is fetched from global memory once; blocks that
 // straddle two sequences, or kernels wider than the staged halo, take a direct per-thread path.
 #include "jq_common.h"
 
 namespace jq {
 
-constexpr int kPoolThreads = 1024;  // big blocks: few device-scope atomics per histogram bin
+constexpr int kPoolThreads = 256;
 constexpr int kPoolPerThread = 8;
-constexpr int kPoolBlockPos = kPoolThreads * kPoolPerThread;
-constexpr int kPoolMaxHalo = 32;  // (pool_k - 1) / 2 up to here uses the LDS path
+constexpr int kPoolBlockPos = kPoolThreads * kPoolPerThread;  // 2048 positions per block
+constexpr int kPoolMaxHalo = 32;                               // (pool_k - 1) / 2 up to here uses the LDS path
+constexpr int kWinBins = 128;                                  // histogram window below the block's top bin
+constexpr int kWinCopies = 16;
+constexpr int kWinStride = kWinBins + 1;                       // +1: copies of one bin fall into different banks
 
 struct PoolArgs {
     const float* in;   // [n_layers][h_kv][T]
@@ -27,24 +29,15 @@ struct PoolArgs {
     SeqTab tab;
 };
 
-// Neighbouring scores mostly share a bin: count each distinct bin of the wave once instead of
-// letting 64 lanes serialise on the same LDS word.  Must be called by all 64 lanes (pass
-// `active` = false for lanes without an element).
-__device__ __forceinline__ void wave_hist_add(uint32_t* bins, uint32_t bin, bool active) {
-    const int lane = threadIdx.x & 63;
-    uint64_t todo = __ballot(active);
-    while (todo) {
-        const int leader = __ffsll((unsigned long long)todo) - 1;
-        const uint32_t lb = __shfl(bin, leader);
-        const uint64_t same = __ballot(active && bin == lb);
-        if (lane == leader) atomicAdd(&bins[lb], (uint32_t)__popcll(same));
-        todo &= ~same;
-    }
-}
-
-template <bool POOL>
+// Histogram of the block's values.  Neighbouring scores crowd into a few bins, which would serialise
+// LDS atomics on one word; so the 128 bins below the block's highest bin are kept in 16 interleaved
+// copies (lane & 15 picks the copy), everything lower goes to one plain 2048-bin array.  Both are
+// merged into the problem's global histogram with one device-scope atomic per non-empty bin.
+template <bool POOL, int K>  // K: pool_k known at compile time (taps unrolled), or 0 for any
 __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
-    __shared__ uint32_t bins[kHistBins];
+    __shared__ uint32_t full[kHistBins];
+    __shared__ uint32_t win[kWinCopies * kWinStride];
+    __shared__ uint32_t wave_max[kPoolThreads / 64];
     __shared__ float tile[POOL ? kPoolBlockPos + 2 * kPoolMaxHalo : 1];
     const int g = blockIdx.y, layer = blockIdx.z;
     const int64_t row = ((int64_t)layer * a.h_kv + g) * a.T;
@@ -55,10 +48,11 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
     const int s_last = find_seq(a.tab.cu_seq, a.tab.n_seq, p1 - 1);
     const bool one_seq = (s_first == s_last);  // uniform over the block
     const bool do_hist = a.hist != nullptr;
-    const int r = (a.pool_k - 1) / 2;
+    const int r = K ? (K - 1) / 2 : (a.pool_k - 1) / 2;
     const bool staged = POOL && one_seq && r <= kPoolMaxHalo;  // uniform
     if (do_hist && one_seq) {
-        for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) bins[b] = 0;
+        for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) full[b] = 0;
+        for (int b = threadIdx.x; b < kWinCopies * kWinStride; b += kPoolThreads) win[b] = 0;
     }
     if (staged) {
         const int64_t lo = a.tab.cu_seq[s_first], hi = a.tab.cu_seq[s_first + 1];
@@ -69,6 +63,8 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
         }
     }
     __syncthreads();
+    uint32_t bin[kPoolPerThread];
+    uint32_t top = 0;
 #pragma unroll
     for (int e = 0; e < kPoolPerThread; ++e) {
         const int j = e * kPoolThreads + threadIdx.x;
@@ -82,7 +78,12 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
                 if (!one_seq) s = find_seq(a.tab.cu_seq, a.tab.n_seq, p);
             } else if (staged) {
                 float acc = 0.f;
-                for (int u = 0; u <= 2 * r; ++u) acc += tile[j + u];  // ascending position order
+                if (K) {
+#pragma unroll
+                    for (int u = 0; u < K; ++u) acc += tile[j + u];
+                } else {
+                    for (int u = 0; u <= 2 * r; ++u) acc += tile[j + u];  // ascending position order
+                }
                 v = acc * a.inv_k;
                 a.out[row + p] = v;
             } else {
@@ -95,19 +96,38 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
                 a.out[row + p] = v;
             }
         }
-        if (do_hist) {  // uniform
-            const uint32_t bin = sortable_key(v) >> 21;
-            if (one_seq) wave_hist_add(bins, bin, in);  // uniform branch, all lanes take part
-            else if (in) atomicAdd(a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride + bin, 1u);
-        }
+        bin[e] = in ? (sortable_key(v) >> 21) : 0xFFFFFFFFu;  // 0xFFFFFFFF: no element
+        if (in) top = max(top, bin[e]);
+        if (do_hist && !one_seq && in)  // block straddles two sequences (rare): straight to global memory
+            atomicAdd(a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride + bin[e], 1u);
     }
-    if (do_hist && one_seq) {
-        __syncthreads();
-        uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s_first) * a.h_kv + g) * kHistStride;
-        for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) {
-            const uint32_t c = bins[b];
-            if (c) atomicAdd(gh + b, c);
-        }
+    if (!(do_hist && one_seq)) return;  // uniform
+
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) top = max(top, (uint32_t)__shfl_xor((int)top, d));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = top;
+    __syncthreads();
+#pragma unroll
+    for (int wv = 0; wv < kPoolThreads / 64; ++wv) top = max(top, wave_max[wv]);
+    const uint32_t base = top >= kWinBins - 1 ? top - (kWinBins - 1) : 0u;  // window = [base, base + 127]
+    uint32_t* my = win + (threadIdx.x & (kWinCopies - 1)) * kWinStride;
+#pragma unroll
+    for (int e = 0; e < kPoolPerThread; ++e) {
+        if (bin[e] == 0xFFFFFFFFu) continue;
+        if (bin[e] >= base) atomicAdd(&my[bin[e] - base], 1u);
+        else atomicAdd(&full[bin[e]], 1u);
+    }
+    __syncthreads();
+    uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s_first) * a.h_kv + g) * kHistStride;
+    if (threadIdx.x < kWinBins) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int k = 0; k < kWinCopies; ++k) c += win[k * kWinStride + threadIdx.x];
+        if (c) atomicAdd(gh + base + threadIdx.x, c);
+    }
+    for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) {
+        const uint32_t c = full[b];
+        if (c) atomicAdd(gh + b, c);
     }
 }
 
@@ -130,13 +150,14 @@ static PoolArgs make_args(const Plan& p, const float* in, float* out, uint32_t* 
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st) {
     const PoolArgs a = make_args(p, scores, pooled, hist_or_null);
     dim3 grid((unsigned)((p.T + kPoolBlockPos - 1) / kPoolBlockPos), p.h_kv, p.n_layers);
-    return launch_kernel(jq_pool_kernel<true>, grid, dim3(kPoolThreads), 0, st, p.marks, kTrPool, a);
+    if (p.pool_k == 7) return launch_kernel(jq_pool_kernel<true, 7>, grid, dim3(kPoolThreads), 0, st, p.marks, kTrPool, a);
+    return launch_kernel(jq_pool_kernel<true, 0>, grid, dim3(kPoolThreads), 0, st, p.marks, kTrPool, a);
 }
 
 hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st) {
     const PoolArgs a = make_args(p, pooled, nullptr, hist);
     dim3 grid((unsigned)((p.T + kPoolBlockPos - 1) / kPoolBlockPos), p.h_kv, p.n_layers);
-    return launch_kernel(jq_pool_kernel<false>, grid, dim3(kPoolThreads), 0, st, nullptr, -1, a);
+    return launch_kernel(jq_pool_kernel<false, 0>, grid, dim3(kPoolThreads), 0, st, nullptr, -1, a);
 }
 
 hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st) {

@@ -193,14 +193,22 @@ __device__ __forceinline__ KeyStream key_stream(const ScoreArgs& a, const WaveIt
 // One 32-key tile against the wave's query rows: rows of the MFMA result are keys, columns are
 // query rows, so each lane updates the running (m, Z) of its own query column from its 16 keys.
 // MASKED is only used for the last, partial tile of a sequence (keys >= valid do not exist).
+__device__ __forceinline__ f32x16 stats_chain(const bf16x8 (&kf)[8], const bf16x8 (&q)[8]) {
+    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k8 = 0; k8 < 8; ++k8) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k8], q[k8], acc, 0, 0, 0);
+    return acc;
+}
+
 template <int NQT, bool MASKED>
 __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (&qf)[NQT][8], float (&m)[NQT],
                                            float (&z)[NQT], float c, int valid, int half) {
+    // software pipeline: the MFMA chain of query tile qt+1 is interleaved with the max/exp2/add work of tile qt
+    f32x16 acc = stats_chain(kf, qf[0]);
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
-        f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int k8 = 0; k8 < 8; ++k8) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[k8], qf[qt][k8], acc, 0, 0, 0);
+        f32x16 nxt = acc;
+        if (qt + 1 < NQT) nxt = stats_chain(kf, qf[qt + 1]);
         if (MASKED) {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
@@ -223,7 +231,15 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
         }
         z[qt] = z[qt] * __builtin_amdgcn_exp2f(m[qt] - mnew) + ((s0 + s1) + (s2 + s3));
         m[qt] = mnew;
-        __builtin_amdgcn_sched_barrier(0);  // one live accumulator tile at a time (register budget)
+        if (qt + 1 < NQT) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);  // then a few VALU
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        acc = nxt;
     }
 }
 
@@ -311,11 +327,19 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
     const float2* p = a.stats + (((int64_t)layer * a.n_chunks + c0) * a.h_kv + g) * a.RP + row;
     const int64_t step = (int64_t)a.h_kv * a.RP;
     float M = -1.0e30f, Z = 0.f;
-    for (int k = kl; k < c1 - c0; k += kCombineLanes) {
-        const float2 mz = p[k * step];
-        const float mm = fmaxf(M, mz.x);
-        Z = Z * __builtin_amdgcn_exp2f(M - mm) + mz.y * __builtin_amdgcn_exp2f(mz.x - mm);
-        M = mm;
+    for (int k0 = kl; k0 < c1 - c0; k0 += 8 * kCombineLanes) {  // 8 independent loads in flight per thread
+        float2 mz[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + u * kCombineLanes;
+            mz[u] = k < c1 - c0 ? p[k * step] : make_float2(-1.0e30f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float mm = fmaxf(M, mz[u].x);
+            Z = Z * __builtin_amdgcn_exp2f(M - mm) + mz[u].y * __builtin_amdgcn_exp2f(mz[u].x - mm);
+            M = mm;
+        }
     }
     part[kl][r] = make_float2(M, Z);
     __syncthreads();
@@ -339,6 +363,14 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
 // ------------------------------------------------------------------------------------------------
 // pass 2: normalised probabilities summed over the query rows
 // ------------------------------------------------------------------------------------------------
+// q.k - beta/c for one tile of 32 query rows against the 32 keys in `kf` (rows = query rows, columns = keys).
+__device__ __forceinline__ f32x16 score_chain(const bf16x8 (&q)[8], bf16x8 qaug, const bf16x8 (&kf)[8], bf16x8 ones) {
+    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k8 = 0; k8 < 8; ++k8) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[k8], kf[k8], acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(qaug, ones, acc, 0, 0, 0);  // - beta_r / c
+}
+
 template <int NQT>
 __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
@@ -391,14 +423,15 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
             fetch_tile(ks.rsrc, slots + (t & 1) * kSlotBytes, (uint32_t)(t + 2) * kKeyTile * ks.row_bytes, ks.row_bytes,
                        ks.n_keys - (t + 2) * kKeyTile, tl, lane);
         }
+        // Software pipeline over the query-row tiles: the MFMA chain of tile qt+1 is issued between the
+        // exp2/add instructions of tile qt (a wave issues in order, so without interleaving its VALU work
+        // would sit behind the whole dependent MFMA chain).
         float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        f32x16 acc = score_chain(qf[0], qaug[0], kf, ones);
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
-            f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int k8 = 0; k8 < 8; ++k8)  // rows = query rows, columns = keys
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[qt][k8], kf[k8], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qaug[qt], ones, acc, 0, 0, 0);  // - beta_r / c
+            f32x16 nxt = acc;
+            if (qt + 1 < NQT) nxt = score_chain(qf[qt + 1], qaug[qt + 1], kf, ones);
 #pragma unroll
             for (int v = 0; v < 16; v += 4) {
                 s0 += __builtin_amdgcn_exp2f(acc[v + 0] * c);
@@ -406,7 +439,15 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
                 s2 += __builtin_amdgcn_exp2f(acc[v + 2] * c);
                 s3 += __builtin_amdgcn_exp2f(acc[v + 3] * c);
             }
-            __builtin_amdgcn_sched_barrier(0);  // one live accumulator tile at a time (register budget)
+            if (qt + 1 < NQT) {
+#pragma unroll
+                for (int i = 0; i < 9; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // then a few VALU
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            acc = nxt;
         }
         float s = (s0 + s1) + (s2 + s3);
         s += __shfl_xor(s, 32);  // the two lane halves hold complementary query rows of the same key

@@ -61,7 +61,8 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* tmp, u
 }
 
 // bins[0..n_bins): find the bin b with (#elements in bins > b) < need <= (#elements in bins >= b).
-// Thread t owns PER consecutive bins, highest bins first.  result[0] = b, result[1] = #elements above.
+// Thread t owns PER consecutive bins, highest bins first.  result[0] = b, result[1] = #elements above,
+// result[2] = #elements inside b.
 template <int THREADS, int PER, typename BinPtr>
 __device__ __forceinline__ void pick_bin(BinPtr bins, int n_bins, uint32_t need, uint32_t* tmp, uint32_t* result) {
     uint32_t c[PER];
@@ -80,6 +81,7 @@ __device__ __forceinline__ void pick_bin(BinPtr bins, int n_bins, uint32_t need,
         if (before < need && need <= before + c[e]) {
             result[0] = (uint32_t)(n_bins - 1 - (PER * (int)threadIdx.x + e));
             result[1] = before;
+            result[2] = c[e];
         }
         before += c[e];
     }
@@ -113,7 +115,7 @@ __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
 __global__ __launch_bounds__(kSelectThreads) void jq_select_stream_kernel(SelectArgs a) {
     __shared__ uint32_t bins[kHistBins];
     __shared__ uint32_t tmp[kSelectThreads / 64 + 1];
-    __shared__ uint32_t res[2];
+    __shared__ uint32_t res[4];
     const Problem p = problem_of(a, blockIdx.x);
     const float* x = p.x;
     const int L = p.L;
@@ -191,7 +193,7 @@ constexpr int kScatterBlockPos = kScatterThreads * kScatterPerThread;
 
 __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(SelectArgs a) {
     __shared__ uint32_t tmp[kScatterThreads / 64 + 1];
-    __shared__ uint32_t res[2];
+    __shared__ uint32_t res[4];
     __shared__ uint32_t base[2];
     const int g = blockIdx.y, layer = blockIdx.z;
     const int64_t p0 = (int64_t)blockIdx.x * kScatterBlockPos;
@@ -246,11 +248,15 @@ __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(Sele
 // ------------------------------------------------------------------------------------------------
 // fast path, step 2: resolve the candidates and emit ascending positions
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSelectThreads) void jq_select_finalize_kernel(SelectArgs a, int words_cap) {
+constexpr int kFinThreads = 512;
+constexpr int kFinCache = 16;  // candidates a thread keeps in registers (8192 per block)
+
+__global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectArgs a, int words_cap) {
     extern __shared__ uint32_t lds[];
-    uint32_t* bins = lds;                         // kHistBins
-    uint32_t* tmp = bins + kHistBins;             // kSelectThreads / 64 + 1 (padded to 32)
-    uint32_t* res = tmp + 32;                     // 2 (padded to 32)
+    uint32_t* bins2 = lds;                        // 2048: level-2 histogram
+    uint32_t* bins3 = bins2 + 2048;               // 1024: level-3 histogram
+    uint32_t* tmp = bins3 + 1024;                 // scan scratch (padded to 32)
+    uint32_t* res = tmp + 32;                     // pick results (padded to 32)
     uint32_t* keep = res + 32;                    // words_cap: bitmap of kept positions
     uint32_t* ties = keep + words_cap;            // words_cap: bitmap of positions with key == tau
 
@@ -261,86 +267,100 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_finalize_kernel(Sele
     const int32_t* sure = a.sure + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
     const uint2* cand = a.cand + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s];
 
-    for (int w = threadIdx.x; w < words; w += kSelectThreads) { keep[w] = 0; ties[w] = 0; }
-    for (int b = threadIdx.x; b < kHistBins; b += kSelectThreads) bins[b] = 0;
+    // The candidate list is read from global memory once: each thread keeps up to kFinCache entries in
+    // registers; anything beyond (huge tie groups) is re-read in every pass.
+    uint2 cc[kFinCache];
+#pragma unroll
+    for (int e = 0; e < kFinCache; ++e) {
+        // loaded before the counter is known (the list's storage spans L entries, so this stays in bounds)
+        const uint32_t i = threadIdx.x + e * kFinThreads;
+        cc[e] = i < (uint32_t)p.L ? cand[i] : make_uint2(0u, 0xFFFFFFFFu);
+    }
+#pragma unroll
+    for (int e = 0; e < kFinCache; ++e)
+        if (threadIdx.x + e * kFinThreads >= n_cand) cc[e].y = 0xFFFFFFFFu;  // position 0xFFFFFFFF marks "none"
+    const uint32_t spill0 = kFinCache * kFinThreads;
+
+    for (int w = threadIdx.x; w < words; w += kFinThreads) { keep[w] = 0; ties[w] = 0; }
+    for (int b = threadIdx.x; b < 3072; b += kFinThreads) bins2[b] = 0;  // both histograms
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < n_sure; i += kSelectThreads) {
+
+    for (uint32_t i = threadIdx.x; i < n_sure; i += kFinThreads) {
         const uint32_t j = (uint32_t)sure[i];
         if (j < (uint32_t)p.L) atomicOr(&keep[j >> 5], 1u << (j & 31));
     }
     uint32_t need = p.B - n_sure;  // >= 1: the threshold bin always contributes
 
-    // The candidate list is read from global memory once: each thread keeps up to kCache of its
-    // entries in registers; anything beyond (rare: huge tie groups) is re-read in every pass.
-    constexpr int kCache = 8;
-    uint2 cc[kCache];
-#pragma unroll
-    for (int e = 0; e < kCache; ++e) {
-        const uint32_t i = threadIdx.x + e * kSelectThreads;
-        cc[e] = i < n_cand ? cand[i] : make_uint2(0u, 0xFFFFFFFFu);  // position 0xFFFFFFFF marks "none"
-    }
-    const uint32_t spill0 = kCache * kSelectThreads;
-
     // level 2 on the candidates
 #pragma unroll
-    for (int e = 0; e < kCache; ++e)
-        if (cc[e].y != 0xFFFFFFFFu) atomicAdd(&bins[(cc[e].x >> 10) & 2047u], 1u);
-    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kSelectThreads) atomicAdd(&bins[(cand[i].x >> 10) & 2047u], 1u);
+    for (int e = 0; e < kFinCache; ++e)
+        if (cc[e].y != 0xFFFFFFFFu) atomicAdd(&bins2[(cc[e].x >> 10) & 2047u], 1u);
+    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kFinThreads) atomicAdd(&bins2[(cand[i].x >> 10) & 2047u], 1u);
     __syncthreads();
-    pick_bin<kSelectThreads, 2>(bins, 2048, need, tmp, res);
+    pick_bin<kFinThreads, 2048 / kFinThreads>(bins2, 2048, need, tmp, res);
     const uint32_t b2 = res[0];
     need -= res[1];
-    __syncthreads();
     // level 3
-    for (int b = threadIdx.x; b < 1024; b += kSelectThreads) bins[b] = 0;
-    __syncthreads();
 #pragma unroll
-    for (int e = 0; e < kCache; ++e)
-        if (cc[e].y != 0xFFFFFFFFu && ((cc[e].x >> 10) & 2047u) == b2) atomicAdd(&bins[cc[e].x & 1023u], 1u);
-    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kSelectThreads) {
+    for (int e = 0; e < kFinCache; ++e)
+        if (cc[e].y != 0xFFFFFFFFu && ((cc[e].x >> 10) & 2047u) == b2) atomicAdd(&bins3[cc[e].x & 1023u], 1u);
+    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kFinThreads) {
         const uint32_t k = cand[i].x;
-        if (((k >> 10) & 2047u) == b2) atomicAdd(&bins[k & 1023u], 1u);
+        if (((k >> 10) & 2047u) == b2) atomicAdd(&bins3[k & 1023u], 1u);
     }
     __syncthreads();
-    pick_bin<kSelectThreads, 1>(bins, 1024, need, tmp, res);
-    const uint32_t low21 = (b2 << 10) | res[0];
-    need -= res[1];  // how many positions with key == tau are kept
-    __syncthreads();
+    pick_bin<kFinThreads, 1024 / kFinThreads>(bins3, 1024, need, tmp, res + 4);
+    const uint32_t low21 = (b2 << 10) | res[4];
+    need -= res[5];                                   // how many positions with key == tau are kept
+    const bool all_ties = (need == res[6]);           // uniform: the whole tie group is kept (the usual case)
 
     auto classify = [&](uint2 c) {
         const uint32_t k21 = c.x & 0x1FFFFFu;
         if (c.y < (uint32_t)p.L) {
-            if (k21 > low21) atomicOr(&keep[c.y >> 5], 1u << (c.y & 31));
+            if (k21 > low21 || (all_ties && k21 == low21)) atomicOr(&keep[c.y >> 5], 1u << (c.y & 31));
             else if (k21 == low21) atomicOr(&ties[c.y >> 5], 1u << (c.y & 31));
         }
     };
 #pragma unroll
-    for (int e = 0; e < kCache; ++e) classify(cc[e]);
-    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kSelectThreads) classify(cand[i]);
+    for (int e = 0; e < kFinCache; ++e) classify(cc[e]);
+    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kFinThreads) classify(cand[i]);
     __syncthreads();
 
     // thread t owns a contiguous run of words, so thread order is position order
-    const int wpt = (words + kSelectThreads - 1) / kSelectThreads;
+    const int wpt = (words + kFinThreads - 1) / kFinThreads;
     const int w0 = threadIdx.x * wpt, w1 = min(words, w0 + wpt);
-    uint32_t n_t = 0;
-    for (int w = w0; w < w1; ++w) n_t += __popc(ties[w]);
     uint32_t total;
-    uint32_t before = block_scan_incl<kSelectThreads>(n_t, tmp, &total) - n_t;
-    for (int w = w0; w < w1 && before < need; ++w) {  // the lowest `need` tie positions join the kept set
-        uint32_t t = ties[w];
-        const uint32_t cnt = __popc(t);
-        uint32_t take = min(cnt, need - before);
-        before += cnt;
-        uint32_t add = 0;
-        while (take--) { const uint32_t low = t & (0u - t); add |= low; t ^= low; }
-        keep[w] |= add;  // only this thread touches word w here
+    if (!all_ties) {  // the lowest `need` tie positions join the kept set
+        uint32_t n_t = 0;
+        for (int w = w0; w < w1; ++w) n_t += __popc(ties[w]);
+        uint32_t before = block_scan_incl<kFinThreads>(n_t, tmp, &total) - n_t;
+        for (int w = w0; w < w1 && before < need; ++w) {
+            uint32_t t = ties[w];
+            const uint32_t cnt = __popc(t);
+            uint32_t take = min(cnt, need - before);
+            before += cnt;
+            uint32_t add = 0;
+            while (take--) { const uint32_t low = t & (0u - t); add |= low; t ^= low; }
+            keep[w] |= add;  // only this thread touches word w here
+        }
+        __syncthreads();
     }
-    __syncthreads();
+    // Exclusive prefix of the kept count per 32-position word (thread t scans its run of words), then the
+    // words are dealt round-robin for emission: kept positions cluster (contiguous heavy-hitter spans), and a
+    // thread that owned a whole cluster would emit hundreds of positions alone.
     uint32_t n_k = 0;
     for (int w = w0; w < w1; ++w) n_k += __popc(keep[w]);
-    uint32_t slot = block_scan_incl<kSelectThreads>(n_k, tmp, &total) - n_k;
+    uint32_t run = block_scan_incl<kFinThreads>(n_k, tmp, &total) - n_k;
+    uint32_t* wpre = ties;  // the tie bitmap is dead by now
     for (int w = w0; w < w1; ++w) {
+        const uint32_t c = __popc(keep[w]);
+        wpre[w] = run;
+        run += c;
+    }
+    __syncthreads();
+    for (int w = threadIdx.x; w < words; w += kFinThreads) {
         uint32_t k = keep[w];
+        uint32_t slot = wpre[w];
         while (k) {
             const int bit = __ffs(k) - 1;
             k &= k - 1;
@@ -350,7 +370,7 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_finalize_kernel(Sele
     }
 }
 
-constexpr int kFinalizeFixedWords = kHistBins + 32 + 32;
+constexpr int kFinalizeFixedWords = 2048 + 1024 + 32 + 32;
 constexpr size_t kMaxLds = 160 * 1024;
 
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st) {
@@ -377,7 +397,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
                                 (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
-    return launch_kernel(jq_select_finalize_kernel, dim3(n_prob), dim3(kSelectThreads), lds_bytes, st, p.marks, kTrFinalize, a,
+    return launch_kernel(jq_select_finalize_kernel, dim3(n_prob), dim3(kFinThreads), lds_bytes, st, p.marks, kTrFinalize, a,
                          words_cap);
 }
 
