@@ -72,11 +72,11 @@ typedef enum jq_status {
 /* Problem description (host memory).  One call handles n_layers * n_seq
  * independent (layer, sequence) problems that share every other dimension. */
 typedef struct jq_shape {
-    int32_t n_layers;          /* >= 1                                                        */
+    int32_t n_layers;          /* 1..65535                                                    */
     int32_t n_seq;             /* 1..JQ_MAX_SEQ                                               */
     int32_t n_q;               /* soft tokens per sequence (the paper's n; 32 in its runs)    */
     int32_t h_q;               /* query heads                                                 */
-    int32_t h_kv;              /* KV heads; h_q % h_kv == 0                                   */
+    int32_t h_kv;              /* KV heads; h_q % h_kv == 0; at most 256                      */
     int32_t d;                 /* head dimension; only 128 is implemented                     */
     int32_t pool_k;            /* odd >= 1; 1 = no pooling                                    */
     float scale;               /* logit scale; 0 selects 1/sqrt(d); must be finite and >= 0   */

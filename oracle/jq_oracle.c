@@ -126,6 +126,42 @@ int jqo_score(int n_q, int h_q, int h_kv, int d, long L, double scale,
 }
 
 /*
+ * Importance scores as a slice of a wider softmax (Section 4.2, Eq. 1 and Eq. 3; Section 4.3).
+ *
+ * In the model's own prefill the soft tokens are appended after the prompt, so soft token i also
+ * attends to the soft tokens up to itself and its softmax normaliser covers more than the prompt
+ * keys.  Given that normaliser as lse[i,h] = log sum_{j in domain} exp(s[h,i,j]) (natural log, the
+ * value attention kernels keep), the attention the prompt key j receives is
+ *
+ *   p[h,i,j]   = exp(s[h,i,j] - lse[i,h])
+ *   score[g,j] = sum_{h in group g} sum_i p[h,i,j]
+ *
+ * With lse taken over the prompt keys alone this is jqo_score.  lse is [n_q, h_q] double.
+ */
+int jqo_score_lse(int n_q, int h_q, int h_kv, int d, long L, double scale, const uint16_t* Q, const uint16_t* K,
+                  const double* lse, double* score) {
+    if (n_q < 1 || h_q < 1 || h_kv < 1 || d < 1 || L < 1 || h_q % h_kv != 0 || !Q || !K || !lse || !score) return -1;
+    const int G = h_q / h_kv;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int g = 0; g < h_kv; ++g)
+        for (long j = 0; j < L; ++j) {
+            const uint16_t* k = K + ((size_t)j * h_kv + g) * d;
+            double total = 0.0;
+            for (int hh = 0; hh < G; ++hh)
+                for (int i = 0; i < n_q; ++i) {
+                    const int h = g * G + hh;
+                    const uint16_t* q = Q + ((size_t)i * h_q + h) * d;
+                    double acc = 0.0;
+                    for (int c = 0; c < d; ++c) acc += bf16_to_f64(q[c]) * bf16_to_f64(k[c]);
+                    total += exp(acc * scale - lse[(size_t)i * h_q + h]);
+                }
+            score[(size_t)g * L + j] = total;
+        }
+    return 0;
+}
+
+/*
  * 1-D average pooling of one head's scores ("pooling configurations",
  * Section 5.1 baselines paragraph).  Reading: stride 1, same-length output,
  * zeros outside [0, L), divisor always pool_k (so the first and last

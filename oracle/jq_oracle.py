@@ -36,10 +36,11 @@ def _load():
         u16p, f64p, i32p = (np.ctypeslib.ndpointer(dtype=t, flags="C_CONTIGUOUS") for t in (np.uint16, np.float64, np.int32))
         lib.jqo_num_threads.restype = ctypes.c_int
         lib.jqo_score.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p]
+        lib.jqo_score_lse.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p, f64p]
         lib.jqo_pool.argtypes = [ctypes.c_long, ctypes.c_int, f64p, f64p]
         lib.jqo_select_topk.argtypes = [ctypes.c_long, ctypes.c_long, f64p, i32p]
         lib.jqo_compact.argtypes = [ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_long, u16p, u16p, i32p, u16p, u16p]
-        for f in (lib.jqo_score, lib.jqo_pool, lib.jqo_select_topk, lib.jqo_compact):
+        for f in (lib.jqo_score, lib.jqo_score_lse, lib.jqo_pool, lib.jqo_select_topk, lib.jqo_compact):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -64,6 +65,20 @@ def score(Q: np.ndarray, K: np.ndarray, scale: float = 0.0) -> np.ndarray:
         raise ValueError("head dims differ")
     out = np.empty((h_kv, L), dtype=np.float64)
     _check(_load().jqo_score(n_q, h_q, h_kv, d, L, float(scale), Q, K, out), "score")
+    return out
+
+
+def score_lse(Q: np.ndarray, K: np.ndarray, lse: np.ndarray, scale: float = 0.0) -> np.ndarray:
+    """Scores as a slice of a wider softmax: lse [n_q, h_q] is the natural-log normaliser of each query row."""
+    Q = np.ascontiguousarray(Q, dtype=np.uint16)
+    K = np.ascontiguousarray(K, dtype=np.uint16)
+    lse = np.ascontiguousarray(lse, dtype=np.float64)
+    n_q, h_q, d = Q.shape
+    L, h_kv, d2 = K.shape
+    if d != d2 or lse.shape != (n_q, h_q):
+        raise ValueError("shape mismatch")
+    out = np.empty((h_kv, L), dtype=np.float64)
+    _check(_load().jqo_score_lse(n_q, h_q, h_kv, d, L, float(scale), Q, K, lse, out), "score_lse")
     return out
 
 
@@ -100,9 +115,11 @@ def compact(K: np.ndarray, V: np.ndarray, idx: np.ndarray):
     return Ko, Vo
 
 
-def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0):
-    """One (layer, sequence): score -> pool -> top-B -> gather.  Returns a dict."""
-    s = score(Q, K, scale)
+def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None):
+    """One (layer, sequence): score -> pool -> top-B -> gather.  Returns a dict.
+
+    With `lse` the scores are the slice-of-a-wider-softmax variant (score_lse)."""
+    s = score(Q, K, scale) if lse is None else score_lse(Q, K, lse, scale)
     p = pool(s, pool_k)
     idx = select_topk(p, B)
     Ko, Vo = compact(K, V, idx)

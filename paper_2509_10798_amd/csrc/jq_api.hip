@@ -29,7 +29,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     if (!std::isfinite(sh->scale) || sh->scale < 0.0f) return JQ_ERR_SHAPE;
     if (sh->n_seq > JQ_MAX_SEQ) return JQ_ERR_UNSUPPORTED;
     if (sh->d != kHeadDim) return JQ_ERR_UNSUPPORTED;
-    if (sh->n_layers > 65535 || sh->h_kv > 65535) return JQ_ERR_UNSUPPORTED;
+    if (sh->n_layers > 65535 || sh->h_kv > 256) return JQ_ERR_UNSUPPORTED;  // grid dimensions; 32-bit byte offsets inside a chunk
     if (sh->cu_seqlens[0] != 0) return JQ_ERR_SHAPE;
     for (int s = 0; s < sh->n_seq; ++s)
         if (sh->cu_seqlens[s + 1] <= sh->cu_seqlens[s]) return JQ_ERR_SHAPE;
@@ -70,7 +70,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     if (chunk > 1024) chunk = 1024;
     if (const char* env = std::getenv("JQ_CHUNK_KEYS")) {  // ablation knob
         const long v = std::atol(env);
-        if (v >= kKeyTile && v <= 65536 && v % kKeyTile == 0) chunk = v;
+        if (v >= kKeyTile && v <= 8192 && v % kKeyTile == 0) chunk = v;
     }
     p.chunk_keys = (int32_t)chunk;
     int64_t nc = 0;

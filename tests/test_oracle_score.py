@@ -160,3 +160,49 @@ def test_rejects_bad_shapes():
     Q = np.zeros((1, 3, 4), dtype=np.uint16); K = np.zeros((2, 2, 4), dtype=np.uint16)
     with pytest.raises(ValueError):
         oracle.score(Q, K)                                       # 3 % 2 != 0
+
+
+# ---------------------------------------------------------------- slice of a wider softmax (supplied lse)
+def numpy_logits(Q, K):
+    Qd, Kd = bf16_bits_to_f64(Q), bf16_bits_to_f64(K)
+    G = Q.shape[1] // K.shape[1]
+    return np.einsum("ihc,jhc->ihj", Qd, np.repeat(Kd, G, axis=1)) / math.sqrt(Q.shape[2])   # [n_q, h_q, L]
+
+
+def test_score_lse_hand_worked_with_one_extra_key():
+    # logits (1, 0, -1) over the prompt plus one soft-token key with logit 1/2 in the normaliser
+    q = bits([[[2, 0, 0, 0]]])
+    k = bits([[[1, 0, 0, 0]], [[0, 1, 0, 0]], [[-1, 0, 0, 0]]])
+    z = math.e + 1 + 1 / math.e + math.exp(0.5)
+    got = oracle.score_lse(q, k, np.array([[math.log(z)]]))
+    np.testing.assert_allclose(got[0], [math.e / z, 1 / z, 1 / (math.e * z)], rtol=1e-15)
+
+
+def test_score_lse_over_the_prompt_equals_score():
+    rng = np.random.default_rng(8)
+    Q, K = rand_bits(rng, (5, 4, 16)), rand_bits(rng, (77, 2, 16))
+    s = numpy_logits(Q, K)
+    m = s.max(axis=2)
+    lse = m + np.log(np.exp(s - m[..., None]).sum(axis=2))        # [n_q, h_q], independent numpy logsumexp
+    np.testing.assert_allclose(oracle.score_lse(Q, K, lse), oracle.score(Q, K), rtol=1e-12)
+
+
+def test_score_lse_wider_domain_scales_each_row():
+    # a causal soft-token tail adds mass to each row's normaliser: every row's contribution shrinks by
+    # Z_prompt / Z_all, checked against numpy with explicit soft-token keys
+    rng = np.random.default_rng(9)
+    n_q, h_q, h_kv, d, L = 4, 4, 2, 8, 21
+    Q, K, Ks = rand_bits(rng, (n_q, h_q, d)), rand_bits(rng, (L, h_kv, d)), rand_bits(rng, (n_q, h_kv, d))
+    s, st = numpy_logits(Q, K), numpy_logits(Q, Ks)                # [n_q,h_q,L], [n_q,h_q,n_q]
+    causal = np.tril(np.ones((n_q, n_q), dtype=bool))[:, None, :]  # soft token i sees soft keys 0..i
+    z_all = np.exp(s).sum(axis=2) + np.where(causal, np.exp(st), 0.0).sum(axis=2)
+    want = (np.exp(s) / z_all[..., None]).sum(axis=0).reshape(h_kv, h_q // h_kv, L).sum(axis=1)
+    got = oracle.score_lse(Q, K, np.log(z_all))
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+    assert (got.sum(axis=1) < n_q * (h_q // h_kv)).all()           # rows no longer sum to one
+
+
+def test_score_lse_rejects_wrong_lse_shape():
+    Q = np.zeros((2, 2, 4), dtype=np.uint16); K = np.zeros((3, 2, 4), dtype=np.uint16)
+    with pytest.raises(ValueError):
+        oracle.score_lse(Q, K, np.zeros((2, 3)))
