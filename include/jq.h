@@ -97,6 +97,17 @@ int jq_workspace_bytes(const jq_shape* shape, size_t* bytes);
 int jq_score(const jq_shape* shape, const void* Q, const void* K, float* scores,
              void* ws, size_t ws_bytes, void* stream);
 
+/* The same scores as a slice of a wider softmax, in ONE pass over K.  In the model's
+ * own prefill (Eq. 1: the soft tokens are concatenated after the prompt) soft token i
+ * also attends to the soft tokens up to itself, so the normaliser of its attention row
+ * covers more than the prompt keys; attention kernels keep it as a log-sum-exp.  Given
+ *   lse[l,s,i,h] = log sum_{j in the row's key domain} exp(scale * Q[l,s,i,h,:].K_j)
+ * (DEVICE, fp32, natural log, [n_layers, n_seq, n_q, h_q]) this computes
+ *   scores[l,g,t] = sum_{h in group g} sum_i exp(scale * Q[l,s,i,h,:].K[l,t,g,:] - lse[l,s,i,h]).
+ * With lse taken over the prompt keys alone the result equals jq_score. */
+int jq_score_lse(const jq_shape* shape, const void* Q, const void* K, const float* lse,
+                 float* scores, void* ws, size_t ws_bytes, void* stream);
+
 /* pooled[l,g,t] = (1/pool_k) * sum_{|u| <= (pool_k-1)/2} scores[l,g,t+u], taking
  * zero for positions outside t's own sequence (divisor is always pool_k).
  * `pooled` must not overlap `scores`. */
@@ -121,6 +132,11 @@ int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_
 int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V,
              void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
              void* ws, size_t ws_bytes, void* stream);
+
+/* jq_evict with caller-supplied normalisers (see jq_score_lse): one pass over K. */
+int jq_evict_lse(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,
+                 void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
+                 void* ws, size_t ws_bytes, void* stream);
 
 /* jq_evict with kernel timing (the measurement hook of the benchmark): `marks` is a
  * HOST array of JQ_TRACE_MARKS hipEvent_t (passed as void*), created by the caller.

@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced",
            "jq_copy_probe", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_combine_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel",
                  "jq_select_finalize_kernel", "jq_compact_kernel")
@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         shp = ctypes.POINTER(_CShape)
         L.jq_workspace_bytes.argtypes = [shp, ctypes.POINTER(sz)]
         L.jq_score.argtypes = [shp, vp, vp, vp, vp, sz, vp]
+        L.jq_score_lse.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_evict_lse.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_pool.argtypes = [shp, vp, vp, vp]
         L.jq_select_topk.argtypes = [shp, vp, vp, vp, sz, vp]
         L.jq_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp]
@@ -101,13 +103,18 @@ class Shape:
         return int(sum(self.budgets)) if self.budgets is not None else 0
 
     def c_struct(self) -> _CShape:
+        key = (self.n_layers, tuple(self.seq_lens), self.n_q, self.h_q, self.h_kv, self.d, self.pool_k,
+               None if self.budgets is None else tuple(self.budgets), float(self.scale))
+        if self._keep and self._keep[0] == key:  # marshalled once per distinct description
+            return self._keep[3]
         cu = np.concatenate([[0], np.cumsum(np.asarray(self.seq_lens, dtype=np.int64))]).astype(np.int32)
         bud = None if self.budgets is None else np.ascontiguousarray(self.budgets, dtype=np.int32)
-        self._keep = [cu, bud]  # keep the host arrays alive while the struct is in use
         i32p = ctypes.POINTER(ctypes.c_int32)
-        return _CShape(self.n_layers, self.n_seq, self.n_q, self.h_q, self.h_kv, self.d, self.pool_k,
-                       float(self.scale), cu.ctypes.data_as(i32p),
-                       bud.ctypes.data_as(i32p) if bud is not None else ctypes.cast(None, i32p))
+        cs = _CShape(self.n_layers, self.n_seq, self.n_q, self.h_q, self.h_kv, self.d, self.pool_k,
+                     float(self.scale), cu.ctypes.data_as(i32p),
+                     bud.ctypes.data_as(i32p) if bud is not None else ctypes.cast(None, i32p))
+        self._keep = [key, cu, bud, cs]  # the host arrays must outlive the struct
+        return cs
 
 
 def _ptr(t) -> Optional[int]:
@@ -137,13 +144,18 @@ def alloc_workspace(shape: Shape, device="cuda"):
     return torch.empty(workspace_bytes(shape), dtype=torch.uint8, device=device)
 
 
-def score(shape: Shape, Q, K, scores=None, ws=None, stream=None):
+def score(shape: Shape, Q, K, scores=None, ws=None, stream=None, lse=None):
+    """Unpooled scores; with `lse` ([n_layers, n_seq, n_q, h_q] fp32) the one-pass supplied-normaliser variant."""
     import torch
     if scores is None:
         scores = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=K.device)
     if ws is None:
         ws = alloc_workspace(shape, K.device)
     cs = shape.c_struct()
+    if lse is not None:
+        _check(lib().jq_score_lse(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(lse), _ptr(scores), _ptr(ws), ws.numel(),
+                                  _stream(stream)), "jq_score_lse")
+        return scores
     _check(lib().jq_score(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(scores), _ptr(ws), ws.numel(), _stream(stream)), "jq_score")
     return scores
 
@@ -180,7 +192,7 @@ def compact(shape: Shape, K, V, idx, K_out=None, V_out=None, stream=None):
 
 
 def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_out=None, ws=None, stream=None,
-          want_idx=True, want_scores=True, marks=None):
+          want_idx=True, want_scores=True, marks=None, lse=None):
     """Fused score -> pool -> top-B -> gather.  Returns (K_out, V_out, idx_out, pooled scores).
 
     `marks`: optional list of TRACE_MARKS torch.cuda.Event(enable_timing=True) objects that have been
@@ -199,6 +211,10 @@ def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_ou
     if ws is None:
         ws = alloc_workspace(shape, dev)
     cs = shape.c_struct()
+    if lse is not None:
+        _check(lib().jq_evict_lse(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(lse), _ptr(K_out), _ptr(V_out),
+                                  _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict_lse")
+        return K_out, V_out, idx_out, scores_out
     if marks is not None:
         arr = (ctypes.c_void_p * len(marks))(*[int(ev.cuda_event) for ev in marks])
         _check(lib().jq_evict_traced(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out),

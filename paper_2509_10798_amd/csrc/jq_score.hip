@@ -360,6 +360,34 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
     a.aug[((int64_t)(layer * a.n_seq + s) * a.h_kv + g) * a.RP + row] = make_uint2((hi >> 16) | mid, lo >> 16);
 }
 
+// Caller-supplied normalisers: lse[layer, seq, i, h] (natural log) becomes the same three-term
+// -beta/c that the combine step would have produced (beta = lse * log2 e, c = scale * log2 e, so
+// -beta/c = -lse / scale), in the wave's row order r = i * group + hh.
+__global__ __launch_bounds__(256) void jq_lse_to_aug_kernel(ScoreArgs a, const float* lse, float inv_scale) {
+    const int64_t n = (int64_t)a.n_layers * a.n_seq * a.h_kv * a.RP;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (a.zero) {
+        const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+        for (int64_t i = tid; i < (int64_t)a.zero_words; i += stride) a.zero[i] = 0u;
+    }
+    if (tid >= n) return;
+    const int r = (int)(tid % a.RP);
+    int64_t rest = tid / a.RP;
+    const int g = (int)(rest % a.h_kv);
+    rest /= a.h_kv;  // = layer * n_seq + s
+    float x = -1.0e30f;
+    if (r < a.rows) {
+        const int i = r / a.group, h = g * a.group + r % a.group;
+        x = -lse[(rest * a.n_q + i) * a.h_q + h] * inv_scale;
+    }
+    const uint32_t hi = __float_as_uint(x) & 0xFFFF0000u;
+    const float r1 = x - __uint_as_float(hi);
+    const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
+    const float r2 = r1 - __uint_as_float(mid);
+    const uint32_t lo = __float_as_uint(r2) & 0xFFFF0000u;
+    a.aug[tid] = make_uint2((hi >> 16) | mid, lo >> 16);
+}
+
 // ------------------------------------------------------------------------------------------------
 // pass 2: normalised probabilities summed over the query rows
 // ------------------------------------------------------------------------------------------------
@@ -487,7 +515,7 @@ static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStre
 }
 
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
-                        uint32_t* zero, size_t zero_words) {
+                        uint32_t* zero, size_t zero_words, const float* lse) {
     void* const* marks = p.marks;
     ScoreArgs a;
     a.Q = (const uint16_t*)Q;
@@ -507,14 +535,21 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     const int64_t waves = (int64_t)p.n_layers * p.n_chunks * p.h_kv;
     dim3 grid((unsigned)((waves + kScoreWaves - 1) / kScoreWaves));
     hipError_t e;
-    for (int rg = 0; rg < p.row_groups; ++rg) {
-        a.row_tile0 = rg * kMaxRowTiles;
-        const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
-        if ((e = launch_stats_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
+    if (lse) {  // normalisers supplied: no statistics pass over K
+        const int64_t n_rows = (int64_t)p.n_layers * p.n_seq * p.h_kv * a.RP;
+        e = launch_kernel(jq_lse_to_aug_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st, nullptr, -1, a, lse,
+                          1.0f / p.scale);
+        if (e != hipSuccess) return e;
+    } else {
+        for (int rg = 0; rg < p.row_groups; ++rg) {
+            a.row_tile0 = rg * kMaxRowTiles;
+            const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
+            if ((e = launch_stats_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
+        }
+        const int64_t n_row_tiles = (int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles;
+        e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a);
+        if (e != hipSuccess) return e;
     }
-    const int64_t n_row_tiles = (int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles;
-    e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a);
-    if (e != hipSuccess) return e;
     for (int rg = 0; rg < p.row_groups; ++rg) {
         a.row_tile0 = rg * kMaxRowTiles;
         a.accumulate = rg > 0;

@@ -1,0 +1,121 @@
+"""GPU parity of the supplied-normaliser (one pass over K) entry points against the oracle, plus the
+measurement aids of the ABI (traced evict, copy probe)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2509_10798_amd as jq
+from parity import assert_kept_set_ok, assert_scores_close, from_dev_bf16, to_dev_bf16
+from workloads import bf16_bits_to_f64, f32_to_bf16_bits, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def torch_():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def prefill_lse(Q, K, K_soft):
+    """What a causal prefill attention kernel would keep for the soft-token rows: log-sum-exp over the prompt
+    keys and the soft-token keys up to the row's own position.  Q [n_q,h_q,d], K [L,h_kv,d], K_soft [n_q,h_kv,d]."""
+    n_q, h_q, d = Q.shape
+    G = h_q // K.shape[1]
+    Qd = bf16_bits_to_f64(Q)
+    lse = np.empty((n_q, h_q))
+    for h in range(h_q):
+        s = Qd[:, h, :] @ bf16_bits_to_f64(K[:, h // G, :]).T / math.sqrt(d)             # [n_q, L]
+        if K_soft is not None:
+            st = Qd[:, h, :] @ bf16_bits_to_f64(K_soft[:, h // G, :]).T / math.sqrt(d)   # [n_q, n_q]
+            st = np.where(np.tril(np.ones((n_q, n_q), dtype=bool)), st, -np.inf)
+            s = np.concatenate([s, st], axis=1)
+        m = s.max(axis=1)
+        lse[:, h] = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+    return lse
+
+
+@pytest.mark.parametrize("seq_lens,n_q,h_q,h_kv", [([700], 16, 8, 2), ([333, 1025], 32, 32, 8), ([90], 40, 8, 2)])
+def test_score_lse_matches_oracle(seq_lens, n_q, h_q, h_kv):
+    torch = torch_()
+    rng = np.random.default_rng(51)
+    T, d, ns = sum(seq_lens), 128, len(seq_lens)
+    Q = f32_to_bf16_bits(rng.standard_normal((1, ns, n_q, h_q, d)).astype(np.float32))
+    K = f32_to_bf16_bits(rng.standard_normal((1, T, h_kv, d)).astype(np.float32))
+    Ks = f32_to_bf16_bits(rng.standard_normal((ns, n_q, h_kv, d)).astype(np.float32))
+    cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    lse = np.stack([prefill_lse(Q[0, s], K[0, cu[s]:cu[s + 1]], Ks[s]) for s in range(ns)])[None].astype(np.float32)
+    sh = jq.Shape(n_layers=1, seq_lens=seq_lens, n_q=n_q, h_q=h_q, h_kv=h_kv)
+    got = jq.score(sh, to_dev_bf16(Q), to_dev_bf16(K), lse=torch.from_numpy(lse).cuda())
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    for s, L in enumerate(seq_lens):
+        ref = oracle.score_lse(Q[0, s], K[0, cu[s]:cu[s + 1]], lse[0, s].astype(np.float64))
+        assert_scores_close(got[0, :, cu[s]:cu[s + 1]], ref, n_q * (h_q // h_kv) / L, "seq %d" % s)
+        assert (got[0, :, cu[s]:cu[s + 1]].sum(axis=1) < n_q * (h_q // h_kv)).all()      # the soft tail took its share
+
+
+def test_score_lse_over_the_prompt_reproduces_two_pass_scores():
+    torch = torch_()
+    w = make_workload(1)
+    Q, K, _ = w.assemble()
+    lse = prefill_lse(Q[0, 0], K[0], None)[None, None].astype(np.float32)
+    sh = jq.Shape(n_layers=1, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv)
+    Qd, Kd = to_dev_bf16(Q), to_dev_bf16(K)
+    one = jq.score(sh, Qd, Kd, lse=torch.from_numpy(lse).cuda())
+    two = jq.score(sh, Qd, Kd)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(one.cpu().numpy(), two.cpu().numpy(), rtol=2e-4, atol=1e-9)
+
+
+def test_evict_lse_on_the_128k_layer():
+    torch = torch_()
+    w = make_workload(3)
+    Q, K, V = w.assemble()
+    rng = np.random.default_rng(52)
+    Ks = f32_to_bf16_bits(rng.standard_normal((w.n_q, w.h_kv, w.d)).astype(np.float32))
+    lse = prefill_lse(Q[0, 0], K[0], Ks).astype(np.float32)
+    sh = jq.Shape(n_layers=1, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    Ko, Vo, idx, pooled = jq.evict(sh, to_dev_bf16(Q), to_dev_bf16(K), to_dev_bf16(V),
+                                   lse=torch.from_numpy(lse[None, None]).cuda())
+    torch.cuda.synchronize()
+    ref = oracle.evict(Q[0, 0], K[0], V[0], w.budgets[0], w.pool_k, lse=lse.astype(np.float64))
+    assert_scores_close(pooled[0].cpu().numpy(), ref["pooled"], w.n_q * w.group / w.seq_lens[0], "pooled")
+    idx_h = idx[0].cpu().numpy()
+    for g in range(w.h_kv):
+        assert_kept_set_ok(ref["pooled"][g], ref["idx"][g], idx_h[g], "head %d" % g)
+    rk, rv = oracle.compact(K[0], V[0], idx_h)
+    np.testing.assert_array_equal(from_dev_bf16(Ko)[0], rk)
+    np.testing.assert_array_equal(from_dev_bf16(Vo)[0], rv)
+
+
+def test_traced_evict_equals_evict_and_times_every_kernel():
+    torch = torch_()
+    w = make_workload(1)
+    Q, K, V = w.assemble()
+    sh = jq.Shape(n_layers=1, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    Qd, Kd, Vd = to_dev_bf16(Q), to_dev_bf16(K), to_dev_bf16(V)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(jq.TRACE_MARKS)]
+    for ev in marks:
+        ev.record()
+    torch.cuda.synchronize()
+    a = jq.evict(sh, Qd, Kd, Vd)
+    b = jq.evict(sh, Qd, Kd, Vd, marks=marks)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int32) if x.dtype != torch.bfloat16 else x.view(torch.int16),
+                           y.view(torch.int32) if y.dtype != torch.bfloat16 else y.view(torch.int16))
+    for j, name in enumerate(jq.TRACE_KERNELS):
+        ms = marks[2 * j].elapsed_time(marks[2 * j + 1])
+        assert 0.0 < ms < 50.0, (name, ms)
+
+
+def test_copy_probe_copies():
+    torch = torch_()
+    src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    jq.copy_probe(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
