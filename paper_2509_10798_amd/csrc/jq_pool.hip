@@ -31,13 +31,13 @@ struct PoolArgs {
 
 // Histogram of the block's values.  Neighbouring scores crowd into a few bins, which would serialise
 // LDS atomics on one word; so the 128 bins below the block's highest bin are kept in 16 interleaved
-// copies (lane & 15 picks the copy), everything lower goes to one plain 2048-bin array.  Both are
-// merged into the problem's global histogram with one device-scope atomic per non-empty bin.
+// copies (lane & 15 picks the copy) and merged into the problem's global histogram with one
+// device-scope atomic per non-empty bin.  Values more than 32 octaves below the block's maximum
+// (practically: exact zeros) go to the global histogram one by one.
 template <bool POOL, int K>  // K: pool_k known at compile time (taps unrolled), or 0 for any
 __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
-    __shared__ uint32_t full[kHistBins];
     __shared__ uint32_t win[kWinCopies * kWinStride];
-    __shared__ uint32_t wave_max[kPoolThreads / 64];
+    __shared__ uint32_t wave_top[kPoolThreads / 64];
     __shared__ float tile[POOL ? kPoolBlockPos + 2 * kPoolMaxHalo : 1];
     const int g = blockIdx.y, layer = blockIdx.z;
     const int64_t row = ((int64_t)layer * a.h_kv + g) * a.T;
@@ -51,7 +51,6 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
     const int r = K ? (K - 1) / 2 : (a.pool_k - 1) / 2;
     const bool staged = POOL && one_seq && r <= kPoolMaxHalo;  // uniform
     if (do_hist && one_seq) {
-        for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) full[b] = 0;
         for (int b = threadIdx.x; b < kWinCopies * kWinStride; b += kPoolThreads) win[b] = 0;
     }
     if (staged) {
@@ -105,29 +104,25 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
 
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) top = max(top, (uint32_t)__shfl_xor((int)top, d));
-    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = top;
+    if ((threadIdx.x & 63) == 0) wave_top[threadIdx.x >> 6] = top;
     __syncthreads();
 #pragma unroll
-    for (int wv = 0; wv < kPoolThreads / 64; ++wv) top = max(top, wave_max[wv]);
+    for (int wv = 0; wv < kPoolThreads / 64; ++wv) top = max(top, wave_top[wv]);
     const uint32_t base = top >= kWinBins - 1 ? top - (kWinBins - 1) : 0u;  // window = [base, base + 127]
+    uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s_first) * a.h_kv + g) * kHistStride;
     uint32_t* my = win + (threadIdx.x & (kWinCopies - 1)) * kWinStride;
 #pragma unroll
     for (int e = 0; e < kPoolPerThread; ++e) {
         if (bin[e] == 0xFFFFFFFFu) continue;
         if (bin[e] >= base) atomicAdd(&my[bin[e] - base], 1u);
-        else atomicAdd(&full[bin[e]], 1u);
+        else atomicAdd(gh + bin[e], 1u);
     }
     __syncthreads();
-    uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s_first) * a.h_kv + g) * kHistStride;
     if (threadIdx.x < kWinBins) {
         uint32_t c = 0;
 #pragma unroll
         for (int k = 0; k < kWinCopies; ++k) c += win[k * kWinStride + threadIdx.x];
         if (c) atomicAdd(gh + base + threadIdx.x, c);
-    }
-    for (int b = threadIdx.x; b < kHistBins; b += kPoolThreads) {
-        const uint32_t c = full[b];
-        if (c) atomicAdd(gh + b, c);
     }
 }
 

@@ -358,14 +358,33 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         run += c;
     }
     __syncthreads();
-    for (int w = threadIdx.x; w < words; w += kFinThreads) {
-        uint32_t k = keep[w];
-        uint32_t slot = wpre[w];
-        while (k) {
-            const int bit = __ffs(k) - 1;
-            k &= k - 1;
-            if (slot < p.B) p.out[slot] = (w << 5) + bit;
-            ++slot;
+    // One word per thread and round.  Sparse words (the usual case) are emitted by their own thread; a dense
+    // word (a contiguous kept span) is emitted by the whole wave at once, one lane per bit, so that no lane
+    // walks 32 positions alone while 63 others wait.
+    const int lane = threadIdx.x & 63;
+    for (int w0r = 0; w0r < words; w0r += kFinThreads) {  // uniform trip count
+        const int w = w0r + threadIdx.x;
+        uint32_t k = w < words ? keep[w] : 0u;
+        uint32_t slot = w < words ? wpre[w] : 0u;
+        const bool dense = __popc(k) > 4;
+        uint64_t todo = __ballot(dense);
+        while (todo) {  // uniform
+            const int src = __ffsll((unsigned long long)todo) - 1;
+            todo &= todo - 1;
+            const uint32_t kk = __shfl(k, src), ss = __shfl(slot, src);
+            const int ww = __shfl(w, src);
+            if (lane < 32 && ((kk >> lane) & 1u)) {
+                const uint32_t o = ss + __popc(kk & ((1u << lane) - 1u));
+                if (o < p.B) p.out[o] = (ww << 5) + lane;
+            }
+        }
+        if (!dense) {
+            while (k) {
+                const int bit = __ffs(k) - 1;
+                k &= k - 1;
+                if (slot < p.B) p.out[slot] = (w << 5) + bit;
+                ++slot;
+            }
         }
     }
 }

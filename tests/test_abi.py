@@ -51,7 +51,7 @@ def test_workspace_size_grows_with_problem():
 @pytest.mark.parametrize("kw,code", [
     (dict(h_q=3), -2), (dict(pool_k=4), -2), (dict(pool_k=0), -2), (dict(n_q=0), -2), (dict(n_layers=0), -2),
     (dict(scale=-1.0), -2), (dict(scale=float("nan")), -2),
-    (dict(d=64), -4), (dict(seq_lens=[8] * 129, budgets=[1] * 129), -4),
+    (dict(d=64), -4), (dict(seq_lens=[8] * 129, budgets=[1] * 129), -4), (dict(h_q=1028, h_kv=257), -4),
     (dict(budgets=[0]), -3), (dict(budgets=[65]), -3),
     (dict(seq_lens=[64, 0], budgets=[8, 1]), -2),
 ])
@@ -77,6 +77,13 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_evict(ctypes.byref(cs), Q, K, V, K + 256, Vo, None, None, ws, need, None) == -6    # K_out inside K
     assert L.jq_evict(ctypes.byref(cs), Q, K, V, Ko, Ko, None, None, ws, need, None) == -6         # outputs overlap
     assert L.jq_evict(ctypes.byref(cs), Q + 2, K, V, Ko, Vo, None, None, ws, need, None) == -4     # misaligned Q
+    lse = big + (6 << 30)
+    assert L.jq_score_lse(ctypes.byref(cs), Q, K, None, Ko, ws, need, None) == -1                  # lse required
+    assert L.jq_evict_lse(ctypes.byref(cs), Q, K, V, None, Ko, Vo, None, None, ws, need, None) == -1
+    assert L.jq_evict_lse(ctypes.byref(cs), Q, K, V, lse + 2, Ko, Vo, None, None, ws, need, None) == -4
+    assert L.jq_evict_lse(ctypes.byref(cs), Q, K, V, Ko, Ko, Vo, None, None, ws, need, None) == -6   # lse inside K_out
+    assert L.jq_evict_traced(ctypes.byref(cs), Q, K, V, Ko, Vo, None, None, ws, need, None, None, 14) == -1
+    assert L.jq_copy_probe(K, K + 64, 1024, None) == -6 and L.jq_copy_probe(K, Ko, 24, None) == -2
     assert L.jq_compact(ctypes.byref(cs), K, V, ws, V, Vo, None) == -6
     assert L.jq_pool(ctypes.byref(cs), K, K, None) == -6
     cs2 = shape(budgets=None).c_struct()
