@@ -358,34 +358,25 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         run += c;
     }
     __syncthreads();
-    // One word per thread and round.  Sparse words (the usual case) are emitted by their own thread; a dense
-    // word (a contiguous kept span) is emitted by the whole wave at once, one lane per bit, so that no lane
-    // walks 32 positions alone while 63 others wait.
-    const int lane = threadIdx.x & 63;
-    for (int w0r = 0; w0r < words; w0r += kFinThreads) {  // uniform trip count
-        const int w = w0r + threadIdx.x;
-        uint32_t k = w < words ? keep[w] : 0u;
-        uint32_t slot = w < words ? wpre[w] : 0u;
-        const bool dense = __popc(k) > 4;
-        uint64_t todo = __ballot(dense);
-        while (todo) {  // uniform
-            const int src = __ffsll((unsigned long long)todo) - 1;
-            todo &= todo - 1;
-            const uint32_t kk = __shfl(k, src), ss = __shfl(slot, src);
-            const int ww = __shfl(w, src);
-            if (lane < 32 && ((kk >> lane) & 1u)) {
-                const uint32_t o = ss + __popc(kk & ((1u << lane) - 1u));
-                if (o < p.B) p.out[o] = (ww << 5) + lane;
-            }
+    // Emission is parallel over OUTPUT slots, not over words: kept positions cluster (contiguous heavy-hitter
+    // spans), so per-word loops leave most lanes idle.  Slot o lives in the last word w with wpre[w] <= o
+    // (binary search in LDS, same trip count for every thread); inside the word, the (o - wpre[w])-th set bit
+    // is found by five popcount halvings.  Consecutive threads write consecutive slots.
+    for (uint32_t o = threadIdx.x; o < p.B; o += kFinThreads) {
+        int lo = 0, hi = words;  // invariant: wpre[lo] <= o, and hi == words or wpre[hi] > o
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (wpre[mid] <= o) lo = mid; else hi = mid;
         }
-        if (!dense) {
-            while (k) {
-                const int bit = __ffs(k) - 1;
-                k &= k - 1;
-                if (slot < p.B) p.out[slot] = (w << 5) + bit;
-                ++slot;
-            }
+        uint32_t r = o - wpre[lo];
+        const uint32_t k = keep[lo];
+        uint32_t pos = 0;
+#pragma unroll
+        for (int sft = 16; sft >= 1; sft >>= 1) {
+            const uint32_t c = __popc((k >> pos) & ((1u << sft) - 1u));
+            if (r >= c) { r -= c; pos += sft; }
         }
+        p.out[o] = (lo << 5) + (int)pos;
     }
 }
 
