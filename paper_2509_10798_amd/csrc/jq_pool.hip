@@ -5,8 +5,9 @@
 //   pooled[l,g,t] = (1/k) * sum_{|u| <= (k-1)/2} scores[l,g,t+u],  zero outside t's own sequence.
 //
 // Memory-bound and tiny next to the K passes.  A block stages its span plus halo in LDS (zeros
-// where the sequence ends), so every score is fetched from global memory once; blocks that
-// straddle two sequences, or kernels wider than the staged halo, take a direct per-thread path.
+// where the sequence ends), so every score is fetched from global memory once; a block whose span
+// crosses a sequence boundary handles one sequence's part after the other, and pooling widths beyond
+// the staged halo read their taps straight from global memory.
 #include "jq_common.h"
 
 namespace jq {
@@ -33,96 +34,114 @@ struct PoolArgs {
 // LDS atomics on one word; so the 128 bins below the block's highest bin are kept in 16 interleaved
 // copies (lane & 15 picks the copy) and merged into the problem's global histogram with one
 // device-scope atomic per non-empty bin.  Values more than 32 octaves below the block's maximum
-// (practically: exact zeros) go to the global histogram one by one.
+// (the far tail of a peaked softmax, exact zeros) are counted in a single full-width LDS histogram
+// that is cleared, filled and flushed only by blocks that meet such a value.
 template <bool POOL, int K>  // K: pool_k known at compile time (taps unrolled), or 0 for any
 __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
     __shared__ uint32_t win[kWinCopies * kWinStride];
+    __shared__ uint32_t low[kHistBins];
     __shared__ uint32_t wave_top[kPoolThreads / 64];
     __shared__ float tile[POOL ? kPoolBlockPos + 2 * kPoolMaxHalo : 1];
     const int g = blockIdx.y, layer = blockIdx.z;
     const int64_t row = ((int64_t)layer * a.h_kv + g) * a.T;
     const float* in_row = a.in + row;
-    const int64_t p0 = (int64_t)blockIdx.x * kPoolBlockPos;
-    const int64_t p1 = min(a.T, p0 + kPoolBlockPos);
-    const int s_first = find_seq(a.tab.cu_seq, a.tab.n_seq, p0);
-    const int s_last = find_seq(a.tab.cu_seq, a.tab.n_seq, p1 - 1);
-    const bool one_seq = (s_first == s_last);  // uniform over the block
+    const int64_t b0 = (int64_t)blockIdx.x * kPoolBlockPos;
+    const int64_t b1 = min(a.T, b0 + kPoolBlockPos);
+    const int s_first = find_seq(a.tab.cu_seq, a.tab.n_seq, b0);
+    const int s_last = find_seq(a.tab.cu_seq, a.tab.n_seq, b1 - 1);
     const bool do_hist = a.hist != nullptr;
     const int r = K ? (K - 1) / 2 : (a.pool_k - 1) / 2;
-    const bool staged = POOL && one_seq && r <= kPoolMaxHalo;  // uniform
-    if (do_hist && one_seq) {
-        for (int b = threadIdx.x; b < kWinCopies * kWinStride; b += kPoolThreads) win[b] = 0;
-    }
-    if (staged) {
-        const int64_t lo = a.tab.cu_seq[s_first], hi = a.tab.cu_seq[s_first + 1];
-        const int n = (int)(p1 - p0) + 2 * r;
-        for (int i = threadIdx.x; i < n; i += kPoolThreads) {
-            const int64_t q = p0 - r + i;
-            tile[i] = (q >= lo && q < hi) ? in_row[q] : 0.f;
-        }
-    }
-    __syncthreads();
-    uint32_t bin[kPoolPerThread];
-    uint32_t top = 0;
-#pragma unroll
-    for (int e = 0; e < kPoolPerThread; ++e) {
-        const int j = e * kPoolThreads + threadIdx.x;
-        const int64_t p = p0 + j;
-        const bool in = p < p1;
-        int s = s_first;
-        float v = 0.f;
-        if (in) {
-            if (!POOL) {
-                v = in_row[p];
-                if (!one_seq) s = find_seq(a.tab.cu_seq, a.tab.n_seq, p);
-            } else if (staged) {
-                float acc = 0.f;
-                if (K) {
-#pragma unroll
-                    for (int u = 0; u < K; ++u) acc += tile[j + u];
-                } else {
-                    for (int u = 0; u <= 2 * r; ++u) acc += tile[j + u];  // ascending position order
-                }
-                v = acc * a.inv_k;
-                a.out[row + p] = v;
-            } else {
-                if (!one_seq) s = find_seq(a.tab.cu_seq, a.tab.n_seq, p);
-                const int64_t lo = max((int64_t)a.tab.cu_seq[s], p - r);
-                const int64_t hi = min((int64_t)a.tab.cu_seq[s + 1] - 1, p + r);
-                float acc = 0.f;
-                for (int64_t q = lo; q <= hi; ++q) acc += in_row[q];
-                v = acc * a.inv_k;
-                a.out[row + p] = v;
+    const bool staged = POOL && r <= kPoolMaxHalo;  // uniform
+
+    // The block's span is handled one sequence at a time (nearly always there is just one), so pooling
+    // windows stop at sequence ends and every count goes to its own problem's histogram.
+    for (int s = s_first; s <= s_last; ++s) {
+        const int64_t lo = a.tab.cu_seq[s], hi = a.tab.cu_seq[s + 1];
+        const int64_t p0 = max(b0, lo), p1 = min(b1, hi);  // this sequence's part of the span
+        if (do_hist)
+            for (int b = threadIdx.x; b < kWinCopies * kWinStride; b += kPoolThreads) win[b] = 0;
+        if (staged) {
+            const int n = (int)(p1 - p0) + 2 * r;
+            for (int i = threadIdx.x; i < n; i += kPoolThreads) {
+                const int64_t q = p0 - r + i;
+                tile[i] = (q >= lo && q < hi) ? in_row[q] : 0.f;
             }
         }
-        bin[e] = in ? (sortable_key(v) >> 21) : 0xFFFFFFFFu;  // 0xFFFFFFFF: no element
-        if (in) top = max(top, bin[e]);
-        if (do_hist && !one_seq && in)  // block straddles two sequences (rare): straight to global memory
-            atomicAdd(a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride + bin[e], 1u);
-    }
-    if (!(do_hist && one_seq)) return;  // uniform
+        __syncthreads();
+        uint32_t bin[kPoolPerThread];
+        uint32_t top = 0;
+#pragma unroll
+        for (int e = 0; e < kPoolPerThread; ++e) {
+            const int j = e * kPoolThreads + threadIdx.x;
+            const int64_t p = p0 + j;
+            const bool in = p < p1;
+            float v = 0.f;
+            if (in) {
+                if (!POOL) {
+                    v = in_row[p];
+                } else if (staged) {
+                    float acc = 0.f;
+                    if (K) {
+#pragma unroll
+                        for (int u = 0; u < K; ++u) acc += tile[j + u];
+                    } else {
+                        for (int u = 0; u <= 2 * r; ++u) acc += tile[j + u];  // ascending position order
+                    }
+                    v = acc * a.inv_k;
+                    a.out[row + p] = v;
+                } else {
+                    const int64_t q0 = max(lo, p - r), q1 = min(hi - 1, p + r);
+                    float acc = 0.f;
+                    for (int64_t q = q0; q <= q1; ++q) acc += in_row[q];
+                    v = acc * a.inv_k;
+                    a.out[row + p] = v;
+                }
+            }
+            bin[e] = in ? (sortable_key(v) >> 21) : 0xFFFFFFFFu;  // 0xFFFFFFFF: no element
+            if (in) top = max(top, bin[e]);
+        }
+        if (!do_hist) {  // uniform
+            __syncthreads();
+            continue;
+        }
 
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) top = max(top, (uint32_t)__shfl_xor((int)top, d));
-    if ((threadIdx.x & 63) == 0) wave_top[threadIdx.x >> 6] = top;
-    __syncthreads();
+        for (int d = 32; d >= 1; d >>= 1) top = max(top, (uint32_t)__shfl_xor((int)top, d));
+        if ((threadIdx.x & 63) == 0) wave_top[threadIdx.x >> 6] = top;
+        __syncthreads();
 #pragma unroll
-    for (int wv = 0; wv < kPoolThreads / 64; ++wv) top = max(top, wave_top[wv]);
-    const uint32_t base = top >= kWinBins - 1 ? top - (kWinBins - 1) : 0u;  // window = [base, base + 127]
-    uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s_first) * a.h_kv + g) * kHistStride;
-    uint32_t* my = win + (threadIdx.x & (kWinCopies - 1)) * kWinStride;
+        for (int wv = 0; wv < kPoolThreads / 64; ++wv) top = max(top, wave_top[wv]);
+        const uint32_t base = top >= kWinBins - 1 ? top - (kWinBins - 1) : 0u;  // window = [base, base + 127]
+        uint32_t* gh = a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride;
+        uint32_t* my = win + (threadIdx.x & (kWinCopies - 1)) * kWinStride;
+        bool below = false;
 #pragma unroll
-    for (int e = 0; e < kPoolPerThread; ++e) {
-        if (bin[e] == 0xFFFFFFFFu) continue;
-        if (bin[e] >= base) atomicAdd(&my[bin[e] - base], 1u);
-        else atomicAdd(gh + bin[e], 1u);
-    }
-    __syncthreads();
-    if (threadIdx.x < kWinBins) {
-        uint32_t c = 0;
+        for (int e = 0; e < kPoolPerThread; ++e) below |= bin[e] < base;  // the "no element" marker is never below
+        const bool any_below = __syncthreads_or(below);                    // uniform over the block
+        if (any_below) {
+            for (uint32_t b = threadIdx.x; b < base; b += kPoolThreads) low[b] = 0;
+            __syncthreads();
+        }
 #pragma unroll
-        for (int k = 0; k < kWinCopies; ++k) c += win[k * kWinStride + threadIdx.x];
-        if (c) atomicAdd(gh + base + threadIdx.x, c);
+        for (int e = 0; e < kPoolPerThread; ++e) {
+            if (bin[e] == 0xFFFFFFFFu) continue;
+            if (bin[e] >= base) atomicAdd(&my[bin[e] - base], 1u);
+            else atomicAdd(&low[bin[e]], 1u);
+        }
+        __syncthreads();
+        if (any_below) {
+            for (uint32_t b = threadIdx.x; b < base; b += kPoolThreads) {
+                const uint32_t c = low[b];
+                if (c) atomicAdd(gh + b, c);
+            }
+        }
+        if (threadIdx.x < kWinBins) {
+            uint32_t c = 0;
+#pragma unroll
+            for (int k = 0; k < kWinCopies; ++k) c += win[k * kWinStride + threadIdx.x];
+            if (c) atomicAdd(gh + base + threadIdx.x, c);
+        }
+        __syncthreads();  // win, low, tile and wave_top are reused by the next sequence
     }
 }
 

@@ -136,6 +136,17 @@ def test_select_narrow_value_range():
     run_select_case(bits.view(np.float32), [9000], [700])
 
 
+def test_select_wide_dynamic_range():
+    # a peaked softmax spreads scores over hundreds of octaves, far below any block's histogram window;
+    # with a large budget the threshold itself lies in that far tail
+    rng = np.random.default_rng(34)
+    x = np.exp(-np.abs(rng.standard_normal((2, 3, 20000))) * 60.0).astype(np.float32)   # down to denormals and 0
+    x[1, 0, 5000:9000] = 0.0
+    run_select_case(x, [20000], [64])
+    run_select_case(x, [20000], [15000])
+    run_select_case(x, [12000, 8000], [9000, 100])
+
+
 def test_compact_is_bit_exact():
     torch = torch_()
     rng = np.random.default_rng(41)
