@@ -201,11 +201,15 @@ __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(Sele
     const int s_first = find_seq(a.tab.cu_seq, a.tab.n_seq, p0);
     const int s_last = find_seq(a.tab.cu_seq, a.tab.n_seq, p1 - 1);
     const float* row = a.pooled + ((int64_t)layer * a.h_kv + g) * a.T;
-    // thread t owns kScatterPerThread consecutive positions
-    const int64_t t0 = p0 + (int64_t)threadIdx.x * kScatterPerThread;
+    // thread t takes positions p0 + t, p0 + t + 256, ...: neighbouring lanes read neighbouring words, and
+    // the lists are unordered, so which thread appends which position does not matter
+    const int64_t t0 = p0 + threadIdx.x;
     uint32_t key[kScatterPerThread];
 #pragma unroll
-    for (int e = 0; e < kScatterPerThread; ++e) key[e] = (t0 + e < p1) ? sortable_key(row[t0 + e]) : 0u;
+    for (int e = 0; e < kScatterPerThread; ++e) {
+        const int64_t t = t0 + (int64_t)e * kScatterThreads;
+        key[e] = (t < p1) ? sortable_key(row[t]) : 0u;
+    }
 
     for (int s = s_first; s <= s_last; ++s) {  // almost always a single sequence
         uint32_t* hist = a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride;
@@ -217,7 +221,8 @@ __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(Sele
         uint32_t n_s = 0, n_c = 0;
 #pragma unroll
         for (int e = 0; e < kScatterPerThread; ++e) {
-            const bool in = t0 + e >= q0 && t0 + e < q1;
+            const int64_t t = t0 + (int64_t)e * kScatterThreads;
+            const bool in = t >= q0 && t < q1;
             n_s += in && (key[e] >> 21) > b1;
             n_c += in && (key[e] >> 21) == b1;
         }
@@ -235,9 +240,10 @@ __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(Sele
         uint2* cand = a.cand + ((int64_t)layer * a.h_kv + g) * a.T + a.tab.cu_seq[s];
 #pragma unroll
         for (int e = 0; e < kScatterPerThread; ++e) {
-            const bool in = t0 + e >= q0 && t0 + e < q1;
+            const int64_t t = t0 + (int64_t)e * kScatterThreads;
+            const bool in = t >= q0 && t < q1;
             const uint32_t bin = key[e] >> 21;
-            const uint32_t j = (uint32_t)(t0 + e - a.tab.cu_seq[s]);
+            const uint32_t j = (uint32_t)(t - a.tab.cu_seq[s]);
             if (in && bin > b1) { if (slot_s < B) sure[slot_s] = (int32_t)j; ++slot_s; }
             if (in && bin == b1) { if (slot_c < (uint32_t)Ls) cand[slot_c] = make_uint2(key[e], j); ++slot_c; }
         }
