@@ -88,6 +88,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     size_t off = 0;
     p.off_stats = off;  off += align_up((size_t)p.n_layers * nc * p.h_kv * RP * sizeof(float2));
     p.off_aug = off;    off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * RP * sizeof(uint2));
+    p.off_qfrag = off;  off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * RP * kHeadDim * 2);
     p.off_hist = off;   off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride * sizeof(uint32_t));
     p.off_scores = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));
     p.off_pooled = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));

@@ -40,7 +40,7 @@ struct Plan {
     SeqTab tab;
     void* const* marks;   // host only: nullptr, or 2 * kTraceKernels events (start, stop) for jq_evict_traced
     // workspace layout (byte offsets, 256-aligned)
-    size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
+    size_t off_stats, off_aug, off_qfrag, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
 };
 
 // Largest s with cu[s] <= v (cu[0] = 0, strictly increasing, v < cu[n]).

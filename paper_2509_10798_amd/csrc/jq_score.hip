@@ -11,7 +11,10 @@
 //                    multiply, one exp2 and one add per logit.
 //
 // One wave owns one (layer, sequence, chunk of keys, KV head) and keeps that head's (up to) 128
-// query rows in registers as MFMA operands.  Key tiles of 32 keys x 128 channels are fetched
+// query rows in registers as MFMA operands.  Gathering them from Q costs 32 row-strided loads per
+// wave (each touches 32 cache lines), so whoever reads Q first -- pass 1, or the kernel that converts
+// caller-supplied normalisers -- also leaves a copy in operand order, which pass 2 reads with fully
+// coalesced loads.  Key tiles of 32 keys x 128 channels are fetched
 // asynchronously, straight from global memory into a private, XOR-swizzled 8 KiB LDS slot (buffer
 // loads with the LDS modifier, 16 B per lane, 16 lanes per 256-byte key row, so every 128-byte
 // line is requested whole), double buffered, and read back in MFMA operand order without bank
@@ -35,6 +38,7 @@ struct ScoreArgs {
     const uint16_t* K;
     float2* stats;    // [n_layers][n_chunks][h_kv][RP]: (m, Z) per chunk of keys
     uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
+    u32x4* qfrag;     // [n_layers][n_seq][h_kv][RP/32][8][64]: query rows in MFMA operand order
     float* scores;    // [n_layers][h_kv][T]
     int32_t n_layers, n_seq, n_q, h_q, h_kv, group, rows, RP, chunk_keys, n_chunks;
     int32_t row_tile0;   // first query-row tile of this launch
@@ -113,6 +117,31 @@ __device__ __forceinline__ void load_q(const ScoreArgs& a, const WaveItem& w, in
             if (!valid) v = u32x4{0u, 0u, 0u, 0u};
             qf[qt][ks] = as_bf16x8(v);
         }
+    }
+}
+
+// Operand-order copy of the query rows: entry ((item * RP/32 + row tile) * 8 + k-step) * 64 + lane.
+__device__ __forceinline__ int64_t qfrag_index(const ScoreArgs& a, int layer, int seq, int g, int row_tile) {
+    return ((((int64_t)(layer * a.n_seq + seq) * a.h_kv + g) * (a.RP / kRowTile) + row_tile) * 8) * 64;
+}
+
+template <int NQT>
+__device__ __forceinline__ void store_q_frags(const ScoreArgs& a, const WaveItem& w, int lane, const bf16x8 (&qf)[NQT][8]) {
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        u32x4* dst = a.qfrag + qfrag_index(a, w.layer, w.seq, w.g, a.row_tile0 + qt) + lane;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) dst[ks * 64] = __builtin_bit_cast(u32x4, qf[qt][ks]);
+    }
+}
+
+template <int NQT>
+__device__ __forceinline__ void load_q_frags(const ScoreArgs& a, const WaveItem& w, int lane, bf16x8 (&qf)[NQT][8]) {
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        const u32x4* src = a.qfrag + qfrag_index(a, w.layer, w.seq, w.g, a.row_tile0 + qt) + lane;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[qt][ks] = as_bf16x8(src[ks * 64]);
     }
 }
 
@@ -261,6 +290,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 
     bf16x8 qf[NQT][8];
     load_q<NQT>(a, w, lane, qf);
+    if (w.k_begin == 0) store_q_frags<NQT>(a, w, lane, qf);  // the sequence's first chunk leaves the operand-order copy
     const float c = a.c;
 
     float m[NQT], z[NQT];
@@ -366,9 +396,26 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
 __global__ __launch_bounds__(256) void jq_lse_to_aug_kernel(ScoreArgs a, const float* lse, float inv_scale) {
     const int64_t n = (int64_t)a.n_layers * a.n_seq * a.h_kv * a.RP;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     if (a.zero) {
-        const int64_t stride = (int64_t)gridDim.x * blockDim.x;
         for (int64_t i = tid; i < (int64_t)a.zero_words; i += stride) a.zero[i] = 0u;
+    }
+    // operand-order copy of Q (no statistics pass runs in this mode): one 16-byte entry per thread and step
+    for (int64_t e = tid; e < n * 16; e += stride) {
+        const int lane = (int)(e & 63), ks = (int)((e >> 6) & 7);
+        int64_t rest = e >> 9;  // (item, row tile)
+        const int tiles = a.RP / kRowTile;
+        const int rt = (int)(rest % tiles);
+        rest /= tiles;
+        const int g = (int)(rest % a.h_kv);
+        rest /= a.h_kv;  // = layer * n_seq + s
+        const int row = rt * kRowTile + (lane & 31);
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (row < a.rows) {
+            const int i = row / a.group, h = g * a.group + row % a.group;
+            v = *(const u32x4*)((const char*)a.Q + ((rest * a.n_q + i) * a.h_q + h) * kHeadDim * 2 + ks * 32 + (lane >> 5) * 16);
+        }
+        a.qfrag[e] = v;
     }
     if (tid >= n) return;
     const int r = (int)(tid % a.RP);
@@ -415,7 +462,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         fetch_tile(ks.rsrc, slots + kSlotBytes, kKeyTile * ks.row_bytes, ks.row_bytes, ks.n_keys - kKeyTile, tl, lane);
 
     bf16x8 qf[NQT][8];
-    load_q<NQT>(a, w, lane, qf);
+    load_q_frags<NQT>(a, w, lane, qf);
     bf16x8 qaug[NQT];
     {
         const uint2* ap = a.aug + ((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP +
@@ -522,6 +569,7 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.K = (const uint16_t*)K;
     a.stats = (float2*)(ws + p.off_stats);
     a.aug = (uint2*)(ws + p.off_aug);
+    a.qfrag = (u32x4*)(ws + p.off_qfrag);
     a.scores = scores;
     a.n_layers = p.n_layers; a.n_seq = p.n_seq; a.n_q = p.n_q; a.h_q = p.h_q; a.h_kv = p.h_kv;
     a.group = p.group; a.rows = p.rows; a.RP = p.row_tiles * kRowTile;
@@ -537,7 +585,9 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     hipError_t e;
     if (lse) {  // normalisers supplied: no statistics pass over K
         const int64_t n_rows = (int64_t)p.n_layers * p.n_seq * p.h_kv * a.RP;
-        e = launch_kernel(jq_lse_to_aug_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st, nullptr, -1, a, lse,
+        const int64_t want = (n_rows * 16 + 255) / 256, need = (n_rows + 255) / 256;  // one Q entry per thread if possible
+        const int64_t blocks = want < 2048 ? want : (need > 2048 ? need : 2048);
+        e = launch_kernel(jq_lse_to_aug_kernel, dim3((unsigned)blocks), dim3(256), 0, st, nullptr, -1, a, lse,
                           1.0f / p.scale);
         if (e != hipSuccess) return e;
     } else {
