@@ -33,8 +33,10 @@ struct Plan {
     int32_t rows;         // n_q * group: query rows that share one KV head
     int32_t row_tiles;    // ceil(rows / 32)
     int32_t row_groups;   // ceil(row_tiles / 4): passes of the score kernels over K
-    int32_t chunk_keys;   // keys one wave streams (multiple of 32)
-    int32_t n_chunks;     // chunks per layer, over all sequences
+    int32_t chunk_keys;   // keys one wave of the second K pass streams (multiple of 32); tab.cu_chunk counts these
+    int32_t n_chunks;     // such chunks per layer, over all sequences
+    int32_t chunk_keys_stats, n_chunks_stats;  // the same for the first K pass (softmax statistics)
+    int32_t cu_chunk_stats[JQ_MAX_SEQ + 1];
     float scale;          // logit scale actually used
     int64_t T, TB;
     SeqTab tab;

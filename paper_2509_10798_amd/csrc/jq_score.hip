@@ -41,6 +41,7 @@ struct ScoreArgs {
     u32x4* qfrag;     // [n_layers][n_seq][h_kv][RP/32][8][64]: query rows in MFMA operand order
     float* scores;    // [n_layers][h_kv][T]
     int32_t n_layers, n_seq, n_q, h_q, h_kv, group, rows, RP, chunk_keys, n_chunks;
+    int32_t group_shift;  // log2(group) when group is a power of two, else -1
     int32_t row_tile0;   // first query-row tile of this launch
     int32_t accumulate;  // pass 2: add to `scores` instead of overwriting
     float c;             // scale * log2(e)
@@ -197,6 +198,41 @@ __device__ __forceinline__ void lds_get_frags(const char* slot, bf16x8 (&kf)[8],
     }
 }
 
+// Query rows of the wave's KV head (row r = i * group + hh  <->  Q[i, g*group + hh]) as MFMA operands,
+// fetched like a key tile: every load instruction covers four whole 256-byte rows (lane l takes 16 B of
+// row 4i + (l >> 4)), so each cache line is requested once, and an 8 KiB LDS slot turns one tile of 32
+// rows at a time into operand order.  All global loads are issued before the first LDS round trip.
+template <int NQT>
+__device__ __forceinline__ void load_q_via_lds(const ScoreArgs& a, const WaveItem& w, int lane, char* slot,
+                                               bf16x8 (&qf)[NQT][8]) {
+    const char* qbase = (const char*)a.Q + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q) * a.h_q * kHeadDim * 2;
+    u32x4 raw[NQT][8];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + (lane >> 4);
+            const int row = (a.row_tile0 + qt) * kRowTile + r;
+            const bool valid = row < a.rows;
+            int it = 0, hh = 0;
+            if (valid) {
+                if (a.group_shift >= 0) { it = row >> a.group_shift; hh = row & (a.group - 1); }
+                else { it = row / a.group; hh = row % a.group; }
+            }
+            const int c = (lane & 15) ^ (r & 15);  // logical chunk; it lands at physical chunk (lane & 15)
+            u32x4 v = *(const u32x4*)(qbase + ((int64_t)it * a.h_q + (w.g * a.group + hh)) * kHeadDim * 2 + c * 16);
+            if (!valid) v = u32x4{0u, 0u, 0u, 0u};  // rows past the end: row 0 of the head was read (in bounds), then zeroed
+            raw[qt][i] = v;
+        }
+    }
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(u32x4*)(slot + 1024 * i + 16 * lane) = raw[qt][i];
+        lds_get_frags(slot, qf[qt], lane);  // same wave, same addresses: LDS keeps program order
+    }
+}
+
 struct KeyStream {
     __amdgpu_buffer_rsrc_t rsrc;
     uint32_t row_bytes;
@@ -283,25 +319,27 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 
     const KeyStream ks = key_stream(a, w);
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
-    // two tiles in flight from the start; a slot is refilled as soon as its fragments are in registers
+    // The first key tile goes to slot 0 at once; slot 1 first serves as the staging area that turns the
+    // query rows into operand order, then takes the second tile.  From then on two tiles are always in
+    // flight: a slot is refilled as soon as its fragments are in registers.
     fetch_tile(ks.rsrc, slots, 0u, ks.row_bytes, ks.n_keys, tl, lane);
+    bf16x8 qf[NQT][8];
+    load_q_via_lds<NQT>(a, w, lane, slots + kSlotBytes, qf);
+    if (w.k_begin == 0) store_q_frags<NQT>(a, w, lane, qf);  // the sequence's first chunk leaves the operand-order copy
+    wait_frags_read();
     if (ks.n_tiles > 1)
         fetch_tile(ks.rsrc, slots + kSlotBytes, kKeyTile * ks.row_bytes, ks.row_bytes, ks.n_keys - kKeyTile, tl, lane);
-
-    bf16x8 qf[NQT][8];
-    load_q<NQT>(a, w, lane, qf);
-    if (w.k_begin == 0) store_q_frags<NQT>(a, w, lane, qf);  // the sequence's first chunk leaves the operand-order copy
     const float c = a.c;
 
     float m[NQT], z[NQT];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
-    // the Q loads above are older than the tile loads only in part: drain everything once
-    __builtin_amdgcn_s_waitcnt(0x0F70);
 
+    // every load older than the second tile's eight (first tile, query rows, operand-order copy) is covered
+    // by the first wait below
     const int n_full = ks.n_keys / kKeyTile;
     for (int t = 0; t < n_full; ++t) {
-        if (t > 0) wait_tile_landed(t + 1 < ks.n_tiles);
+        wait_tile_landed(t + 1 < ks.n_tiles);
         bf16x8 kf[8];
         lds_get_frags(slots + (t & 1) * kSlotBytes, kf, lane);
         if (t + 2 < ks.n_tiles) {
@@ -312,7 +350,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         stats_tile<NQT, false>(kf, qf, m, z, c, kKeyTile, half);
     }
     if (n_full < ks.n_tiles) {  // partial last tile
-        if (n_full > 0) wait_tile_landed(false);
+        wait_tile_landed(false);
         bf16x8 kf[8];
         lds_get_frags(slots + (n_full & 1) * kSlotBytes, kf, lane);
         stats_tile<NQT, true>(kf, qf, m, z, c, ks.n_keys - n_full * kKeyTile, half);
@@ -573,15 +611,24 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.scores = scores;
     a.n_layers = p.n_layers; a.n_seq = p.n_seq; a.n_q = p.n_q; a.h_q = p.h_q; a.h_kv = p.h_kv;
     a.group = p.group; a.rows = p.rows; a.RP = p.row_tiles * kRowTile;
-    a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
+    a.group_shift = -1;
+    for (int sh = 0; sh < 16; ++sh)
+        if (p.group == (1 << sh)) a.group_shift = sh;
     a.row_tile0 = 0; a.accumulate = 0;
     a.c = p.scale * 1.4426950408889634f;
     a.T = p.T;
     a.zero = zero; a.zero_words = zero_words;
     a.tab = p.tab;
+    // the two K passes cut the sequences into chunks of their own size
+    a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
+    ScoreArgs a1 = a;
+    a1.chunk_keys = p.chunk_keys_stats; a1.n_chunks = p.n_chunks_stats;
+    for (int s = 0; s <= p.n_seq; ++s) a1.tab.cu_chunk[s] = p.cu_chunk_stats[s];
 
     const int64_t waves = (int64_t)p.n_layers * p.n_chunks * p.h_kv;
     dim3 grid((unsigned)((waves + kScoreWaves - 1) / kScoreWaves));
+    const int64_t waves1 = (int64_t)p.n_layers * p.n_chunks_stats * p.h_kv;
+    dim3 grid1((unsigned)((waves1 + kScoreWaves - 1) / kScoreWaves));
     hipError_t e;
     if (lse) {  // normalisers supplied: no statistics pass over K
         const int64_t n_rows = (int64_t)p.n_layers * p.n_seq * p.h_kv * a.RP;
@@ -592,12 +639,12 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         if (e != hipSuccess) return e;
     } else {
         for (int rg = 0; rg < p.row_groups; ++rg) {
-            a.row_tile0 = rg * kMaxRowTiles;
-            const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
-            if ((e = launch_stats_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
+            a1.row_tile0 = rg * kMaxRowTiles;
+            const int nqt = min(kMaxRowTiles, p.row_tiles - a1.row_tile0);
+            if ((e = launch_stats_n(nqt, a1, grid1, st, marks)) != hipSuccess) return e;
         }
         const int64_t n_row_tiles = (int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles;
-        e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a);
+        e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a1);
         if (e != hipSuccess) return e;
     }
     for (int rg = 0; rg < p.row_groups; ++rg) {
