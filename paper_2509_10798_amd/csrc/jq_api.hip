@@ -49,6 +49,8 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     for (int s = 0; s <= sh->n_seq; ++s) p.tab.cu_seq[s] = sh->cu_seqlens[s];
     p.tab.cu_bud[0] = 0;
     for (int s = 0; s < sh->n_seq; ++s) {
+        // the score kernels address one head's rows of a sequence through a 32-bit buffer offset
+        if ((int64_t)(sh->cu_seqlens[s + 1] - sh->cu_seqlens[s]) * p.h_kv * kHeadDim * 2 > (int64_t)UINT32_MAX) return JQ_ERR_UNSUPPORTED;
         int32_t b = 1;
         if (sh->budgets) {
             b = sh->budgets[s];
@@ -62,40 +64,28 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     }
     p.TB = tb;
 
-    // One wave streams a chunk of keys of one head.  Small calls aim at one wave per hardware slot
-    // (256 CUs x 8 waves) in the second pass and at half as many, twice as long waves in the first,
-    // whose start-up (gathering the head's query rows) costs more than its smaller per-tile work can
-    // hide; the chunk is capped so that big calls run in several rounds.
-    const int64_t keys = (int64_t)p.n_layers * p.h_kv * p.T;
-    auto pick_chunk = [&](int64_t waves, int64_t cap, const char* knob) {
-        int64_t chunk = (keys + waves - 1) / waves;
-        chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
-        if (chunk < 64) chunk = 64;
-        if (chunk > cap) chunk = cap;
-        if (const char* env = std::getenv(knob)) {  // ablation knob
-            const long v = std::atol(env);
-            if (v >= kKeyTile && v <= 8192 && v % kKeyTile == 0) chunk = v;
-        }
-        return chunk;
-    };
-    auto chunk_table = [&](int64_t chunk, int32_t* cu) {
-        int64_t nc = 0;
-        cu[0] = 0;
-        for (int s = 0; s < sh->n_seq; ++s) {
-            const int64_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
-            nc += (L + chunk - 1) / chunk;
-            cu[s + 1] = (int32_t)nc;
-        }
-        return nc;
-    };
-    p.chunk_keys = (int32_t)pick_chunk(2048, 1024, "JQ_CHUNK_KEYS");
-    p.chunk_keys_stats = (int32_t)pick_chunk(1024, 1024, "JQ_CHUNK_KEYS_STATS");
-    if (std::getenv("JQ_CHUNK_KEYS") && !std::getenv("JQ_CHUNK_KEYS_STATS")) p.chunk_keys_stats = p.chunk_keys;
-    const int64_t nc2 = chunk_table(p.chunk_keys, p.tab.cu_chunk);
-    const int64_t nc = chunk_table(p.chunk_keys_stats, p.cu_chunk_stats);
-    p.n_chunks = (int32_t)nc2;
-    p.n_chunks_stats = (int32_t)nc;
-    if ((int64_t)p.n_layers * nc2 * p.h_kv / kScoreWaves >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
+    // A sequence of L keys is worked on by ceil(L / chunk_keys) waves per head (which share its 32-key tiles
+    // round-robin).  Small calls aim at one wave per SIMD (256 CUs x 4): start-up -- gathering the head's
+    // query rows -- is paid per wave, and one wave with two tiles in flight keeps its SIMD busy.  The cap
+    // makes big calls run in several rounds.
+    int64_t chunk = ((int64_t)p.n_layers * p.h_kv * p.T + 1023) / 1024;
+    chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
+    if (chunk < 64) chunk = 64;
+    if (chunk > 1024) chunk = 1024;
+    if (const char* env = std::getenv("JQ_CHUNK_KEYS")) {  // ablation knob
+        const long v = std::atol(env);
+        if (v >= kKeyTile && v <= 8192 && v % kKeyTile == 0) chunk = v;
+    }
+    p.chunk_keys = (int32_t)chunk;
+    int64_t nc = 0;
+    p.tab.cu_chunk[0] = 0;
+    for (int s = 0; s < sh->n_seq; ++s) {
+        const int64_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
+        nc += (L + chunk - 1) / chunk;
+        p.tab.cu_chunk[s + 1] = (int32_t)nc;
+    }
+    p.n_chunks = (int32_t)nc;
+    if ((int64_t)p.n_layers * nc * p.h_kv / kScoreWaves >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
     if ((int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
 
     const size_t RP = (size_t)p.row_tiles * kRowTile;

@@ -24,7 +24,7 @@ struct SeqTab {
     int32_t n_seq;
     int32_t cu_seq[JQ_MAX_SEQ + 1];    // token offsets
     int32_t cu_bud[JQ_MAX_SEQ + 1];    // kept-row offsets
-    int32_t cu_chunk[JQ_MAX_SEQ + 1];  // score-chunk offsets (chunk = `chunk_keys` keys of one sequence)
+    int32_t cu_chunk[JQ_MAX_SEQ + 1];  // score-wave offsets (ceil(L / chunk_keys) waves per sequence and head)
 };
 
 // Everything the host derives from a jq_shape.
@@ -33,10 +33,8 @@ struct Plan {
     int32_t rows;         // n_q * group: query rows that share one KV head
     int32_t row_tiles;    // ceil(rows / 32)
     int32_t row_groups;   // ceil(row_tiles / 4): passes of the score kernels over K
-    int32_t chunk_keys;   // keys one wave of the second K pass streams (multiple of 32); tab.cu_chunk counts these
-    int32_t n_chunks;     // such chunks per layer, over all sequences
-    int32_t chunk_keys_stats, n_chunks_stats;  // the same for the first K pass (softmax statistics)
-    int32_t cu_chunk_stats[JQ_MAX_SEQ + 1];
+    int32_t chunk_keys;   // a sequence of L keys gets ceil(L / chunk_keys) score waves per head (multiple of 32)
+    int32_t n_chunks;     // such waves per layer and head, over all sequences (tab.cu_chunk counts them)
     float scale;          // logit scale actually used
     int64_t T, TB;
     SeqTab tab;

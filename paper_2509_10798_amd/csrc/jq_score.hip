@@ -2,16 +2,15 @@
 // (paper Section 4.3, Eq. 3), as two K-streaming MFMA passes for gfx950.
 //
 //   pass 1 (stats):  per query row r, the running maximum m_r and Z_r = sum_j 2^(t_rj - m_r) of its
-//                    base-2 logits t_rj = c * q_r.k_j, c = scale * log2(e); one partial per
-//                    chunk of keys.
+//                    base-2 logits t_rj = c * q_r.k_j, c = scale * log2(e); one partial per wave.
 //   combine:         beta_r = m_r + log2 Z_r over a sequence's partials, stored as -beta_r / c split
 //                    into three bf16 terms.
 //   pass 2 (score):  score_j = sum_r 2^(c * (q_r.k_j - beta_r / c)).  The -beta_r/c term enters
 //                    through one extra MFMA step whose key-side operand is 1.0, so the epilogue is one
 //                    multiply, one exp2 and one add per logit.
 //
-// One wave owns one (layer, sequence, chunk of keys, KV head) and keeps that head's (up to) 128
-// query rows in registers as MFMA operands.  Gathering them from Q costs 32 row-strided loads per
+// One wave owns one (layer, sequence, KV head) and a strided set of that sequence's 32-key tiles, and
+// keeps the head's (up to) 128 query rows in registers as MFMA operands.  Gathering them from Q costs 32 row-strided loads per
 // wave (each touches 32 cache lines), so whoever reads Q first -- pass 1, or the kernel that converts
 // caller-supplied normalisers -- also leaves a copy in operand order, which pass 2 reads with fully
 // coalesced loads.  Key tiles of 32 keys x 128 channels are fetched
@@ -25,6 +24,8 @@
 // contraction elements selected by (l >> 5); both operands use the same element order, so any
 // fixed channel permutation cancels.  Result: lane l holds column (l & 31), register v holds row
 // 8*(v/4) + 4*(l>>5) + (v&3).
+#include <type_traits>
+
 #include "jq_common.h"
 
 namespace jq {
@@ -75,11 +76,16 @@ __device__ __forceinline__ void wait_frags_read() {
     asm volatile("" ::: "memory");
 }
 
-// Which (layer, sequence, key range, head) this wave owns.
+// Which (layer, sequence, head) and which of its key tiles this wave owns.  A sequence of L keys gets
+// W = ceil(L / chunk_keys) waves per head; wave w of them takes the 32-key tiles w, w + W, w + 2W, ...
+// Interleaving the tiles (instead of giving each wave one contiguous range) makes all waves that run
+// at the same time sweep one window of the key tensor, which DRAM serves at close to its streaming rate.
 struct WaveItem {
-    int layer, seq, g, chunk_global;
-    int k_begin, k_end;  // sequence-local key range
-    int64_t tok0;        // first token of the sequence in the flattened T axis
+    int layer, seq, g, chunk_global;  // chunk_global: the wave's slot in the per-chunk statistics
+    int wave, n_waves;                // w and W
+    int L;                            // keys in the sequence
+    int n_tiles;                      // tiles this wave owns
+    int64_t tok0;                     // first token of the sequence in the flattened T axis
 };
 
 __device__ __forceinline__ bool wave_item(const ScoreArgs& a, bool reverse, WaveItem& w) {
@@ -93,9 +99,11 @@ __device__ __forceinline__ bool wave_item(const ScoreArgs& a, bool reverse, Wave
     w.chunk_global = (int)(rest % a.n_chunks);
     w.layer = (int)(rest / a.n_chunks);
     w.seq = find_seq(a.tab.cu_chunk, a.tab.n_seq, w.chunk_global);
-    const int L = a.tab.cu_seq[w.seq + 1] - a.tab.cu_seq[w.seq];
-    w.k_begin = (w.chunk_global - a.tab.cu_chunk[w.seq]) * a.chunk_keys;
-    w.k_end = min(L, w.k_begin + a.chunk_keys);
+    w.L = a.tab.cu_seq[w.seq + 1] - a.tab.cu_seq[w.seq];
+    w.wave = w.chunk_global - a.tab.cu_chunk[w.seq];
+    w.n_waves = a.tab.cu_chunk[w.seq + 1] - a.tab.cu_chunk[w.seq];
+    const int seq_tiles = (w.L + kKeyTile - 1) / kKeyTile;  // >= n_waves, since a chunk is at least one tile
+    w.n_tiles = (seq_tiles - w.wave + w.n_waves - 1) / w.n_waves;
     w.tok0 = a.tab.cu_seq[w.seq];
     return true;
 }
@@ -234,21 +242,18 @@ __device__ __forceinline__ void load_q_via_lds(const ScoreArgs& a, const WaveIte
 }
 
 struct KeyStream {
-    __amdgpu_buffer_rsrc_t rsrc;
+    __amdgpu_buffer_rsrc_t rsrc;  // this head's rows of the whole sequence
     uint32_t row_bytes;
-    int n_keys, n_tiles;
 };
 
 __device__ __forceinline__ KeyStream key_stream(const ScoreArgs& a, const WaveItem& w) {
     KeyStream ks;
     ks.row_bytes = (uint32_t)a.h_kv * kHeadDim * 2;
-    ks.n_keys = w.k_end - w.k_begin;
-    ks.n_tiles = (ks.n_keys + kKeyTile - 1) / kKeyTile;
-    const char* kchunk =
-        (const char*)a.K + (((int64_t)w.layer * a.T + w.tok0 + w.k_begin) * a.h_kv + w.g) * kHeadDim * 2;
-    // the resource covers exactly this head's rows of the chunk; every generated offset stays inside it
-    const uint32_t bytes = (uint32_t)(ks.n_keys - 1) * ks.row_bytes + kHeadDim * 2;
-    ks.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kchunk, 0, (int)bytes, 0x00020000);
+    const char* kseq = (const char*)a.K + (((int64_t)w.layer * a.T + w.tok0) * a.h_kv + w.g) * kHeadDim * 2;
+    // the resource covers exactly this head's rows of the sequence (the host checks that this is below
+    // 4 GiB); every generated offset stays inside it
+    const uint32_t bytes = (uint32_t)(w.L - 1) * ks.row_bytes + kHeadDim * 2;
+    ks.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kseq, 0, (int)bytes, 0x00020000);
     return ks;
 }
 
@@ -265,7 +270,10 @@ __device__ __forceinline__ f32x16 stats_chain(const bf16x8 (&kf)[8], const bf16x
     return acc;
 }
 
-template <int NQT, bool MASKED>
+// FIXED: keep the offsets m as they are and only accumulate Z += sum 2^(t - m).  Any offset gives the same
+// (m, Z) pair up to rounding as long as no term overflows; terms that underflow are negligible next to
+// the 2^0 the offset's own key contributed.
+template <int NQT, bool MASKED, bool FIXED>
 __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (&qf)[NQT][8], float (&m)[NQT],
                                            float (&z)[NQT], float c, int valid, int half) {
     // software pipeline: the MFMA chain of query tile qt+1 is interleaved with the max/exp2/add work of tile qt
@@ -279,10 +287,13 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
             for (int v = 0; v < 16; ++v)
                 if (8 * (v >> 2) + 4 * half + (v & 3) >= valid) acc[v] = -INFINITY;
         }
-        float tmax = fmaxf(acc[0], acc[1]);
+        float mnew = m[qt];
+        if (!FIXED) {
+            float tmax = fmaxf(acc[0], acc[1]);
 #pragma unroll
-        for (int v = 2; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
-        const float mnew = fmaxf(m[qt], tmax * c);
+            for (int v = 2; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
+            mnew = fmaxf(m[qt], tmax * c);
+        }
         float s0 = __builtin_amdgcn_exp2f(fmaf(acc[0], c, -mnew));
         float s1 = __builtin_amdgcn_exp2f(fmaf(acc[1], c, -mnew));
         float s2 = __builtin_amdgcn_exp2f(fmaf(acc[2], c, -mnew));
@@ -294,8 +305,12 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
             s2 += __builtin_amdgcn_exp2f(fmaf(acc[v + 2], c, -mnew));
             s3 += __builtin_amdgcn_exp2f(fmaf(acc[v + 3], c, -mnew));
         }
-        z[qt] = z[qt] * __builtin_amdgcn_exp2f(m[qt] - mnew) + ((s0 + s1) + (s2 + s3));
-        m[qt] = mnew;
+        if (FIXED) {
+            z[qt] += (s0 + s1) + (s2 + s3);
+        } else {
+            z[qt] = z[qt] * __builtin_amdgcn_exp2f(m[qt] - mnew) + ((s0 + s1) + (s2 + s3));
+            m[qt] = mnew;
+        }
         if (qt + 1 < NQT) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -319,41 +334,68 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 
     const KeyStream ks = key_stream(a, w);
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
+    // the wave's k-th tile is tile w.wave + k * w.n_waves of the sequence and uses slot k & 1
+    auto fetch = [&](int k) {
+        const int t = w.wave + k * w.n_waves;
+        fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, (uint32_t)t * kKeyTile * ks.row_bytes, ks.row_bytes,
+                   w.L - t * kKeyTile, tl, lane);
+    };
     // The first key tile goes to slot 0 at once; slot 1 first serves as the staging area that turns the
     // query rows into operand order, then takes the second tile.  From then on two tiles are always in
     // flight: a slot is refilled as soon as its fragments are in registers.
-    fetch_tile(ks.rsrc, slots, 0u, ks.row_bytes, ks.n_keys, tl, lane);
+    fetch(0);
     bf16x8 qf[NQT][8];
     load_q_via_lds<NQT>(a, w, lane, slots + kSlotBytes, qf);
-    if (w.k_begin == 0) store_q_frags<NQT>(a, w, lane, qf);  // the sequence's first chunk leaves the operand-order copy
+    if (w.wave == 0) store_q_frags<NQT>(a, w, lane, qf);  // the sequence's first wave leaves the operand-order copy
     wait_frags_read();
-    if (ks.n_tiles > 1)
-        fetch_tile(ks.rsrc, slots + kSlotBytes, kKeyTile * ks.row_bytes, ks.row_bytes, ks.n_keys - kKeyTile, tl, lane);
+    if (w.n_tiles > 1) fetch(1);
     const float c = a.c;
 
     float m[NQT], z[NQT];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
 
-    // every load older than the second tile's eight (first tile, query rows, operand-order copy) is covered
-    // by the first wait below
-    const int n_full = ks.n_keys / kKeyTile;
-    for (int t = 0; t < n_full; ++t) {
-        wait_tile_landed(t + 1 < ks.n_tiles);
+    // Every load older than the second tile's eight (first tile, query rows, operand-order copy) is covered
+    // by the first wait of the sweep.  Only the sequence's last tile can be partial, and it is some wave's last.
+    const int last_valid = w.L - (w.wave + (w.n_tiles - 1) * w.n_waves) * kKeyTile;
+    const int n_full = last_valid >= kKeyTile ? w.n_tiles : w.n_tiles - 1;
+    // One sweep over the wave's tiles (the first two are already requested).  FAST: the first tile sets each
+    // lane's offset m to the maximum of its logits there, later tiles keep it -- no maximum to track.
+    auto full_tile = [&](int k, auto fixed) {
+        wait_tile_landed(k + 1 < w.n_tiles);
         bf16x8 kf[8];
-        lds_get_frags(slots + (t & 1) * kSlotBytes, kf, lane);
-        if (t + 2 < ks.n_tiles) {
+        lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
+        if (k + 2 < w.n_tiles) {
             wait_frags_read();
-            fetch_tile(ks.rsrc, slots + (t & 1) * kSlotBytes, (uint32_t)(t + 2) * kKeyTile * ks.row_bytes, ks.row_bytes,
-                       ks.n_keys - (t + 2) * kKeyTile, tl, lane);
+            fetch(k + 2);
         }
-        stats_tile<NQT, false>(kf, qf, m, z, c, kKeyTile, half);
-    }
-    if (n_full < ks.n_tiles) {  // partial last tile
-        wait_tile_landed(false);
-        bf16x8 kf[8];
-        lds_get_frags(slots + (n_full & 1) * kSlotBytes, kf, lane);
-        stats_tile<NQT, true>(kf, qf, m, z, c, ks.n_keys - n_full * kKeyTile, half);
+        stats_tile<NQT, false, decltype(fixed)::value>(kf, qf, m, z, c, kKeyTile, half);
+    };
+    auto sweep = [&](auto fast) {
+        if (n_full > 0) full_tile(0, std::false_type{});
+        for (int k = 1; k < n_full; ++k) full_tile(k, fast);
+        if (n_full < w.n_tiles) {  // partial last tile
+            wait_tile_landed(false);
+            bf16x8 kf[8];
+            lds_get_frags(slots + (n_full & 1) * kSlotBytes, kf, lane);
+            if (decltype(fast)::value && n_full > 0) stats_tile<NQT, true, true>(kf, qf, m, z, c, last_valid, half);
+            else stats_tile<NQT, true, false>(kf, qf, m, z, c, last_valid, half);
+        }
+    };
+    sweep(std::true_type{});
+    // A logit more than 2^7 (base 2) above the first tile's maximum overflows 2^(t - m) to infinity.  That
+    // cannot be repaired afterwards, so such a wave (wave-uniform decision) repeats its sweep with the
+    // running maximum.
+    bool overflow = false;
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) overflow |= !(z[qt] < INFINITY);
+    if (__any(overflow)) {
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
+        wait_frags_read();
+        fetch(0);
+        if (w.n_tiles > 1) fetch(1);
+        sweep(std::false_type{});
     }
 
     // lanes l and l+32 hold the same query rows over complementary keys: merge, then one partial per chunk
@@ -495,9 +537,16 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
 
     const KeyStream ks = key_stream(a, w);
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
-    fetch_tile(ks.rsrc, slots, 0u, ks.row_bytes, ks.n_keys, tl, lane);
-    if (ks.n_tiles > 1)
-        fetch_tile(ks.rsrc, slots + kSlotBytes, kKeyTile * ks.row_bytes, ks.row_bytes, ks.n_keys - kKeyTile, tl, lane);
+    // The wave walks its tiles from the last to the first (pass 1 swept the keys front to back, so the end
+    // of the sequence is what the caches still hold): its k-th tile here is sequence tile tile_of(k).
+    auto tile_of = [&](int k) { return w.wave + (w.n_tiles - 1 - k) * w.n_waves; };
+    auto fetch = [&](int k) {
+        const int t = tile_of(k);
+        fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, (uint32_t)t * kKeyTile * ks.row_bytes, ks.row_bytes,
+                   w.L - t * kKeyTile, tl, lane);
+    };
+    fetch(0);
+    if (w.n_tiles > 1) fetch(1);
 
     bf16x8 qf[NQT][8];
     load_q_frags<NQT>(a, w, lane, qf);
@@ -517,24 +566,27 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     if (half == 0) { ones_bits[0] = 0x3F803F80u; ones_bits[1] = 0x00003F80u; }  // 1.0 at elements 0..2
     const bf16x8 ones = as_bf16x8(ones_bits);
 
-    float* out = a.scores + ((int64_t)w.layer * a.h_kv + w.g) * a.T + w.tok0 + w.k_begin;
+    float* out = a.scores + ((int64_t)w.layer * a.h_kv + w.g) * a.T + w.tok0;
     const float c = a.c;
     float pending = 0.f;  // previous tile's result, stored one iteration late so that the store has a
                           // whole tile of compute to retire before the next wait on outstanding loads
+    auto store_tile = [&](int k, float v) {  // only the sequence's last tile can be partial
+        const int t = tile_of(k);
+        if (lane < 32 && t * kKeyTile + lane < w.L) {
+            float* o = out + t * kKeyTile + lane;
+            *o = a.accumulate ? *o + v : v;
+        }
+    };
 
     __builtin_amdgcn_s_waitcnt(0x0F70);  // Q, the -beta/c terms and the first two tiles are in
-    for (int t = 0; t < ks.n_tiles; ++t) {
-        if (t > 0) wait_tile_landed(t + 1 < ks.n_tiles);
+    for (int k = 0; k < w.n_tiles; ++k) {
+        if (k > 0) wait_tile_landed(k + 1 < w.n_tiles);
         bf16x8 kf[8];
-        lds_get_frags(slots + (t & 1) * kSlotBytes, kf, lane);
-        if (t > 0 && lane < 32) {  // tile t-1 was full (only the last tile can be partial)
-            float* o = out + (t - 1) * kKeyTile + lane;
-            *o = a.accumulate ? *o + pending : pending;
-        }
-        if (t + 2 < ks.n_tiles) {  // issued after the store: only these 8 loads are newer than tile t+1
+        lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
+        if (k > 0) store_tile(k - 1, pending);
+        if (k + 2 < w.n_tiles) {  // issued after the store: only these 8 loads are newer than tile k+1
             wait_frags_read();
-            fetch_tile(ks.rsrc, slots + (t & 1) * kSlotBytes, (uint32_t)(t + 2) * kKeyTile * ks.row_bytes, ks.row_bytes,
-                       ks.n_keys - (t + 2) * kKeyTile, tl, lane);
+            fetch(k + 2);
         }
         // Software pipeline over the query-row tiles: the MFMA chain of tile qt+1 is issued between the
         // exp2/add instructions of tile qt (a wave issues in order, so without interleaving its VALU work
@@ -566,14 +618,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         s += __shfl_xor(s, 32);  // the two lane halves hold complementary query rows of the same key
         pending = s;
     }
-    {
-        const int t = ks.n_tiles - 1;
-        const int valid = ks.n_keys - t * kKeyTile;
-        if (lane < 32 && lane < valid) {
-            float* o = out + t * kKeyTile + lane;
-            *o = a.accumulate ? *o + pending : pending;
-        }
-    }
+    store_tile(w.n_tiles - 1, pending);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -619,16 +664,10 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.T = p.T;
     a.zero = zero; a.zero_words = zero_words;
     a.tab = p.tab;
-    // the two K passes cut the sequences into chunks of their own size
     a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
-    ScoreArgs a1 = a;
-    a1.chunk_keys = p.chunk_keys_stats; a1.n_chunks = p.n_chunks_stats;
-    for (int s = 0; s <= p.n_seq; ++s) a1.tab.cu_chunk[s] = p.cu_chunk_stats[s];
 
     const int64_t waves = (int64_t)p.n_layers * p.n_chunks * p.h_kv;
     dim3 grid((unsigned)((waves + kScoreWaves - 1) / kScoreWaves));
-    const int64_t waves1 = (int64_t)p.n_layers * p.n_chunks_stats * p.h_kv;
-    dim3 grid1((unsigned)((waves1 + kScoreWaves - 1) / kScoreWaves));
     hipError_t e;
     if (lse) {  // normalisers supplied: no statistics pass over K
         const int64_t n_rows = (int64_t)p.n_layers * p.n_seq * p.h_kv * a.RP;
@@ -639,12 +678,12 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         if (e != hipSuccess) return e;
     } else {
         for (int rg = 0; rg < p.row_groups; ++rg) {
-            a1.row_tile0 = rg * kMaxRowTiles;
-            const int nqt = min(kMaxRowTiles, p.row_tiles - a1.row_tile0);
-            if ((e = launch_stats_n(nqt, a1, grid1, st, marks)) != hipSuccess) return e;
+            a.row_tile0 = rg * kMaxRowTiles;
+            const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
+            if ((e = launch_stats_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
         }
         const int64_t n_row_tiles = (int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles;
-        e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a1);
+        e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a);
         if (e != hipSuccess) return e;
     }
     for (int rg = 0; rg < p.row_groups; ++rg) {

@@ -61,6 +61,33 @@ def test_score_with_peaked_softmax_and_custom_scale():
     run_score_case(1, [1500], 16, 8, 2, seed=12, scale=0.35, spread=1.5)
 
 
+@pytest.mark.parametrize("alpha,where", [(9.0, 3500), (9.0, 3), (7.0, 4999), (30.0, 2048), (9.0, 31)])
+def test_score_with_one_dominant_key(monkeypatch, alpha, where):
+    # The statistics pass keeps the first tile's maximum as the softmax offset of a query row.  A key that
+    # aligns with a query row, planted late, exceeds that offset by more than fp32 exp2 can hold
+    # (alpha >= 9: the wave must fall back to the running maximum), by a large but representable factor
+    # (alpha = 7), or sits in the first tile itself, so that every later term underflows.
+    print("score dominant key", alpha, where, flush=True)
+    torch = torch_()
+    monkeypatch.setenv("JQ_CHUNK_KEYS", "1024")            # long waves: many tiles after the first
+    rng = np.random.default_rng(15)
+    L, n_q, h_q, h_kv, d = 5000, 16, 8, 2, 128
+    Qf = rng.standard_normal((1, 1, n_q, h_q, d)).astype(np.float32)
+    Kf = rng.standard_normal((1, L, h_kv, d)).astype(np.float32)
+    Kf[0, where, 0] = alpha * Qf[0, 0, 5, 1]               # head 0 of K <- query row (token 5, head 1 of group 0)
+    Kf[0, where, 1] = alpha * Qf[0, 0, 2, 6]
+    Q, K = f32_to_bf16_bits(Qf), f32_to_bf16_bits(Kf)
+    sh = jq.Shape(n_layers=1, seq_lens=[L], n_q=n_q, h_q=h_q, h_kv=h_kv)
+    got = jq.score(sh, to_dev_bf16(Q), to_dev_bf16(K))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()[0]
+    ref = oracle.score(Q[0, 0], K[0])
+    assert np.isfinite(got).all()
+    assert_scores_close(got, ref, n_q * (h_q // h_kv) / L, "dominant key")
+    np.testing.assert_allclose(got.sum(axis=1), n_q * (h_q // h_kv), rtol=1e-4)
+    assert ref[0, where] > 0.99 and got[0, where] > 0.99   # that query row's whole mass sits on the planted key
+
+
 def test_score_several_chunks_per_sequence(monkeypatch):
     # force 64-key chunks so that one sequence is split over many waves and partial statistics merge
     print("score chunked", flush=True)
