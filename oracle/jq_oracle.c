@@ -21,7 +21,8 @@
  * Pins (tests/test_oracle_*.py): hand-worked 3-key softmax, row-sum invariant,
  * L=1, zero queries, key-shift invariance, permutation/duplication laws, GQA
  * mapping by construction, brute force without max subtraction, numpy
- * cross-checks; pooling impulse/constant/weight identities; exhaustive subset
+ * cross-checks; the supplied-normaliser and soft-token-tail variants by hand-worked cases, by reduction
+ * to jqo_score and by numpy with explicit keys; pooling impulse/constant/weight identities; exhaustive subset
  * search for top-B; numpy.take for compaction.
  */
 #include <math.h>
@@ -158,6 +159,67 @@ int jqo_score_lse(int n_q, int h_q, int h_kv, int d, long L, double scale, const
                 }
             score[(size_t)g * L + j] = total;
         }
+    return 0;
+}
+
+/*
+ * Importance scores with the soft tokens' own keys in the softmax (Section 4.2: the soft tokens are
+ * appended to the prompt; Section 4.3 / Eq. 3: their attention over the prompt is the score).
+ *
+ * In a causal model soft token i attends to the L prompt keys and to soft tokens 0..i (itself
+ * included), so with the soft tokens' keys Kt given explicitly
+ *
+ *   Z[h,i]     = sum_{j < L} exp(s[h,i,j]) + sum_{i' <= i} exp(scale * Q[i,h,:] . Kt[i',g,:])
+ *   p[h,i,j]   = exp(s[h,i,j]) / Z[h,i]                      (prompt keys only are scored)
+ *   score[g,j] = sum_{h in group g} sum_i p[h,i,j]
+ *
+ * Reading: "causal" includes the diagonal (a token attends to itself), as in every decoder-only model
+ * the paper evaluates.  The same function scores a prompt under its own last n_q tokens (the
+ * observation window of the SnapKV-style baselines in Section 5.1): pass the window's queries and keys.
+ * Kt is [n_q, h_kv, d] bf16 bits.  Two passes per row, like jqo_score, with the maximum taken over both parts.
+ */
+int jqo_score_tail(int n_q, int h_q, int h_kv, int d, long L, double scale, const uint16_t* Q, const uint16_t* K,
+                   const uint16_t* Kt, double* score) {
+    if (n_q < 1 || h_q < 1 || h_kv < 1 || d < 1 || L < 1 || h_q % h_kv != 0 || !Q || !K || !Kt || !score) return -1;
+    const int G = h_q / h_kv;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
+    double* mz = (double*)malloc(sizeof(double) * 2 * (size_t)n_q * h_q);  /* (m, Z) per (i, h) */
+    if (!mz) return -1;
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+    for (int i = 0; i < n_q; ++i)
+        for (int h = 0; h < h_q; ++h) {
+            const int g = h / G;
+            const uint16_t* q = Q + ((size_t)i * h_q + h) * d;
+            double m = -INFINITY;
+            for (int pass = 0; pass < 2; ++pass) {
+                double z = 0.0;
+                for (long j = 0; j < L + i + 1; ++j) {  /* the L prompt keys, then soft tokens 0..i */
+                    const uint16_t* k = j < L ? K + ((size_t)j * h_kv + g) * d : Kt + ((size_t)(j - L) * h_kv + g) * d;
+                    double acc = 0.0;
+                    for (int c = 0; c < d; ++c) acc += bf16_to_f64(q[c]) * bf16_to_f64(k[c]);
+                    const double sv = acc * scale;
+                    if (pass == 0) { if (sv > m) m = sv; }
+                    else z += exp(sv - m);
+                }
+                if (pass == 1) { mz[2 * ((size_t)i * h_q + h)] = m; mz[2 * ((size_t)i * h_q + h) + 1] = z; }
+            }
+        }
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int g = 0; g < h_kv; ++g)
+        for (long j = 0; j < L; ++j) {
+            const uint16_t* k = K + ((size_t)j * h_kv + g) * d;
+            double total = 0.0;
+            for (int hh = 0; hh < G; ++hh)
+                for (int i = 0; i < n_q; ++i) {
+                    const int h = g * G + hh;
+                    const uint16_t* q = Q + ((size_t)i * h_q + h) * d;
+                    double acc = 0.0;
+                    for (int c = 0; c < d; ++c) acc += bf16_to_f64(q[c]) * bf16_to_f64(k[c]);
+                    total += exp(acc * scale - mz[2 * ((size_t)i * h_q + h)]) / mz[2 * ((size_t)i * h_q + h) + 1];
+                }
+            score[(size_t)g * L + j] = total;
+        }
+    free(mz);
     return 0;
 }
 

@@ -37,10 +37,11 @@ def _load():
         lib.jqo_num_threads.restype = ctypes.c_int
         lib.jqo_score.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p]
         lib.jqo_score_lse.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p, f64p]
+        lib.jqo_score_tail.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, u16p, f64p]
         lib.jqo_pool.argtypes = [ctypes.c_long, ctypes.c_int, f64p, f64p]
         lib.jqo_select_topk.argtypes = [ctypes.c_long, ctypes.c_long, f64p, i32p]
         lib.jqo_compact.argtypes = [ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_long, u16p, u16p, i32p, u16p, u16p]
-        for f in (lib.jqo_score, lib.jqo_score_lse, lib.jqo_pool, lib.jqo_select_topk, lib.jqo_compact):
+        for f in (lib.jqo_score, lib.jqo_score_lse, lib.jqo_score_tail, lib.jqo_pool, lib.jqo_select_topk, lib.jqo_compact):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -82,6 +83,20 @@ def score_lse(Q: np.ndarray, K: np.ndarray, lse: np.ndarray, scale: float = 0.0)
     return out
 
 
+def score_tail(Q: np.ndarray, K: np.ndarray, K_tail: np.ndarray, scale: float = 0.0) -> np.ndarray:
+    """Scores with the soft tokens' own keys K_tail [n_q, h_kv, d] in each row's softmax, causally (i' <= i)."""
+    Q = np.ascontiguousarray(Q, dtype=np.uint16)
+    K = np.ascontiguousarray(K, dtype=np.uint16)
+    K_tail = np.ascontiguousarray(K_tail, dtype=np.uint16)
+    n_q, h_q, d = Q.shape
+    L, h_kv, d2 = K.shape
+    if d != d2 or K_tail.shape != (n_q, h_kv, d):
+        raise ValueError("shape mismatch")
+    out = np.empty((h_kv, L), dtype=np.float64)
+    _check(_load().jqo_score_tail(n_q, h_q, h_kv, d, L, float(scale), Q, K, K_tail, out), "score_tail")
+    return out
+
+
 def pool(scores: np.ndarray, pool_k: int) -> np.ndarray:
     """scores [h_kv, L] (or [L]) float64 -> pooled, same shape."""
     s = np.ascontiguousarray(scores, dtype=np.float64)
@@ -115,11 +130,17 @@ def compact(K: np.ndarray, V: np.ndarray, idx: np.ndarray):
     return Ko, Vo
 
 
-def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None):
+def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None, K_tail=None):
     """One (layer, sequence): score -> pool -> top-B -> gather.  Returns a dict.
 
-    With `lse` the scores are the slice-of-a-wider-softmax variant (score_lse)."""
-    s = score(Q, K, scale) if lse is None else score_lse(Q, K, lse, scale)
+    With `lse` the scores are the slice-of-a-wider-softmax variant (score_lse), with `K_tail` the
+    variant whose softmax also covers the soft tokens' own keys (score_tail)."""
+    if lse is not None:
+        s = score_lse(Q, K, lse, scale)
+    elif K_tail is not None:
+        s = score_tail(Q, K, K_tail, scale)
+    else:
+        s = score(Q, K, scale)
     p = pool(s, pool_k)
     idx = select_topk(p, B)
     Ko, Vo = compact(K, V, idx)

@@ -206,3 +206,75 @@ def test_score_lse_rejects_wrong_lse_shape():
     Q = np.zeros((2, 2, 4), dtype=np.uint16); K = np.zeros((3, 2, 4), dtype=np.uint16)
     with pytest.raises(ValueError):
         oracle.score_lse(Q, K, np.zeros((2, 3)))
+
+
+# ---------------------------------------------------------------- soft tokens' own keys in the softmax (causal tail)
+def test_score_tail_hand_worked_powers_of_two(golden_dir):
+    want = np.loadtxt(os.path.join(golden_dir, "softmax_with_soft_token_tail.txt"))
+    q = bits([[[1.0]], [[1.0]]])                 # n_q=2, h_q=1, d=1
+    k = bits([[[0.0]], [[1.0]]])                 # L=2
+    kt = bits([[[2.0]], [[0.0]]])                # soft-token keys
+    got = oracle.score_tail(q, k, kt, scale=math.log(2.0))
+    np.testing.assert_allclose(got[0], want, rtol=1e-15)
+    # dropping the diagonal (token not attending to itself) would give (1/3 + 1/7, 2/3 + 2/7); seeing the
+    # future key from token 0 would give (1/8 + 1/8, 2/8 + 2/8): both are far from the stored values
+    assert abs(got[0, 0] - (1 / 3 + 1 / 7)) > 0.1 and abs(got[0, 0] - 0.25) > 0.01
+
+
+def test_score_tail_single_soft_token_is_plain_softmax_over_prompt_plus_itself():
+    # with one soft token its row is the ordinary softmax over the L + 1 keys: the already pinned
+    # jqo_score on the concatenated keys, prompt columns only
+    rng = np.random.default_rng(21)
+    Q, K, Kt = rand_bits(rng, (1, 4, 16)), rand_bits(rng, (50, 2, 16)), rand_bits(rng, (1, 2, 16))
+    want = oracle.score(Q, np.concatenate([K, Kt], axis=0))[:, :50]
+    np.testing.assert_allclose(oracle.score_tail(Q, K, Kt), want, rtol=1e-12)
+
+
+def test_score_tail_matches_numpy_with_causal_mask_and_the_lse_variant():
+    rng = np.random.default_rng(22)
+    n_q, h_q, h_kv, d, L = 5, 6, 2, 8, 33
+    Q, K, Kt = rand_bits(rng, (n_q, h_q, d), 1.5), rand_bits(rng, (L, h_kv, d)), rand_bits(rng, (n_q, h_kv, d), 2.0)
+    s, st = numpy_logits(Q, K), numpy_logits(Q, Kt)
+    causal = np.tril(np.ones((n_q, n_q), dtype=bool))[:, None, :]
+    z_all = np.exp(s).sum(axis=2) + np.where(causal, np.exp(st), 0.0).sum(axis=2)
+    want = (np.exp(s) / z_all[..., None]).sum(axis=0).reshape(h_kv, h_q // h_kv, L).sum(axis=1)
+    got = oracle.score_tail(Q, K, Kt)
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+    np.testing.assert_allclose(got, oracle.score_lse(Q, K, np.log(z_all)), rtol=1e-12)
+
+
+def test_score_tail_is_causal_and_uses_the_right_kv_head():
+    rng = np.random.default_rng(23)
+    n_q, h_q, h_kv, d, L = 3, 4, 2, 8, 17
+    Q, K, Kt = rand_bits(rng, (n_q, h_q, d)), rand_bits(rng, (L, h_kv, d)), rand_bits(rng, (n_q, h_kv, d))
+    base = oracle.score_tail(Q, K, Kt)
+    # the last soft token's key is seen by the last soft token only: with n_q = 1 rows nothing else changes
+    Kt2 = Kt.copy(); Kt2[2] = bits(rng.standard_normal((h_kv, d)).astype(np.float32) * 3)
+    first_two = oracle.score_tail(Q[:2], K, Kt[:2])
+    np.testing.assert_allclose(oracle.score_tail(Q[:2], K, Kt2[:2]), first_two, rtol=0)
+    changed = oracle.score_tail(Q, K, Kt2)
+    last_old = base - first_two                    # contribution of soft token 2 alone (scores add over rows)
+    last_new = changed - first_two
+    assert not np.allclose(last_old, last_new)
+    # soft-token keys of KV head 1 never touch the scores of KV head 0
+    Kt3 = Kt.copy(); Kt3[:, 1] = bits(rng.standard_normal((n_q, d)).astype(np.float32) * 3)
+    np.testing.assert_allclose(oracle.score_tail(Q, K, Kt3)[0], base[0], rtol=0)
+    assert not np.allclose(oracle.score_tail(Q, K, Kt3)[1], base[1])
+
+
+def test_score_tail_vanishing_tail_keys_give_the_prompt_only_scores():
+    # soft-token keys pointing away from every query (logit about -|q|^2 * 40 * scale) carry no mass
+    rng = np.random.default_rng(24)
+    Q, K = rand_bits(rng, (2, 2, 16)), rand_bits(rng, (40, 2, 16))
+    Qd = bf16_bits_to_f64(Q)
+    Kt = bits((-40.0 * Qd.sum(axis=0)).astype(np.float32))       # [h_kv = h_q, d]: against both soft tokens' queries
+    Kt = np.stack([Kt, Kt])
+    logits = np.einsum("ihc,thc->iht", Qd, bf16_bits_to_f64(Kt)) / 4.0
+    assert logits.max() < -50                                      # the construction did what it should
+    np.testing.assert_allclose(oracle.score_tail(Q, K, Kt), oracle.score(Q, K), rtol=1e-12)
+
+
+def test_score_tail_rejects_wrong_shape():
+    Q = np.zeros((2, 2, 4), dtype=np.uint16); K = np.zeros((3, 2, 4), dtype=np.uint16)
+    with pytest.raises(ValueError):
+        oracle.score_tail(Q, K, np.zeros((3, 2, 4), dtype=np.uint16))
