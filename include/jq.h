@@ -108,6 +108,20 @@ int jq_score(const jq_shape* shape, const void* Q, const void* K, float* scores,
 int jq_score_lse(const jq_shape* shape, const void* Q, const void* K, const float* lse,
                  float* scores, void* ws, size_t ws_bytes, void* stream);
 
+/* The scores with the soft tokens' own keys in the softmax (Section 4.2: the soft tokens
+ * are appended to the prompt, so in a causal model soft token i attends to the prompt
+ * and to soft tokens 0..i, itself included).  K_tail (DEVICE, bf16,
+ * [n_layers, n_seq, n_q, h_kv, d]) holds those keys:
+ *   Z[l,s,i,h]    = sum_{j in sequence s} exp(scale * Q[l,s,i,h,:].K[l,j,g,:])
+ *                 + sum_{i' <= i} exp(scale * Q[l,s,i,h,:].K_tail[l,s,i',g,:])
+ *   scores[l,g,t] = sum_{h in group g} sum_i exp(scale * Q[l,s,i,h,:].K[l,t,g,:]) / Z[l,s,i,h].
+ * Two passes over K like jq_score; the tail only enters the normalisers.  The same call
+ * scores a prompt under its own last n_q tokens (the observation window of the
+ * SnapKV-style baselines of Section 5.1): pass the prompt without the window as K and
+ * the window's queries and keys as Q and K_tail. */
+int jq_score_tail(const jq_shape* shape, const void* Q, const void* K, const void* K_tail, float* scores,
+                  void* ws, size_t ws_bytes, void* stream);
+
 /* pooled[l,g,t] = (1/pool_k) * sum_{|u| <= (pool_k-1)/2} scores[l,g,t+u], taking
  * zero for positions outside t's own sequence (divisor is always pool_k).
  * `pooled` must not overlap `scores`. */
@@ -137,6 +151,11 @@ int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V,
 int jq_evict_lse(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,
                  void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
                  void* ws, size_t ws_bytes, void* stream);
+
+/* jq_evict with the soft tokens' own keys in the softmax (see jq_score_tail). */
+int jq_evict_tail(const jq_shape* shape, const void* Q, const void* K, const void* V, const void* K_tail,
+                  void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
+                  void* ws, size_t ws_bytes, void* stream);
 
 /* jq_evict with kernel timing (the measurement hook of the benchmark): `marks` is a
  * HOST array of JQ_TRACE_MARKS hipEvent_t (passed as void*), created by the caller.

@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced",
            "jq_copy_probe", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_combine_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel",
                  "jq_select_finalize_kernel", "jq_compact_kernel")
@@ -58,6 +58,8 @@ def lib() -> ctypes.CDLL:
         L.jq_score.argtypes = [shp, vp, vp, vp, vp, sz, vp]
         L.jq_score_lse.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_lse.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_score_tail.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_evict_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_pool.argtypes = [shp, vp, vp, vp]
         L.jq_select_topk.argtypes = [shp, vp, vp, vp, sz, vp]
         L.jq_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp]
@@ -144,8 +146,9 @@ def alloc_workspace(shape: Shape, device="cuda"):
     return torch.empty(workspace_bytes(shape), dtype=torch.uint8, device=device)
 
 
-def score(shape: Shape, Q, K, scores=None, ws=None, stream=None, lse=None):
-    """Unpooled scores; with `lse` ([n_layers, n_seq, n_q, h_q] fp32) the one-pass supplied-normaliser variant."""
+def score(shape: Shape, Q, K, scores=None, ws=None, stream=None, lse=None, k_tail=None):
+    """Unpooled scores; with `lse` ([n_layers, n_seq, n_q, h_q] fp32) the one-pass supplied-normaliser variant,
+    with `k_tail` ([n_layers, n_seq, n_q, h_kv, d] bf16) the variant whose softmax covers the soft tokens' own keys."""
     import torch
     if scores is None:
         scores = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=K.device)
@@ -155,6 +158,10 @@ def score(shape: Shape, Q, K, scores=None, ws=None, stream=None, lse=None):
     if lse is not None:
         _check(lib().jq_score_lse(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(lse), _ptr(scores), _ptr(ws), ws.numel(),
                                   _stream(stream)), "jq_score_lse")
+        return scores
+    if k_tail is not None:
+        _check(lib().jq_score_tail(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(k_tail), _ptr(scores), _ptr(ws), ws.numel(),
+                                   _stream(stream)), "jq_score_tail")
         return scores
     _check(lib().jq_score(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(scores), _ptr(ws), ws.numel(), _stream(stream)), "jq_score")
     return scores
@@ -192,7 +199,7 @@ def compact(shape: Shape, K, V, idx, K_out=None, V_out=None, stream=None):
 
 
 def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_out=None, ws=None, stream=None,
-          want_idx=True, want_scores=True, marks=None, lse=None):
+          want_idx=True, want_scores=True, marks=None, lse=None, k_tail=None):
     """Fused score -> pool -> top-B -> gather.  Returns (K_out, V_out, idx_out, pooled scores).
 
     `marks`: optional list of TRACE_MARKS torch.cuda.Event(enable_timing=True) objects that have been
@@ -214,6 +221,10 @@ def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_ou
     if lse is not None:
         _check(lib().jq_evict_lse(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(lse), _ptr(K_out), _ptr(V_out),
                                   _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict_lse")
+        return K_out, V_out, idx_out, scores_out
+    if k_tail is not None:
+        _check(lib().jq_evict_tail(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(k_tail), _ptr(K_out), _ptr(V_out),
+                                   _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict_tail")
         return K_out, V_out, idx_out, scores_out
     if marks is not None:
         arr = (ctypes.c_void_p * len(marks))(*[int(ev.cuda_event) for ev in marks])

@@ -116,6 +116,7 @@ size_t q_bytes(const Plan& p) { return (size_t)p.n_layers * p.n_seq * p.n_q * p.
 size_t score_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.T * 4; }
 size_t idx_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.TB * 4; }
 size_t lse_bytes(const Plan& p) { return (size_t)p.n_layers * p.n_seq * p.n_q * p.h_q * 4; }
+size_t tail_bytes(const Plan& p) { return (size_t)p.n_layers * p.n_seq * p.n_q * p.h_kv * p.d * 2; }
 
 inline int launch_status(hipError_t e) {
     if (e == hipSuccess) return JQ_OK;
@@ -139,30 +140,40 @@ int jq_workspace_bytes(const jq_shape* shape, size_t* bytes) {
     return JQ_OK;
 }
 
-static int score_impl(const jq_shape* shape, const void* Q, const void* K, const float* lse, bool want_lse,
-                      float* scores, void* ws, size_t ws_bytes, void* stream) {
+// `extra` is the variant's additional input: normalisers (lse) or the soft tokens' keys (k_tail), at most one.
+static int score_impl(const jq_shape* shape, const void* Q, const void* K, const float* lse, const void* k_tail,
+                      bool want_extra, float* scores, void* ws, size_t ws_bytes, void* stream) {
     Plan p;
     int rc = make_plan(shape, false, &p);
     if (rc != JQ_OK) return rc;
-    if (!Q || !K || !scores || (want_lse && !lse)) return JQ_ERR_NULL;
+    const void* extra = lse ? (const void*)lse : k_tail;
+    if (!Q || !K || !scores || (want_extra && !extra)) return JQ_ERR_NULL;
     if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
-    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(scores, 4) || (lse && misaligned(lse, 4)))
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(scores, 4) || (lse && misaligned(lse, 4)) ||
+        (k_tail && misaligned(k_tail, 16)))
         return JQ_ERR_UNSUPPORTED;
+    const size_t extra_bytes = lse ? lse_bytes(p) : tail_bytes(p);
     if (overlaps(scores, score_bytes(p), K, kv_bytes(p)) || overlaps(scores, score_bytes(p), Q, q_bytes(p)) ||
-        overlaps(scores, score_bytes(p), ws, p.ws_bytes) || (lse && overlaps(scores, score_bytes(p), lse, lse_bytes(p))) ||
-        (lse && overlaps(ws, p.ws_bytes, lse, lse_bytes(p))))
+        overlaps(scores, score_bytes(p), ws, p.ws_bytes) || overlaps(ws, p.ws_bytes, Q, q_bytes(p)) ||
+        overlaps(ws, p.ws_bytes, K, kv_bytes(p)) ||
+        (extra && (overlaps(scores, score_bytes(p), extra, extra_bytes) || overlaps(ws, p.ws_bytes, extra, extra_bytes))))
         return JQ_ERR_ALIAS;
-    return launch_status(launch_score(p, Q, K, scores, (char*)ws, (hipStream_t)stream, nullptr, 0, lse));
+    return launch_status(launch_score(p, Q, K, scores, (char*)ws, (hipStream_t)stream, nullptr, 0, lse, k_tail));
 }
 
 int jq_score(const jq_shape* shape, const void* Q, const void* K, float* scores, void* ws, size_t ws_bytes,
              void* stream) {
-    return score_impl(shape, Q, K, nullptr, false, scores, ws, ws_bytes, stream);
+    return score_impl(shape, Q, K, nullptr, nullptr, false, scores, ws, ws_bytes, stream);
 }
 
 int jq_score_lse(const jq_shape* shape, const void* Q, const void* K, const float* lse, float* scores, void* ws,
                  size_t ws_bytes, void* stream) {
-    return score_impl(shape, Q, K, lse, true, scores, ws, ws_bytes, stream);
+    return score_impl(shape, Q, K, lse, nullptr, true, scores, ws, ws_bytes, stream);
+}
+
+int jq_score_tail(const jq_shape* shape, const void* Q, const void* K, const void* K_tail, float* scores, void* ws,
+                  size_t ws_bytes, void* stream) {
+    return score_impl(shape, Q, K, nullptr, K_tail, true, scores, ws, ws_bytes, stream);
 }
 
 int jq_pool(const jq_shape* shape, const float* scores, float* pooled, void* stream) {
@@ -211,19 +222,20 @@ int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_
 }
 
 static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,
-                      void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes,
-                      void* stream, void* const* marks) {
+                      const void* k_tail, void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
+                      size_t ws_bytes, void* stream, void* const* marks) {
     Plan p;
     int rc = make_plan(shape, true, &p);
     if (rc != JQ_OK) return rc;
     if (!Q || !K || !V || !K_out || !V_out) return JQ_ERR_NULL;
     if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(K_out, 16) || misaligned(V_out, 16) ||
-        (idx_out && misaligned(idx_out, 4)) || (scores_out && misaligned(scores_out, 4)) || (lse && misaligned(lse, 4)))
+        (idx_out && misaligned(idx_out, 4)) || (scores_out && misaligned(scores_out, 4)) || (lse && misaligned(lse, 4)) ||
+        (k_tail && misaligned(k_tail, 16)))
         return JQ_ERR_UNSUPPORTED;
     const size_t nin = kv_bytes(p), nout = kv_out_bytes(p);
-    const void* ins[4] = {Q, K, V, lse};
-    const size_t in_bytes[4] = {q_bytes(p), nin, nin, lse_bytes(p)};
+    const void* ins[4] = {Q, K, V, lse ? (const void*)lse : k_tail};
+    const size_t in_bytes[4] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p)};
     const void* outs[5] = {K_out, V_out, idx_out, scores_out, ws};
     const size_t out_bytes[5] = {nout, nout, idx_bytes(p), score_bytes(p), p.ws_bytes};
     for (int o = 0; o < 5; ++o) {
@@ -242,7 +254,7 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
     int32_t* idx = idx_out ? idx_out : (int32_t*)(w + p.off_idx);
     p.marks = marks;
     const size_t zero_words = (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride;
-    hipError_t e = launch_score(p, Q, K, raw, w, st, hist, zero_words, lse);  // also clears the selection histograms
+    hipError_t e = launch_score(p, Q, K, raw, w, st, hist, zero_words, lse, k_tail);  // also clears the selection histograms
     if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, st);
     if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st);
     if (e == hipSuccess) e = launch_compact(p, K, V, idx, K_out, V_out, st);
@@ -251,13 +263,19 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
 
 int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
              int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
-    return evict_impl(shape, Q, K, V, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
+    return evict_impl(shape, Q, K, V, nullptr, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
 }
 
 int jq_evict_lse(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse, void* K_out,
                  void* V_out, int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
     if (!lse) return JQ_ERR_NULL;
-    return evict_impl(shape, Q, K, V, lse, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
+    return evict_impl(shape, Q, K, V, lse, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
+}
+
+int jq_evict_tail(const jq_shape* shape, const void* Q, const void* K, const void* V, const void* K_tail, void* K_out,
+                  void* V_out, int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+    if (!K_tail) return JQ_ERR_NULL;
+    return evict_impl(shape, Q, K, V, nullptr, K_tail, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
 }
 
 int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
@@ -267,7 +285,7 @@ int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const v
     if (n_marks != JQ_TRACE_MARKS) return JQ_ERR_SHAPE;
     for (int i = 0; i < n_marks; ++i)
         if (!marks[i]) return JQ_ERR_NULL;
-    return evict_impl(shape, Q, K, V, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, marks);
+    return evict_impl(shape, Q, K, V, nullptr, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, marks);
 }
 
 int jq_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {

@@ -79,8 +79,10 @@ inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, size_t lds
 // Stage launchers (enqueue only).  Each returns a hipError_t from the launch.
 // `zero_words` words at `zero` (nullable) are cleared on the way (between the two K passes).
 // With `lse` (nullable, [n_layers, n_seq, n_q, h_q] natural-log normalisers) the statistics pass is skipped.
+// With `k_tail` (nullable, [n_layers, n_seq, n_q, h_kv, d] bf16) the normalisers also cover those keys, causally.
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
-                        uint32_t* zero = nullptr, size_t zero_words = 0, const float* lse = nullptr);
+                        uint32_t* zero = nullptr, size_t zero_words = 0, const float* lse = nullptr,
+                        const void* k_tail = nullptr);
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st);
 hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st);

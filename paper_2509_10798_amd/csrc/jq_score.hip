@@ -37,6 +37,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct ScoreArgs {
     const uint16_t* Q;
     const uint16_t* K;
+    const uint16_t* K_tail;  // [n_layers][n_seq][n_q][h_kv][d] keys of the soft tokens themselves, or null
     float2* stats;    // [n_layers][n_chunks][h_kv][RP]: (m, Z) per chunk of keys
     uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
     u32x4* qfrag;     // [n_layers][n_seq][h_kv][RP/32][8][64]: query rows in MFMA operand order
@@ -451,6 +452,29 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
             M = mm;
         }
     }
+    if (a.K_tail && row < a.rows) {
+        // The soft tokens' own keys enter the normaliser causally: row (i, hh) sees soft tokens 0..i.
+        // Partial-lane kl takes i' = kl, kl + 32, ...; each term is one more (m, Z) partial.
+        const int i = row / a.group, h = g * a.group + row % a.group;
+        const uint16_t* q = a.Q + (((int64_t)(layer * a.n_seq + s) * a.n_q + i) * a.h_q + h) * kHeadDim;
+        const uint16_t* kt0 = a.K_tail + ((int64_t)(layer * a.n_seq + s) * a.n_q * a.h_kv + g) * kHeadDim;
+        for (int it = kl; it <= i; it += kCombineLanes) {
+            const uint16_t* kt = kt0 + (int64_t)it * a.h_kv * kHeadDim;
+            float dot = 0.f;
+            for (int cc = 0; cc < kHeadDim; cc += 8) {
+                const u32x4 qa = *(const u32x4*)(q + cc), ka = *(const u32x4*)(kt + cc);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {  // bf16 -> fp32 is a shift; products of two bf16 are exact in fp32
+                    dot = fmaf(__uint_as_float(qa[e] << 16), __uint_as_float(ka[e] << 16), dot);
+                    dot = fmaf(__uint_as_float(qa[e] & 0xFFFF0000u), __uint_as_float(ka[e] & 0xFFFF0000u), dot);
+                }
+            }
+            const float t = dot * a.c;
+            const float mm = fmaxf(M, t);
+            Z = Z * __builtin_amdgcn_exp2f(M - mm) + __builtin_amdgcn_exp2f(t - mm);
+            M = mm;
+        }
+    }
     part[kl][r] = make_float2(M, Z);
     __syncthreads();
     if (kl != 0) return;
@@ -645,11 +669,12 @@ static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStre
 }
 
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
-                        uint32_t* zero, size_t zero_words, const float* lse) {
+                        uint32_t* zero, size_t zero_words, const float* lse, const void* k_tail) {
     void* const* marks = p.marks;
     ScoreArgs a;
     a.Q = (const uint16_t*)Q;
     a.K = (const uint16_t*)K;
+    a.K_tail = (const uint16_t*)k_tail;
     a.stats = (float2*)(ws + p.off_stats);
     a.aug = (uint2*)(ws + p.off_aug);
     a.qfrag = (u32x4*)(ws + p.off_qfrag);

@@ -82,6 +82,12 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_evict_lse(ctypes.byref(cs), Q, K, V, None, Ko, Vo, None, None, ws, need, None) == -1
     assert L.jq_evict_lse(ctypes.byref(cs), Q, K, V, lse + 2, Ko, Vo, None, None, ws, need, None) == -4
     assert L.jq_evict_lse(ctypes.byref(cs), Q, K, V, Ko, Ko, Vo, None, None, ws, need, None) == -6   # lse inside K_out
+    kt = big + (7 << 30)
+    assert L.jq_score_tail(ctypes.byref(cs), Q, K, None, Ko, ws, need, None) == -1                 # soft-token keys required
+    assert L.jq_score_tail(ctypes.byref(cs), Q, K, kt + 2, Ko, ws, need, None) == -4
+    assert L.jq_score_tail(ctypes.byref(cs), Q, K, ws + 512, Ko, ws, need, None) == -6             # keys inside the workspace
+    assert L.jq_evict_tail(ctypes.byref(cs), Q, K, V, None, Ko, Vo, None, None, ws, need, None) == -1
+    assert L.jq_evict_tail(ctypes.byref(cs), Q, K, V, Vo, Ko, Vo, None, None, ws, need, None) == -6   # keys inside V_out
     assert L.jq_evict_traced(ctypes.byref(cs), Q, K, V, Ko, Vo, None, None, ws, need, None, None, 14) == -1
     assert L.jq_copy_probe(K, K + 64, 1024, None) == -6 and L.jq_copy_probe(K, Ko, 24, None) == -2
     assert L.jq_compact(ctypes.byref(cs), K, V, ws, V, Vo, None) == -6
