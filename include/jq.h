@@ -140,6 +140,16 @@ int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx,
 int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_t* idx,
                void* K_out, void* V_out, void* stream);
 
+/* Critical-KV hit rate (Eq. 6): for every (layer, sequence, KV head)
+ *   rate[l,s,g] = |I_cur & I_ref| / |I_ref|
+ * where I_cur = idx_cur[l, g, cu_budgets[s] .. cu_budgets[s+1]) holds shape->budgets[s]
+ * positions and I_ref = idx_ref[l, g, ...] holds ref_budgets[s] positions (HOST array of
+ * n_seq entries, each 1..L_s; NULL means the same budgets as `shape`).  Both lists must be
+ * ascending, as jq_select_topk / jq_evict write them; idx_cur is [n_layers, h_kv, sum budgets],
+ * idx_ref [n_layers, h_kv, sum ref_budgets], rate [n_layers, n_seq, h_kv] fp32 (DEVICE). */
+int jq_hit_rate(const jq_shape* shape, const int32_t* idx_cur, const int32_t* idx_ref,
+                const int32_t* ref_budgets, float* rate, void* stream);
+
 /* score -> pool -> select -> compact in one call.  `idx_out` (kept positions) and
  * `scores_out` (POOLED scores) may each be NULL when the caller does not want
  * them; the workspace then holds them. */

@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced", "jq_hit_rate",
            "jq_copy_probe", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_combine_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel",
                  "jq_select_finalize_kernel", "jq_compact_kernel")
@@ -58,6 +58,7 @@ def lib() -> ctypes.CDLL:
         L.jq_score.argtypes = [shp, vp, vp, vp, vp, sz, vp]
         L.jq_score_lse.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_lse.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_hit_rate.argtypes = [shp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, vp]
         L.jq_score_tail.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_pool.argtypes = [shp, vp, vp, vp]
@@ -235,6 +236,23 @@ def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_ou
     _check(lib().jq_evict(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(idx_out),
                           _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict")
     return K_out, V_out, idx_out, scores_out
+
+
+def hit_rate(shape: Shape, idx_cur, idx_ref, ref_budgets=None, rate=None, stream=None):
+    """Eq. 6 per (layer, sequence, head): |I_cur & I_ref| / |I_ref| for ascending position lists; returns
+    rate [n_layers, n_seq, h_kv] fp32.  `ref_budgets`: list lengths of idx_ref per sequence (default: shape's)."""
+    import torch
+    if rate is None:
+        rate = torch.empty((shape.n_layers, shape.n_seq, shape.h_kv), dtype=torch.float32, device=idx_cur.device)
+    cs = shape.c_struct()
+    rb = None
+    if ref_budgets is not None:
+        rb = np.ascontiguousarray(ref_budgets, dtype=np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    _check(lib().jq_hit_rate(ctypes.byref(cs), _ptr(idx_cur), _ptr(idx_ref),
+                             rb.ctypes.data_as(i32p) if rb is not None else ctypes.cast(None, i32p), _ptr(rate),
+                             _stream(stream)), "jq_hit_rate")
+    return rate
 
 
 def copy_probe(src, dst, stream=None):

@@ -288,6 +288,30 @@ int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const v
     return evict_impl(shape, Q, K, V, nullptr, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, marks);
 }
 
+int jq_hit_rate(const jq_shape* shape, const int32_t* idx_cur, const int32_t* idx_ref, const int32_t* ref_budgets,
+                float* rate, void* stream) {
+    Plan p;
+    const int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if (!idx_cur || !idx_ref || !rate) return JQ_ERR_NULL;
+    int32_t cu_ref[JQ_MAX_SEQ + 1];
+    int64_t tb_ref = 0;
+    cu_ref[0] = 0;
+    for (int s = 0; s < p.n_seq; ++s) {
+        const int32_t L = shape->cu_seqlens[s + 1] - shape->cu_seqlens[s];
+        const int32_t b = ref_budgets ? ref_budgets[s] : shape->budgets[s];
+        if (b < 1 || b > L) return JQ_ERR_BUDGET;
+        tb_ref += b;
+        if (tb_ref > INT32_MAX) return JQ_ERR_UNSUPPORTED;
+        cu_ref[s + 1] = (int32_t)tb_ref;
+    }
+    if (misaligned(idx_cur, 4) || misaligned(idx_ref, 4) || misaligned(rate, 4)) return JQ_ERR_UNSUPPORTED;
+    const size_t rate_bytes = (size_t)p.n_layers * p.n_seq * p.h_kv * sizeof(float);
+    const size_t ref_bytes = (size_t)p.n_layers * p.h_kv * (size_t)tb_ref * sizeof(int32_t);
+    if (overlaps(rate, rate_bytes, idx_cur, idx_bytes(p)) || overlaps(rate, rate_bytes, idx_ref, ref_bytes)) return JQ_ERR_ALIAS;
+    return launch_status(launch_hit_rate(p, cu_ref, tb_ref, idx_cur, idx_ref, rate, (hipStream_t)stream));
+}
+
 int jq_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
     if (!src || !dst) return JQ_ERR_NULL;
     if (bytes == 0 || bytes % 16 != 0) return JQ_ERR_SHAPE;

@@ -90,6 +90,9 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
                           hipStream_t st);
 
+// `cu_ref_budgets`: n_seq + 1 prefix sums of the reference list lengths, `tb_ref` their total.
+hipError_t launch_hit_rate(const Plan& p, const int32_t* cu_ref_budgets, int64_t tb_ref, const int32_t* cur,
+                           const int32_t* ref, float* rate, hipStream_t st);
 hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 
 }  // namespace jq

@@ -53,6 +53,56 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
                          dim3(kCompactThreads), 0, st, p.marks, kTrCompact, a);
 }
 
+// Critical-KV hit rate (paper Eq. 6): |I_cur & I_ref| / |I_ref| per (layer, sequence, KV head) for two kept
+// sets given as ascending position lists.  One workgroup per problem; every position of the reference
+// list is looked up in the current list by binary search.  Integer work; the quotient is the only rounding.
+struct HitArgs {
+    const int32_t* cur;  // [n_layers][h_kv][TB_cur]
+    const int32_t* ref;  // [n_layers][h_kv][TB_ref]
+    float* rate;         // [n_layers][n_seq][h_kv]
+    int32_t n_layers, n_seq, h_kv;
+    int64_t TB_cur, TB_ref;
+    int32_t cu_cur[JQ_MAX_SEQ + 1], cu_ref[JQ_MAX_SEQ + 1];
+};
+
+__global__ __launch_bounds__(256) void jq_hit_rate_kernel(HitArgs a) {
+    __shared__ uint32_t wave_hits[4];
+    const int g = blockIdx.x % a.h_kv;
+    const int s = (blockIdx.x / a.h_kv) % a.n_seq;
+    const int layer = blockIdx.x / (a.h_kv * a.n_seq);
+    const int nc = a.cu_cur[s + 1] - a.cu_cur[s], nr = a.cu_ref[s + 1] - a.cu_ref[s];
+    const int32_t* cur = a.cur + ((int64_t)layer * a.h_kv + g) * a.TB_cur + a.cu_cur[s];
+    const int32_t* ref = a.ref + ((int64_t)layer * a.h_kv + g) * a.TB_ref + a.cu_ref[s];
+    uint32_t hits = 0;
+    for (int i = threadIdx.x; i < nr; i += 256) {
+        const int32_t want = ref[i];
+        int lo = 0, hi = nc;  // first position of cur that is >= want
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (cur[mid] < want) lo = mid + 1; else hi = mid;
+        }
+        hits += (lo < nc && cur[lo] == want);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) hits += __shfl_xor(hits, d);
+    if ((threadIdx.x & 63) == 0) wave_hits[threadIdx.x >> 6] = hits;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t total = wave_hits[0] + wave_hits[1] + wave_hits[2] + wave_hits[3];
+        a.rate[((int64_t)layer * a.n_seq + s) * a.h_kv + g] = (float)total / (float)nr;
+    }
+}
+
+hipError_t launch_hit_rate(const Plan& p, const int32_t* cu_ref_budgets, int64_t tb_ref, const int32_t* cur,
+                           const int32_t* ref, float* rate, hipStream_t st) {
+    HitArgs a;
+    a.cur = cur; a.ref = ref; a.rate = rate;
+    a.n_layers = p.n_layers; a.n_seq = p.n_seq; a.h_kv = p.h_kv;
+    a.TB_cur = p.TB; a.TB_ref = tb_ref;
+    for (int s = 0; s <= p.n_seq; ++s) { a.cu_cur[s] = p.tab.cu_bud[s]; a.cu_ref[s] = cu_ref_budgets[s]; }
+    return launch_kernel(jq_hit_rate_kernel, dim3((unsigned)(p.n_layers * p.n_seq * p.h_kv)), dim3(256), 0, st, nullptr, -1, a);
+}
+
 // Plain streaming copy, 16 bytes per lane: the known-size reference against which hardware traffic
 // counters are calibrated.
 __global__ __launch_bounds__(256) void jq_copy_probe_kernel(const u32x4* src, u32x4* dst, size_t n16) {

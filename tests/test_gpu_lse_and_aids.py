@@ -119,3 +119,50 @@ def test_copy_probe_copies():
     jq.copy_probe(src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+def test_hit_rate_matches_oracle_on_random_sets_and_on_two_scorers():
+    # Eq. 6 between two kept sets, per (layer, sequence, head)
+    torch = torch_()
+    rng = np.random.default_rng(71)
+    nl, h_kv, seq_lens, budgets, ref_budgets = 2, 3, [500, 64, 3000], [100, 64, 700], [80, 10, 1500]
+    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, budgets=budgets)
+
+    def random_sets(buds):
+        out = np.empty((nl, h_kv, sum(buds)), dtype=np.int32)
+        cb = np.concatenate([[0], np.cumsum(buds)])
+        for l in range(nl):
+            for g in range(h_kv):
+                for s, L in enumerate(seq_lens):
+                    out[l, g, cb[s]:cb[s + 1]] = np.sort(rng.choice(L, buds[s], replace=False))
+        return out, cb
+
+    cur, cb = random_sets(budgets)
+    for rb in (None, ref_budgets):
+        ref, cr = random_sets(budgets if rb is None else rb)
+        got = jq.hit_rate(sh, torch.from_numpy(cur).cuda(), torch.from_numpy(ref).cuda(), ref_budgets=rb)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy()
+        for l in range(nl):
+            for s in range(len(seq_lens)):
+                for g in range(h_kv):
+                    want = oracle.hit_rate(cur[l, g, cb[s]:cb[s + 1]], ref[l, g, cr[s]:cr[s + 1]])
+                    assert abs(float(got[l, s, g]) - want) <= 1e-7, (l, s, g)
+    same = jq.hit_rate(sh, torch.from_numpy(cur).cuda(), torch.from_numpy(cur.copy()).cuda())
+    torch.cuda.synchronize()
+    assert (same.cpu().numpy() == 1.0).all()
+
+    # the kept sets of the prompt-only softmax and of the softmax that also covers strong soft-token keys
+    w = make_workload(1, seq_lens=[1500], budget=[200])
+    Q, K, V = w.assemble()
+    Kt = f32_to_bf16_bits(rng.standard_normal((1, 1, w.n_q, w.h_kv, w.d)).astype(np.float32) * 2.0)
+    sh2 = jq.Shape(n_layers=1, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    Qd, Kd, Vd = to_dev_bf16(Q), to_dev_bf16(K), to_dev_bf16(V)
+    _, _, idx_a, _ = jq.evict(sh2, Qd, Kd, Vd)
+    _, _, idx_b, _ = jq.evict(sh2, Qd, Kd, Vd, k_tail=to_dev_bf16(Kt))
+    rate = jq.hit_rate(sh2, idx_b, idx_a)
+    torch.cuda.synchronize()
+    ia, ib, rate = idx_a.cpu().numpy(), idx_b.cpu().numpy(), rate.cpu().numpy()
+    for g in range(w.h_kv):
+        assert abs(float(rate[0, 0, g]) - oracle.hit_rate(ib[0, g], ia[0, g])) <= 1e-7
+    assert rate.min() > 0.5            # the planted heavy hitters stay in both sets
