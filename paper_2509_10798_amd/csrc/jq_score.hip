@@ -263,7 +263,9 @@ __device__ __forceinline__ KeyStream key_stream(const ScoreArgs& a, const WaveIt
 // ------------------------------------------------------------------------------------------------
 // One 32-key tile against the wave's query rows: rows of the MFMA result are keys, columns are
 // query rows, so each lane updates the running (m, Z) of its own query column from its 16 keys.
-// MASKED is only used for the last, partial tile of a sequence (keys >= valid do not exist).
+// MASKED: key (row of the tile) number >= valid[qt] does not exist for query tile qt's column of this lane --
+// used for the last, partial tile of a sequence (one uniform bound) and for the tiles of the soft tokens'
+// own keys, where the bound is causal and differs per lane.
 __device__ __forceinline__ f32x16 stats_chain(const bf16x8 (&kf)[8], const bf16x8 (&q)[8]) {
     f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -276,7 +278,7 @@ __device__ __forceinline__ f32x16 stats_chain(const bf16x8 (&kf)[8], const bf16x
 // the 2^0 the offset's own key contributed.
 template <int NQT, bool MASKED, bool FIXED>
 __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (&qf)[NQT][8], float (&m)[NQT],
-                                           float (&z)[NQT], float c, int valid, int half) {
+                                           float (&z)[NQT], float c, const int (&valid)[NQT], int half) {
     // software pipeline: the MFMA chain of query tile qt+1 is interleaved with the max/exp2/add work of tile qt
     f32x16 acc = stats_chain(kf, qf[0]);
 #pragma unroll
@@ -286,7 +288,7 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
         if (MASKED) {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                if (8 * (v >> 2) + 4 * half + (v & 3) >= valid) acc[v] = -INFINITY;
+                if (8 * (v >> 2) + 4 * half + (v & 3) >= valid[qt]) acc[v] = -INFINITY;
         }
         float mnew = m[qt];
         if (!FIXED) {
@@ -335,11 +337,27 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 
     const KeyStream ks = key_stream(a, w);
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
+    // With the soft tokens' own keys in the softmax, the sequence's first wave takes them as further tiles
+    // after its prompt tiles (same row stride, n_q rows), masked causally per query row.
+    const int n_tail = (a.K_tail && w.wave == 0) ? (a.n_q + kKeyTile - 1) / kKeyTile : 0;
+    const int n_all = w.n_tiles + n_tail;
+    __amdgpu_buffer_rsrc_t tail_rsrc = ks.rsrc;
+    if (n_tail) {
+        const char* kt = (const char*)a.K_tail + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q * a.h_kv + w.g) * kHeadDim * 2;
+        tail_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kt, 0, (int)((uint32_t)(a.n_q - 1) * ks.row_bytes + kHeadDim * 2),
+                                                      0x00020000);
+    }
     // the wave's k-th tile is tile w.wave + k * w.n_waves of the sequence and uses slot k & 1
     auto fetch = [&](int k) {
-        const int t = w.wave + k * w.n_waves;
-        fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, (uint32_t)t * kKeyTile * ks.row_bytes, ks.row_bytes,
-                   w.L - t * kKeyTile, tl, lane);
+        if (k < w.n_tiles) {
+            const int t = w.wave + k * w.n_waves;
+            fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, (uint32_t)t * kKeyTile * ks.row_bytes, ks.row_bytes,
+                       w.L - t * kKeyTile, tl, lane);
+        } else {
+            const int t = k - w.n_tiles;
+            fetch_tile(tail_rsrc, slots + (k & 1) * kSlotBytes, (uint32_t)t * kKeyTile * ks.row_bytes, ks.row_bytes,
+                       a.n_q - t * kKeyTile, tl, lane);
+        }
     };
     // The first key tile goes to slot 0 at once; slot 1 first serves as the staging area that turns the
     // query rows into operand order, then takes the second tile.  From then on two tiles are always in
@@ -349,7 +367,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     load_q_via_lds<NQT>(a, w, lane, slots + kSlotBytes, qf);
     if (w.wave == 0) store_q_frags<NQT>(a, w, lane, qf);  // the sequence's first wave leaves the operand-order copy
     wait_frags_read();
-    if (w.n_tiles > 1) fetch(1);
+    if (n_all > 1) fetch(1);
     const float c = a.c;
 
     float m[NQT], z[NQT];
@@ -360,27 +378,49 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     // by the first wait of the sweep.  Only the sequence's last tile can be partial, and it is some wave's last.
     const int last_valid = w.L - (w.wave + (w.n_tiles - 1) * w.n_waves) * kKeyTile;
     const int n_full = last_valid >= kKeyTile ? w.n_tiles : w.n_tiles - 1;
+    // soft token of this lane's query row in each query tile (row r = i * group + hh): it sees soft tokens 0..i
+    int soft_i[NQT];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) soft_i[qt] = ((a.row_tile0 + qt) * kRowTile + (lane & 31)) / a.group;
     // One sweep over the wave's tiles (the first two are already requested).  FAST: the first tile sets each
     // lane's offset m to the maximum of its logits there, later tiles keep it -- no maximum to track.
     auto full_tile = [&](int k, auto fixed) {
-        wait_tile_landed(k + 1 < w.n_tiles);
+        wait_tile_landed(k + 1 < n_all);
         bf16x8 kf[8];
         lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
-        if (k + 2 < w.n_tiles) {
+        if (k + 2 < n_all) {
             wait_frags_read();
             fetch(k + 2);
         }
-        stats_tile<NQT, false, decltype(fixed)::value>(kf, qf, m, z, c, kKeyTile, half);
+        int valid[NQT];
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) valid[qt] = kKeyTile;
+        stats_tile<NQT, false, decltype(fixed)::value>(kf, qf, m, z, c, valid, half);
+    };
+    auto masked_tile = [&](int k, const int (&valid)[NQT], bool fixed) {
+        wait_tile_landed(k + 1 < n_all);
+        bf16x8 kf[8];
+        lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
+        if (k + 2 < n_all) {
+            wait_frags_read();
+            fetch(k + 2);
+        }
+        if (fixed) stats_tile<NQT, true, true>(kf, qf, m, z, c, valid, half);
+        else stats_tile<NQT, true, false>(kf, qf, m, z, c, valid, half);
     };
     auto sweep = [&](auto fast) {
         if (n_full > 0) full_tile(0, std::false_type{});
         for (int k = 1; k < n_full; ++k) full_tile(k, fast);
-        if (n_full < w.n_tiles) {  // partial last tile
-            wait_tile_landed(false);
-            bf16x8 kf[8];
-            lds_get_frags(slots + (n_full & 1) * kSlotBytes, kf, lane);
-            if (decltype(fast)::value && n_full > 0) stats_tile<NQT, true, true>(kf, qf, m, z, c, last_valid, half);
-            else stats_tile<NQT, true, false>(kf, qf, m, z, c, last_valid, half);
+        int valid[NQT];
+        if (n_full < w.n_tiles) {  // partial last tile of the prompt
+#pragma unroll
+            for (int qt = 0; qt < NQT; ++qt) valid[qt] = last_valid;
+            masked_tile(n_full, valid, decltype(fast)::value && n_full > 0);
+        }
+        for (int t = 0; t < n_tail; ++t) {  // soft token t * 32 + j is visible to the row of soft token i iff it is <= i
+#pragma unroll
+            for (int qt = 0; qt < NQT; ++qt) valid[qt] = soft_i[qt] + 1 - t * kKeyTile;
+            masked_tile(w.n_tiles + t, valid, decltype(fast)::value);
         }
     };
     sweep(std::true_type{});
@@ -395,7 +435,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
         wait_frags_read();
         fetch(0);
-        if (w.n_tiles > 1) fetch(1);
+        if (n_all > 1) fetch(1);
         sweep(std::false_type{});
     }
 
@@ -449,29 +489,6 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
         for (int u = 0; u < 8; ++u) {
             const float mm = fmaxf(M, mz[u].x);
             Z = Z * __builtin_amdgcn_exp2f(M - mm) + mz[u].y * __builtin_amdgcn_exp2f(mz[u].x - mm);
-            M = mm;
-        }
-    }
-    if (a.K_tail && row < a.rows) {
-        // The soft tokens' own keys enter the normaliser causally: row (i, hh) sees soft tokens 0..i.
-        // Partial-lane kl takes i' = kl, kl + 32, ...; each term is one more (m, Z) partial.
-        const int i = row / a.group, h = g * a.group + row % a.group;
-        const uint16_t* q = a.Q + (((int64_t)(layer * a.n_seq + s) * a.n_q + i) * a.h_q + h) * kHeadDim;
-        const uint16_t* kt0 = a.K_tail + ((int64_t)(layer * a.n_seq + s) * a.n_q * a.h_kv + g) * kHeadDim;
-        for (int it = kl; it <= i; it += kCombineLanes) {
-            const uint16_t* kt = kt0 + (int64_t)it * a.h_kv * kHeadDim;
-            float dot = 0.f;
-            for (int cc = 0; cc < kHeadDim; cc += 8) {
-                const u32x4 qa = *(const u32x4*)(q + cc), ka = *(const u32x4*)(kt + cc);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {  // bf16 -> fp32 is a shift; products of two bf16 are exact in fp32
-                    dot = fmaf(__uint_as_float(qa[e] << 16), __uint_as_float(ka[e] << 16), dot);
-                    dot = fmaf(__uint_as_float(qa[e] & 0xFFFF0000u), __uint_as_float(ka[e] & 0xFFFF0000u), dot);
-                }
-            }
-            const float t = dot * a.c;
-            const float mm = fmaxf(M, t);
-            Z = Z * __builtin_amdgcn_exp2f(M - mm) + __builtin_amdgcn_exp2f(t - mm);
             M = mm;
         }
     }

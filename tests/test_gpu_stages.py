@@ -48,6 +48,7 @@ def run_score_case(n_layers, seq_lens, n_q, h_q, h_kv, seed, scale=0.0, spread=1
     (2, [517, 64, 3001], 10, 8, 2),   # layers x ragged batch, 40 query rows (padded row tile)
     (1, [700], 40, 8, 2),             # 160 query rows: two passes over K
     (1, [300], 3, 6, 6),              # no grouping (G = 1), 3 query rows
+    (1, [400, 77], 11, 6, 2),         # three query heads per KV head (not a power of two), 33 query rows
 ])
 def test_score_matches_oracle(n_layers, seq_lens, n_q, h_q, h_kv):
     print("score case", n_layers, seq_lens, n_q, h_q, h_kv, flush=True)
@@ -196,6 +197,50 @@ def test_compact_is_bit_exact():
             rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], idx[l, :, cb[s]:cb[s + 1]])
             np.testing.assert_array_equal(Ko[l, cb[s]:cb[s + 1]], rk)
             np.testing.assert_array_equal(Vo[l, cb[s]:cb[s + 1]], rv)
+
+
+def test_sink_and_recent_window_retention_through_compact():
+    # position-based retention (attention sinks + recent window, the StreamingLLM baseline of Section 5.1)
+    # needs no scores: the caller writes the positions and jq_compact prunes the cache
+    torch = torch_()
+    rng = np.random.default_rng(42)
+    nl, seq_lens, h_kv, d, sink, recent = 2, [500, 90], 4, 128, 4, 28
+    budgets = [sink + recent] * 2
+    T = sum(seq_lens)
+    K = rng.integers(0, 65536, (nl, T, h_kv, d)).astype(np.uint16)
+    V = rng.integers(0, 65536, (nl, T, h_kv, d)).astype(np.uint16)
+    idx = np.empty((nl, h_kv, sum(budgets)), dtype=np.int32)
+    for s, L in enumerate(seq_lens):
+        idx[:, :, s * 32:(s + 1) * 32] = np.concatenate([np.arange(sink), np.arange(L - recent, L)])
+    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, budgets=budgets)
+    Ko, Vo = jq.compact(sh, to_dev_bf16(K), to_dev_bf16(V), torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    Ko, Vo = from_dev_bf16(Ko), from_dev_bf16(Vo)
+    cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    for s, L in enumerate(seq_lens):
+        seg = K[:, cu[s]:cu[s + 1]]
+        np.testing.assert_array_equal(Ko[:, s * 32:s * 32 + sink], seg[:, :sink])
+        np.testing.assert_array_equal(Ko[:, s * 32 + sink:(s + 1) * 32], seg[:, L - recent:])
+        np.testing.assert_array_equal(Vo[:, s * 32 + sink:(s + 1) * 32], V[:, cu[s]:cu[s + 1]][:, L - recent:])
+
+
+def test_layer_dependent_budgets_by_one_call_per_layer():
+    # budgets that shrink with depth (the pyramid-shaped allocation among the Section 5.1 baselines):
+    # budgets are uniform over the layers of one call, so such a schedule is one call per layer
+    torch = torch_()
+    w = make_workload(1, seq_lens=[1200], budget=[300], n_layers=3)
+    Q, K, V = w.assemble()
+    for layer, B in enumerate([300, 180, 60]):
+        sh = jq.Shape(n_layers=1, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=[B])
+        Ko, Vo, idx, pooled = jq.evict(sh, to_dev_bf16(Q[layer:layer + 1]), to_dev_bf16(K[layer:layer + 1]),
+                                       to_dev_bf16(V[layer:layer + 1]))
+        torch.cuda.synchronize()
+        r = oracle.evict(Q[layer, 0], K[layer], V[layer], B, w.pool_k)
+        for g in range(w.h_kv):
+            assert_kept_set_ok(r["pooled"][g], r["idx"][g], idx[0, g].cpu().numpy(), "layer %d head %d" % (layer, g))
+        rk, rv = oracle.compact(K[layer], V[layer], np.ascontiguousarray(idx[0].cpu().numpy()))
+        np.testing.assert_array_equal(from_dev_bf16(Ko)[0], rk)
+        np.testing.assert_array_equal(from_dev_bf16(Vo)[0], rv)
 
 
 def test_evict_equals_stage_composition_and_oracle():
