@@ -256,8 +256,9 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
     const size_t zero_words = (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride;
     hipError_t e = launch_score(p, Q, K, raw, w, st, hist, zero_words, lse, k_tail);  // also clears the selection histograms
     if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, st);
-    if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st);
-    if (e == hipSuccess) e = launch_compact(p, K, V, idx, K_out, V_out, st);
+    bool gathered = false;  // the selection's last kernel gathers the kept rows itself unless it had to stream
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st, K, V, K_out, V_out, &gathered);
+    if (e == hipSuccess && !gathered) e = launch_compact(p, K, V, idx, K_out, V_out, st);
     return launch_status(e);
 }
 

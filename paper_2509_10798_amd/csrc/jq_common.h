@@ -60,7 +60,7 @@ __device__ inline uint32_t sortable_key(float x) {
 }
 
 // Kernels whose start/stop timestamps jq_evict_traced reports, in launch order.
-enum TraceKernel { kTrStats = 0, kTrCombine, kTrScore, kTrPool, kTrScatter, kTrFinalize, kTrCompact, kTraceKernels };
+enum TraceKernel { kTrStats = 0, kTrCombine, kTrScore, kTrPool, kTrScatter, kTrFinalize, kTraceKernels };
 
 // Launch through hipLaunchKernel so that the status belongs to this launch alone (the sticky
 // "last error" of the runtime may hold an unrelated, earlier code from the host application).
@@ -86,7 +86,11 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st);
 hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st);
-hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st);
+// With K, V, K_out, V_out (all or none) the selection also gathers the kept rows when its fast path runs;
+// `*gathered` tells whether it did (otherwise launch_compact is still due).
+hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
+                         const void* K = nullptr, const void* V = nullptr, void* K_out = nullptr, void* V_out = nullptr,
+                         bool* gathered = nullptr);
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
                           hipStream_t st);
 

@@ -50,7 +50,7 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
     return launch_kernel(jq_compact_kernel, dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads)),
-                         dim3(kCompactThreads), 0, st, p.marks, kTrCompact, a);
+                         dim3(kCompactThreads), 0, st, nullptr, -1, a);
 }
 
 // Critical-KV hit rate (paper Eq. 6): |I_cur & I_ref| / |I_ref| per (layer, sequence, KV head) for two kept

@@ -11,9 +11,12 @@
 //   scatter  -- the whole GPU streams the scores once; positions above bin b1 go to a "sure"
 //               list, (key, position) pairs inside b1 to a candidate list (block-aggregated
 //               appends; the order between blocks is arbitrary);
-//   finalize -- one workgroup per problem resolves levels 2 and 3 on the candidates in LDS,
-//               marks sure / chosen positions in an L-bit LDS bitmap, trims the tie group to
-//               its lowest positions and emits the set bits in ascending order.
+//   finalize -- a workgroup resolves levels 2 and 3 on a problem's candidates in LDS, marks sure /
+//               chosen positions in an L-bit LDS bitmap, trims the tie group to its lowest
+//               positions and emits set bits in ascending order.  Several workgroups ("slices")
+//               work on one problem: each repeats the (cheap, L2-resident) resolution and emits
+//               its own range of output slots; in the fused eviction call it also gathers the K/V
+//               rows of those slots, so the pruned cache needs no further kernel.
 // General path (very long sequences): one workgroup per problem streams the row three times.
 #include "jq_common.h"
 
@@ -27,6 +30,10 @@ struct SelectArgs {
     int32_t* idx;         // [n_layers][h_kv][TB]
     int32_t n_layers, h_kv;
     int64_t T, TB;
+    // fused gather (all four null when the kept rows are not wanted): K,V [n_layers][T][h_kv][d] bf16,
+    // K_out,V_out [n_layers][TB][h_kv][d]
+    const char* K; const char* V;
+    char* K_out; char* V_out;
     SeqTab tab;
 };
 
@@ -266,7 +273,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
     uint32_t* keep = res + 32;                    // words_cap: bitmap of kept positions
     uint32_t* ties = keep + words_cap;            // words_cap: bitmap of positions with key == tau
 
-    const Problem p = problem_of(a, blockIdx.x);
+    const Problem p = problem_of(a, blockIdx.x);  // blockIdx.y: which slice of the problem's output slots
     const int words = (p.L + 31) >> 5;
     const uint32_t n_sure = min(p.hist[kHistBins], p.B);
     const uint32_t n_cand = min(p.hist[kHistBins + 1], (uint32_t)p.L);
@@ -368,30 +375,54 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
     // spans), so per-word loops leave most lanes idle.  Slot o lives in the last word w with wpre[w] <= o
     // (binary search in LDS, same trip count for every thread); inside the word, the (o - wpre[w])-th set bit
     // is found by five popcount halvings.  Consecutive threads write consecutive slots.
-    for (uint32_t o = threadIdx.x; o < p.B; o += kFinThreads) {
-        int lo = 0, hi = words;  // invariant: wpre[lo] <= o, and hi == words or wpre[hi] > o
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (wpre[mid] <= o) lo = mid; else hi = mid;
-        }
-        uint32_t r = o - wpre[lo];
-        const uint32_t k = keep[lo];
-        uint32_t pos = 0;
+    const uint32_t per_slice = (p.B + gridDim.y - 1) / gridDim.y;
+    const uint32_t o_begin = min(p.B, blockIdx.y * per_slice), o_end = min(p.B, o_begin + per_slice);
+    uint32_t* slot_pos = bins2;  // the histograms are dead: positions of the current batch of kFinThreads slots
+    for (uint32_t o0 = o_begin; o0 < o_end; o0 += kFinThreads) {  // uniform trip count
+        const uint32_t o = o0 + threadIdx.x;
+        if (o < o_end) {
+            int lo = 0, hi = words;  // invariant: wpre[lo] <= o, and hi == words or wpre[hi] > o
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (wpre[mid] <= o) lo = mid; else hi = mid;
+            }
+            uint32_t r = o - wpre[lo];
+            const uint32_t k = keep[lo];
+            uint32_t pos = 0;
 #pragma unroll
-        for (int sft = 16; sft >= 1; sft >>= 1) {
-            const uint32_t c = __popc((k >> pos) & ((1u << sft) - 1u));
-            if (r >= c) { r -= c; pos += sft; }
+            for (int sft = 16; sft >= 1; sft >>= 1) {
+                const uint32_t c = __popc((k >> pos) & ((1u << sft) - 1u));
+                if (r >= c) { r -= c; pos += sft; }
+            }
+            p.out[o] = (lo << 5) + (int)pos;
+            slot_pos[threadIdx.x] = (uint32_t)(lo << 5) + pos;
         }
-        p.out[o] = (lo << 5) + (int)pos;
+        if (a.K_out == nullptr) continue;  // uniform
+        // Pruned cache (paper Section 4.3): the kept rows of this batch, 16 lanes x 16 B per 256-byte head row.
+        __syncthreads();
+        const uint32_t n_rows = min((uint32_t)kFinThreads, o_end - o0);
+        const int part = threadIdx.x & 15;
+        for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
+            const int64_t src = ((((int64_t)p.layer * a.T + a.tab.cu_seq[p.s] + slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+            const int64_t dst = ((((int64_t)p.layer * a.TB + a.tab.cu_bud[p.s] + o0 + rr) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+            const uint4 kv = *(const uint4*)(a.K + src);
+            const uint4 vv = *(const uint4*)(a.V + src);
+            *(uint4*)(a.K_out + dst) = kv;
+            *(uint4*)(a.V_out + dst) = vv;
+        }
+        __syncthreads();  // slot_pos is rewritten by the next batch
     }
 }
 
 constexpr int kFinalizeFixedWords = 2048 + 1024 + 32 + 32;
 constexpr size_t kMaxLds = 160 * 1024;
 
-hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st) {
+hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
+                         const void* K, const void* V, void* K_out, void* V_out, bool* gathered) {
     SelectArgs a;
     a.pooled = pooled; a.hist = hist; a.idx = idx;
+    a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
+    if (gathered) *gathered = false;
     a.sure = (int32_t*)(ws + p.off_sure);
     a.cand = (uint2*)(ws + p.off_cand);
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
@@ -413,8 +444,20 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
                                 (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
-    return launch_kernel(jq_select_finalize_kernel, dim3(n_prob), dim3(kFinThreads), lds_bytes, st, p.marks, kTrFinalize, a,
-                         words_cap);
+    // Slices per problem: enough workgroups to spread the emission (and the gather) over the chip, each with
+    // at least 64 output slots.
+    int64_t min_budget = INT32_MAX;
+    for (int s = 0; s < p.n_seq; ++s) {
+        const int64_t b = p.tab.cu_bud[s + 1] - p.tab.cu_bud[s];
+        if (b < min_budget) min_budget = b;
+    }
+    int64_t slices = (256 + n_prob - 1) / n_prob;
+    if (slices > (min_budget + 63) / 64) slices = (min_budget + 63) / 64;
+    if (slices > 64) slices = 64;
+    if (slices < 1) slices = 1;
+    if (gathered) *gathered = K_out != nullptr;
+    return launch_kernel(jq_select_finalize_kernel, dim3(n_prob, (unsigned)slices), dim3(kFinThreads), lds_bytes, st, p.marks,
+                         kTrFinalize, a, words_cap);
 }
 
 }  // namespace jq
