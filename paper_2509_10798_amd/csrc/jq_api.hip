@@ -1,4 +1,4 @@
-// C ABI of libjq: argument validation, planning (chunking, workspace layout) and the launch
+// C ABI of libjq: argument validation, planning (wave counts, workspace layout) and the launch
 // sequences.  Everything here runs on the host; no HIP call is made before validation succeeds.
 #include <cmath>
 #include <cstdio>
@@ -29,7 +29,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     if (!std::isfinite(sh->scale) || sh->scale < 0.0f) return JQ_ERR_SHAPE;
     if (sh->n_seq > JQ_MAX_SEQ) return JQ_ERR_UNSUPPORTED;
     if (sh->d != kHeadDim) return JQ_ERR_UNSUPPORTED;
-    if (sh->n_layers > 65535 || sh->h_kv > 256) return JQ_ERR_UNSUPPORTED;  // grid dimensions; 32-bit byte offsets inside a chunk
+    if (sh->n_layers > 65535 || sh->h_kv > 256) return JQ_ERR_UNSUPPORTED;  // grid dimensions
     if (sh->cu_seqlens[0] != 0) return JQ_ERR_SHAPE;
     for (int s = 0; s < sh->n_seq; ++s)
         if (sh->cu_seqlens[s + 1] <= sh->cu_seqlens[s]) return JQ_ERR_SHAPE;

@@ -14,7 +14,8 @@ namespace jq {
 
 constexpr int kPoolThreads = 256;
 constexpr int kPoolPerThread = 8;
-constexpr int kPoolBlockPos = kPoolThreads * kPoolPerThread;  // 2048 positions per block
+constexpr int kPoolBlockPos = kPoolThreads * kPoolPerThread;  // 2048 positions per block (8192 were slower: fewer
+                                                              // resident blocks hide less latency)
 constexpr int kPoolMaxHalo = 32;                               // (pool_k - 1) / 2 up to here uses the LDS path
 constexpr int kWinBins = 128;                                  // histogram window below the block's top bin
 constexpr int kWinCopies = 16;
@@ -39,9 +40,12 @@ struct PoolArgs {
 template <bool POOL, int K>  // K: pool_k known at compile time (taps unrolled), or 0 for any
 __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
     __shared__ uint32_t win[kWinCopies * kWinStride];
-    __shared__ uint32_t low[kHistBins];
     __shared__ uint32_t wave_top[kPoolThreads / 64];
-    __shared__ float tile[POOL ? kPoolBlockPos + 2 * kPoolMaxHalo : 1];
+    // staged inputs; once the block's values are in registers the same memory serves as the full-width
+    // histogram `low` of the far tail
+    __shared__ __attribute__((aligned(16))) float tile[(POOL ? kPoolBlockPos + 2 * kPoolMaxHalo + 8 : 4) > kHistBins
+                                                           ? (POOL ? kPoolBlockPos + 2 * kPoolMaxHalo + 8 : 4) : kHistBins];
+    uint32_t* low = (uint32_t*)tile;
     const int g = blockIdx.y, layer = blockIdx.z;
     const int64_t row = ((int64_t)layer * a.h_kv + g) * a.T;
     const float* in_row = a.in + row;
@@ -68,37 +72,69 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
             }
         }
         __syncthreads();
+        // Thread t owns two runs of four consecutive positions, 4t.. and 1024 + 4t..: with the taps unrolled a
+        // run reads its 4 + 2r inputs as a few 16-byte LDS loads (lanes 16 B apart: no bank conflict) instead
+        // of 2r + 1 loads per output, and stores one 16-byte vector when the row allows it.
         uint32_t bin[kPoolPerThread];
         uint32_t top = 0;
+        const bool vec_store = ((row + p0) & 3) == 0;  // uniform
 #pragma unroll
-        for (int e = 0; e < kPoolPerThread; ++e) {
-            const int j = e * kPoolThreads + threadIdx.x;
-            const int64_t p = p0 + j;
-            const bool in = p < p1;
-            float v = 0.f;
-            if (in) {
+        for (int h = 0; h < kPoolPerThread / 4; ++h) {
+            const int j0 = h * (kPoolThreads * 4) + threadIdx.x * 4;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (p0 + j0 < p1) {
                 if (!POOL) {
-                    v = in_row[p];
-                } else if (staged) {
-                    float acc = 0.f;
-                    if (K) {
 #pragma unroll
-                        for (int u = 0; u < K; ++u) acc += tile[j + u];
-                    } else {
-                        for (int u = 0; u <= 2 * r; ++u) acc += tile[j + u];  // ascending position order
+                    for (int u = 0; u < 4; ++u)
+                        if (p0 + j0 + u < p1) v[u] = in_row[p0 + j0 + u];
+                } else if (staged && K > 0 && K <= 13) {
+                    constexpr int kNeed = 4 + (K > 0 ? K - 1 : 0);  // inputs of the run
+                    float x[16];
+#pragma unroll
+                    for (int q = 0; q < (kNeed + 3) / 4; ++q) {
+                        const float4 f = *(const float4*)&tile[j0 + 4 * q];
+                        x[4 * q] = f.x; x[4 * q + 1] = f.y; x[4 * q + 2] = f.z; x[4 * q + 3] = f.w;
                     }
-                    v = acc * a.inv_k;
-                    a.out[row + p] = v;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        float acc = 0.f;
+#pragma unroll
+                        for (int k = 0; k < (K > 0 ? K : 1); ++k) acc += x[u + k];  // ascending position order
+                        v[u] = acc * a.inv_k;
+                    }
+                } else if (staged) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        float acc = 0.f;
+                        for (int k = 0; k <= 2 * r; ++k) acc += tile[j0 + u + k];
+                        v[u] = acc * a.inv_k;
+                    }
                 } else {
-                    const int64_t q0 = max(lo, p - r), q1 = min(hi - 1, p + r);
-                    float acc = 0.f;
-                    for (int64_t q = q0; q <= q1; ++q) acc += in_row[q];
-                    v = acc * a.inv_k;
-                    a.out[row + p] = v;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int64_t p = p0 + j0 + u;
+                        const int64_t q0 = max(lo, p - r), q1 = min(hi - 1, p + r);
+                        float acc = 0.f;
+                        for (int64_t q = q0; q <= q1 && p < p1; ++q) acc += in_row[q];
+                        v[u] = acc * a.inv_k;
+                    }
+                }
+                if (POOL) {
+                    if (vec_store && p0 + j0 + 3 < p1) {
+                        *(float4*)&a.out[row + p0 + j0] = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            if (p0 + j0 + u < p1) a.out[row + p0 + j0 + u] = v[u];
+                    }
                 }
             }
-            bin[e] = in ? (sortable_key(v) >> 21) : 0xFFFFFFFFu;  // 0xFFFFFFFF: no element
-            if (in) top = max(top, bin[e]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool in = p0 + j0 + u < p1;
+                bin[4 * h + u] = in ? (sortable_key(v[u]) >> 21) : 0xFFFFFFFFu;  // 0xFFFFFFFF: no element
+                if (in) top = max(top, bin[4 * h + u]);
+            }
         }
         if (!do_hist) {  // uniform
             __syncthreads();

@@ -38,7 +38,7 @@ struct ScoreArgs {
     const uint16_t* Q;
     const uint16_t* K;
     const uint16_t* K_tail;  // [n_layers][n_seq][n_q][h_kv][d] keys of the soft tokens themselves, or null
-    float2* stats;    // [n_layers][n_chunks][h_kv][RP]: (m, Z) per chunk of keys
+    float2* stats;    // [n_layers][n_chunks][h_kv][RP]: (m, Z) per score wave (n_chunks = waves per layer and head)
     uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
     u32x4* qfrag;     // [n_layers][n_seq][h_kv][RP/32][8][64]: query rows in MFMA operand order
     float* scores;    // [n_layers][h_kv][T]
@@ -179,7 +179,7 @@ __device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t rsrc, char* dst
                                              (int)soff, 0, 0);
 }
 
-// `tile_off` = byte offset of the tile's first key row inside the wave's chunk (uniform).
+// `tile_off` = byte offset of the tile's first key row inside the buffer resource (uniform).
 __device__ __forceinline__ void fetch_tile(__amdgpu_buffer_rsrc_t rsrc, char* slot, uint32_t tile_off,
                                            uint32_t row_bytes, int valid, const TileLanes& tl, int lane) {
     if (valid >= kKeyTile) {
@@ -439,7 +439,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         sweep(std::false_type{});
     }
 
-    // lanes l and l+32 hold the same query rows over complementary keys: merge, then one partial per chunk
+    // lanes l and l+32 hold the same query rows over complementary keys: merge, then one partial per wave
     float2* out = a.stats + (((int64_t)w.layer * a.n_chunks + w.chunk_global) * a.h_kv + w.g) * a.RP +
                   a.row_tile0 * kRowTile + (lane & 31);
 #pragma unroll
