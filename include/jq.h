@@ -13,6 +13,9 @@
  *   jq_select_topk  top-B retention per KV head (Section 4.3)
  *   jq_compact      gather of the kept K/V rows into a dense pruned cache
  *   jq_evict        all of the above for n_layers x n_seq problems in one call
+ *   jq_score_lse, jq_evict_lse    the same with caller-supplied softmax normalisers
+ *   jq_score_tail, jq_evict_tail  the same with the soft tokens' own keys in the softmax
+ *   jq_hit_rate     critical-KV hit rate between two kept sets (Eq. 6)
  *
  * Conventions common to every entry point
  * ---------------------------------------
@@ -61,7 +64,8 @@ typedef enum jq_status {
     JQ_ERR_NULL = -1,        /* a required pointer is NULL                               */
     JQ_ERR_SHAPE = -2,       /* a dimension, pool_k, scale or cu_seqlens is malformed    */
     JQ_ERR_BUDGET = -3,      /* some budget is outside 1..L_s                            */
-    JQ_ERR_UNSUPPORTED = -4, /* valid but not implemented (d != 128, too many sequences) */
+    JQ_ERR_UNSUPPORTED = -4, /* valid but not implemented (d != 128, too many sequences, */
+                             /* a sequence of 4 GiB or more of keys, a misaligned tensor) */
     JQ_ERR_WORKSPACE = -5,   /* workspace missing, misaligned (16 B) or too small        */
     JQ_ERR_ALIAS = -6,       /* an output overlaps an input or another output            */
     JQ_ERR_LAUNCH = -7       /* the HIP runtime refused a launch                         */
@@ -80,7 +84,8 @@ typedef struct jq_shape {
     int32_t d;                 /* head dimension; only 128 is implemented                     */
     int32_t pool_k;            /* odd >= 1; 1 = no pooling                                    */
     float scale;               /* logit scale; 0 selects 1/sqrt(d); must be finite and >= 0   */
-    const int32_t* cu_seqlens; /* HOST [n_seq+1]; cu[0] = 0, strictly increasing              */
+    const int32_t* cu_seqlens; /* HOST [n_seq+1]; cu[0] = 0, strictly increasing; one sequence's  */
+                               /* keys (L_s * h_kv * d * 2 bytes) must stay below 4 GiB           */
     const int32_t* budgets;    /* HOST [n_seq]; 1 <= budgets[s] <= L_s.  May be NULL for      */
                                /* jq_score and jq_pool, which do not use it.                  */
 } jq_shape;
