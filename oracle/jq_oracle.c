@@ -243,6 +243,28 @@ int jqo_pool(long L, int pool_k, const double* score, double* pooled) {
     return 0;
 }
 
+/*
+ * Training objective, forward value only (Section 4.2, Eq. 3-5): the attention maps of the soft tokens and of
+ * the response tokens over the prompt, each averaged over its tokens, and their mean squared error.
+ * With the scores of jqo_score (sums over n tokens and the G heads of the group) the averaged map is
+ * score / (n * G), so
+ *   mse[g] = (1 / L) * sum_j ( score_a[g,j] / rows_a  -  score_b[g,j] / rows_b )^2,   rows = n * G.
+ * Readings: the average also runs over the query heads that share the KV head; Eq. 5 divides by the
+ * length of the maps (it prints the symbol of the head dimension, which has no place there).
+ */
+int jqo_map_mse(long L, int h_kv, double rows_a, double rows_b, const double* score_a, const double* score_b, double* mse) {
+    if (L < 1 || h_kv < 1 || !(rows_a > 0.0) || !(rows_b > 0.0) || !score_a || !score_b || !mse) return -1;
+    for (int g = 0; g < h_kv; ++g) {
+        double acc = 0.0;
+        for (long j = 0; j < L; ++j) {
+            const double diff = score_a[(size_t)g * L + j] / rows_a - score_b[(size_t)g * L + j] / rows_b;
+            acc += diff * diff;
+        }
+        mse[g] = acc / (double)L;
+    }
+    return 0;
+}
+
 typedef struct { double v; int32_t i; } jqo_item;
 
 static int jqo_item_cmp(const void* a, const void* b) {

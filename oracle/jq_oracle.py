@@ -38,6 +38,8 @@ def _load():
         lib.jqo_score.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p]
         lib.jqo_score_lse.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p, f64p]
         lib.jqo_score_tail.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, u16p, f64p]
+        lib.jqo_map_mse.argtypes = [ctypes.c_long, ctypes.c_int, ctypes.c_double, ctypes.c_double, f64p, f64p, f64p]
+        lib.jqo_map_mse.restype = ctypes.c_int
         lib.jqo_pool.argtypes = [ctypes.c_long, ctypes.c_int, f64p, f64p]
         lib.jqo_select_topk.argtypes = [ctypes.c_long, ctypes.c_long, f64p, i32p]
         lib.jqo_compact.argtypes = [ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_long, u16p, u16p, i32p, u16p, u16p]
@@ -169,6 +171,17 @@ def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0):
             Ko[l, cb[s]:cb[s + 1]] = r["K_out"]
             Vo[l, cb[s]:cb[s + 1]] = r["V_out"]
     return {"scores": scores, "pooled": pooled, "idx": idx, "K_out": Ko, "V_out": Vo}
+
+
+def map_mse(score_a: np.ndarray, rows_a: float, score_b: np.ndarray, rows_b: float) -> np.ndarray:
+    """Eq. 5 forward per KV head: mean over the prompt of (score_a/rows_a - score_b/rows_b)^2; scores [h_kv, L]."""
+    a = np.ascontiguousarray(score_a, dtype=np.float64)
+    b = np.ascontiguousarray(score_b, dtype=np.float64)
+    if a.shape != b.shape or a.ndim != 2:
+        raise ValueError("shape mismatch")
+    out = np.empty(a.shape[0], dtype=np.float64)
+    _check(_load().jqo_map_mse(a.shape[1], a.shape[0], float(rows_a), float(rows_b), a, b, out), "map_mse")
+    return out
 
 
 def hit_rate(idx_cur, idx_ref) -> float:

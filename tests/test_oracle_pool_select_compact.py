@@ -146,3 +146,38 @@ def test_hit_rate():
     assert oracle.hit_rate([1, 2, 3, 4], [1, 2, 3, 4]) == 1.0
     assert oracle.hit_rate([1, 2, 9, 8], [1, 2, 3, 4]) == 0.5
     assert oracle.hit_rate([7], [1, 2]) == 0.0
+
+
+# ---------------------------------------------------------------- Eq. 5 forward (training objective value)
+def test_map_mse_closed_forms():
+    L = 8
+    a = np.full((1, L), 4.0)                       # 4 query rows, uniform map 1/L each -> averaged map 1/8
+    assert oracle.map_mse(a, 4 * L, a, 4 * L)[0] == 0.0
+    b = np.zeros((1, L)); b[0, 0] = 6.0            # 6 query rows, all mass on position 0 -> averaged map e_0
+    # (1/8)[(1/8 - 1)^2 + 7 (1/8)^2] = (49 + 7) / 512
+    np.testing.assert_allclose(oracle.map_mse(a, 4 * L, b, 6.0)[0], 56.0 / 512.0, rtol=1e-15)
+    np.testing.assert_allclose(oracle.map_mse(b, 6.0, a, 4 * L)[0], 56.0 / 512.0, rtol=1e-15)   # symmetric
+    # scaling both maps' row counts together with their scores changes nothing (maps are averages)
+    np.testing.assert_allclose(oracle.map_mse(3 * a, 12 * L, 5 * b, 30.0)[0], 56.0 / 512.0, rtol=1e-15)
+
+
+def test_map_mse_matches_numpy_on_real_maps_and_is_per_head():
+    from workloads import f32_to_bf16_bits
+
+    def rand_bits(rng, shape):
+        return f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+
+    rng = np.random.default_rng(17)
+    n, m, h_q, h_kv, d, L = 4, 9, 4, 2, 16, 50
+    K = rand_bits(rng, (L, h_kv, d))
+    Qs, Qr = rand_bits(rng, (n, h_q, d)), rand_bits(rng, (m, h_q, d))
+    sa, sb = oracle.score(Qs, K), oracle.score(Qr, K)
+    G = h_q // h_kv
+    got = oracle.map_mse(sa, n * G, sb, m * G)
+    want = ((sa / (n * G) - sb / (m * G)) ** 2).mean(axis=1)
+    np.testing.assert_allclose(got, want, rtol=1e-13)
+    assert abs(sa[0].sum() / (n * G) - 1.0) < 1e-12      # the averaged maps are probability vectors
+    sb2 = sb.copy(); sb2[1] += 0.5                        # another head's map does not leak into head 0
+    assert oracle.map_mse(sa, n * G, sb2, m * G)[0] == got[0]
+    with pytest.raises(ValueError):
+        oracle.map_mse(sa, 0.0, sb, 1.0)
