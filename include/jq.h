@@ -16,6 +16,7 @@
  *   jq_score_lse, jq_evict_lse    the same with caller-supplied softmax normalisers
  *   jq_score_tail, jq_evict_tail  the same with the soft tokens' own keys in the softmax
  *   jq_hit_rate     critical-KV hit rate between two kept sets (Eq. 6)
+ *   jq_map_mse      forward value of the training objective (Eq. 5) from two score maps
  *
  * Conventions common to every entry point
  * ---------------------------------------
@@ -154,6 +155,16 @@ int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_
  * idx_ref [n_layers, h_kv, sum ref_budgets], rate [n_layers, n_seq, h_kv] fp32 (DEVICE). */
 int jq_hit_rate(const jq_shape* shape, const int32_t* idx_cur, const int32_t* idx_ref,
                 const int32_t* ref_budgets, float* rate, void* stream);
+
+/* Forward value of the training objective (Section 4.2, Eq. 3-5).  scores_a and scores_b are
+ * jq_score outputs for the same prompt under two sets of query tokens (soft tokens and response
+ * tokens); rows_a, rows_b are their numbers of summed probability rows per KV head
+ * (tokens * h_q / h_kv), so that scores / rows is the attention map averaged over the tokens:
+ *   mse[l,s,g] = (1 / L_s) * sum_t ( scores_a[l,g,t] / rows_a - scores_b[l,g,t] / rows_b )^2
+ * over the tokens t of sequence s.  mse is [n_layers, n_seq, h_kv] fp32 (DEVICE).  Only
+ * n_layers, n_seq, h_kv and cu_seqlens of `shape` matter here. */
+int jq_map_mse(const jq_shape* shape, const float* scores_a, float rows_a, const float* scores_b, float rows_b,
+               float* mse, void* stream);
 
 /* score -> pool -> select -> compact in one call.  `idx_out` (kept positions) and
  * `scores_out` (POOLED scores) may each be NULL when the caller does not want

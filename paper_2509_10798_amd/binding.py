@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced", "jq_hit_rate",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
            "jq_copy_probe", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_combine_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel",
                  "jq_select_finalize_kernel")
@@ -59,6 +59,7 @@ def lib() -> ctypes.CDLL:
         L.jq_score_lse.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_lse.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_hit_rate.argtypes = [shp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, vp]
+        L.jq_map_mse.argtypes = [shp, vp, ctypes.c_float, vp, ctypes.c_float, vp, vp]
         L.jq_score_tail.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_pool.argtypes = [shp, vp, vp, vp]
@@ -253,6 +254,17 @@ def hit_rate(shape: Shape, idx_cur, idx_ref, ref_budgets=None, rate=None, stream
                              rb.ctypes.data_as(i32p) if rb is not None else ctypes.cast(None, i32p), _ptr(rate),
                              _stream(stream)), "jq_hit_rate")
     return rate
+
+
+def map_mse(shape: Shape, scores_a, rows_a: float, scores_b, rows_b: float, mse=None, stream=None):
+    """Eq. 5 forward per (layer, sequence, head): mean over the prompt of (scores_a/rows_a - scores_b/rows_b)^2."""
+    import torch
+    if mse is None:
+        mse = torch.empty((shape.n_layers, shape.n_seq, shape.h_kv), dtype=torch.float32, device=scores_a.device)
+    cs = shape.c_struct()
+    _check(lib().jq_map_mse(ctypes.byref(cs), _ptr(scores_a), float(rows_a), _ptr(scores_b), float(rows_b), _ptr(mse),
+                            _stream(stream)), "jq_map_mse")
+    return mse
 
 
 def copy_probe(src, dst, stream=None):

@@ -313,6 +313,20 @@ int jq_hit_rate(const jq_shape* shape, const int32_t* idx_cur, const int32_t* id
     return launch_status(launch_hit_rate(p, cu_ref, tb_ref, idx_cur, idx_ref, rate, (hipStream_t)stream));
 }
 
+int jq_map_mse(const jq_shape* shape, const float* scores_a, float rows_a, const float* scores_b, float rows_b, float* mse,
+               void* stream) {
+    Plan p;
+    const int rc = make_plan(shape, false, &p);
+    if (rc != JQ_OK) return rc;
+    if (!scores_a || !scores_b || !mse) return JQ_ERR_NULL;
+    if (!(rows_a > 0.0f) || !(rows_b > 0.0f) || !std::isfinite(rows_a) || !std::isfinite(rows_b)) return JQ_ERR_SHAPE;
+    if (misaligned(scores_a, 4) || misaligned(scores_b, 4) || misaligned(mse, 4)) return JQ_ERR_UNSUPPORTED;
+    const size_t out_bytes = (size_t)p.n_layers * p.n_seq * p.h_kv * sizeof(float);
+    if (overlaps(mse, out_bytes, scores_a, score_bytes(p)) || overlaps(mse, out_bytes, scores_b, score_bytes(p)))
+        return JQ_ERR_ALIAS;
+    return launch_status(launch_map_mse(p, scores_a, rows_a, scores_b, rows_b, mse, (hipStream_t)stream));
+}
+
 int jq_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
     if (!src || !dst) return JQ_ERR_NULL;
     if (bytes == 0 || bytes % 16 != 0) return JQ_ERR_SHAPE;

@@ -84,6 +84,8 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
                         uint32_t* zero = nullptr, size_t zero_words = 0, const float* lse = nullptr,
                         const void* k_tail = nullptr);
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st);
+hipError_t launch_map_mse(const Plan& p, const float* scores_a, float rows_a, const float* scores_b, float rows_b,
+                          float* mse, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st);
 hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st);
 // With K, V, K_out, V_out (all or none) the selection also gathers the kept rows when its fast path runs;

@@ -181,6 +181,50 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
     }
 }
 
+// Forward value of the training objective (paper Section 4.2, Eq. 3-5): mean squared difference of two averaged
+// attention maps, map = scores / rows.  One workgroup per (layer, sequence, KV head); every thread sums its
+// strided share in fp64 (the terms span many orders of magnitude), then a fixed-order tree in LDS.
+constexpr int kMseThreads = 1024;
+struct MseArgs {
+    const float* a; const float* b;  // [n_layers][h_kv][T]
+    float* mse;                      // [n_layers][n_seq][h_kv]
+    float inv_rows_a, inv_rows_b;
+    int32_t h_kv;
+    int64_t T;
+    SeqTab tab;
+};
+
+__global__ __launch_bounds__(kMseThreads) void jq_map_mse_kernel(MseArgs a) {
+    __shared__ double part[kMseThreads];
+    const int g = blockIdx.x % a.h_kv;
+    const int s = (blockIdx.x / a.h_kv) % a.tab.n_seq;
+    const int layer = blockIdx.x / (a.h_kv * a.tab.n_seq);
+    const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
+    const int64_t row = ((int64_t)layer * a.h_kv + g) * a.T + a.tab.cu_seq[s];
+    double acc = 0.0;
+    for (int j = threadIdx.x; j < L; j += kMseThreads) {
+        const double diff = (double)a.a[row + j] * (double)a.inv_rows_a - (double)a.b[row + j] * (double)a.inv_rows_b;
+        acc += diff * diff;
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int half = kMseThreads / 2; half >= 1; half >>= 1) {
+        if ((int)threadIdx.x < half) part[threadIdx.x] += part[threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) a.mse[blockIdx.x] = (float)(part[0] / (double)L);
+}
+
+hipError_t launch_map_mse(const Plan& p, const float* scores_a, float rows_a, const float* scores_b, float rows_b,
+                          float* mse, hipStream_t st) {
+    MseArgs a;
+    a.a = scores_a; a.b = scores_b; a.mse = mse;
+    a.inv_rows_a = 1.0f / rows_a; a.inv_rows_b = 1.0f / rows_b;
+    a.h_kv = p.h_kv; a.T = p.T; a.tab = p.tab;
+    return launch_kernel(jq_map_mse_kernel, dim3((unsigned)(p.n_layers * p.n_seq * p.h_kv)), dim3(kMseThreads), 0, st, nullptr,
+                         -1, a);
+}
+
 __global__ __launch_bounds__(256) void jq_fill_u32_kernel(uint32_t* dst, size_t n, uint32_t v) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;

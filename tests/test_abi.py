@@ -93,6 +93,9 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_hit_rate(ctypes.byref(cs), Ko, Vo, None, Ko + 8, None) == -6                       # rate inside idx_cur
     too_many = (ctypes.c_int32 * sh.n_seq)(*([10 ** 9] * sh.n_seq))
     assert L.jq_hit_rate(ctypes.byref(cs), Ko, Vo, too_many, ws, None) == -3                       # reference budget > L
+    assert L.jq_map_mse(ctypes.byref(cs), K, 1.0, None, 1.0, ws, None) == -1
+    assert L.jq_map_mse(ctypes.byref(cs), K, 0.0, V, 1.0, ws, None) == -2                          # no rows
+    assert L.jq_map_mse(ctypes.byref(cs), K, 1.0, V, 1.0, K + 64, None) == -6                      # result inside an input
     assert L.jq_copy_probe(K, K + 64, 1024, None) == -6 and L.jq_copy_probe(K, Ko, 24, None) == -2
     assert L.jq_compact(ctypes.byref(cs), K, V, ws, V, Vo, None) == -6
     assert L.jq_pool(ctypes.byref(cs), K, K, None) == -6

@@ -166,3 +166,34 @@ def test_hit_rate_matches_oracle_on_random_sets_and_on_two_scorers():
     for g in range(w.h_kv):
         assert abs(float(rate[0, 0, g]) - oracle.hit_rate(ib[0, g], ia[0, g])) <= 1e-7
     assert rate.min() > 0.5            # the planted heavy hitters stay in both sets
+
+
+def test_map_mse_of_soft_and_response_maps_matches_oracle():
+    # Eq. 3-5 forward: soft-token map (n = 8 tokens) against a response map (m = 70 tokens: 280 query rows, three
+    # passes over K), both from jq_score, ragged batch of two prompts
+    torch = torch_()
+    rng = np.random.default_rng(81)
+    seq_lens, h_q, h_kv, d, n, m = [900, 333], 8, 2, 128, 8, 70
+    T = sum(seq_lens)
+    K = f32_to_bf16_bits(rng.standard_normal((1, T, h_kv, d)).astype(np.float32))
+    Qs = f32_to_bf16_bits(rng.standard_normal((1, 2, n, h_q, d)).astype(np.float32))
+    Qr = f32_to_bf16_bits(rng.standard_normal((1, 2, m, h_q, d)).astype(np.float32))
+    G = h_q // h_kv
+    Kd = to_dev_bf16(K)
+    sh_s = jq.Shape(n_layers=1, seq_lens=seq_lens, n_q=n, h_q=h_q, h_kv=h_kv)
+    sh_r = jq.Shape(n_layers=1, seq_lens=seq_lens, n_q=m, h_q=h_q, h_kv=h_kv)
+    sa = jq.score(sh_s, to_dev_bf16(Qs), Kd)
+    sb = jq.score(sh_r, to_dev_bf16(Qr), Kd)
+    got = jq.map_mse(sh_s, sa, n * G, sb, m * G)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    for s in range(2):
+        ra = oracle.score(Qs[0, s], K[0, cu[s]:cu[s + 1]])
+        rb = oracle.score(Qr[0, s], K[0, cu[s]:cu[s + 1]])
+        want = oracle.map_mse(ra, n * G, rb, m * G)
+        # the maps agree with the oracle's to 2e-3 relative per entry, so does their squared difference in the mean
+        np.testing.assert_allclose(got[0, s], want, rtol=8e-3)
+        # and the reduction itself is exact to fp32 rounding when fed the GPU's own maps
+        own = oracle.map_mse(sa[0, :, cu[s]:cu[s + 1]].cpu().numpy(), n * G, sb[0, :, cu[s]:cu[s + 1]].cpu().numpy(), m * G)
+        np.testing.assert_allclose(got[0, s], own, rtol=2e-6)
