@@ -11,8 +11,8 @@
 //
 // One wave owns one (layer, sequence, KV head) and a strided set of that sequence's 32-key tiles, and
 // keeps the head's (up to) 128 query rows in registers as MFMA operands.  Gathering them from Q costs 32 row-strided loads per
-// wave (each touches 32 cache lines), so whoever reads Q first -- pass 1, or the kernel that converts
-// caller-supplied normalisers -- also leaves a copy in operand order, which pass 2 reads with fully
+// wave (each touches 32 cache lines), so pass 1 fetches them like a key tile (whole rows, through an LDS
+// slot) and also leaves a copy in operand order, which pass 2 reads with fully
 // coalesced loads.  Key tiles of 32 keys x 128 channels are fetched
 // asynchronously, straight from global memory into a private, XOR-swizzled 8 KiB LDS slot (buffer
 // loads with the LDS modifier, 16 B per lane, 16 lanes per 256-byte key row, so every 128-byte
@@ -38,6 +38,8 @@ struct ScoreArgs {
     const uint16_t* Q;
     const uint16_t* K;
     const uint16_t* K_tail;  // [n_layers][n_seq][n_q][h_kv][d] keys of the soft tokens themselves, or null
+    const float* lse;        // [n_layers][n_seq][n_q][h_q] caller-supplied natural-log normalisers, or null
+    float inv_scale;         // 1 / scale
     float2* stats;    // [n_layers][n_chunks][h_kv][RP]: (m, Z) per score wave (n_chunks = waves per layer and head)
     uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
     u32x4* qfrag;     // [n_layers][n_seq][h_kv][RP/32][8][64]: query rows in MFMA operand order
@@ -454,6 +456,16 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 // ------------------------------------------------------------------------------------------------
 // combine: per (layer, sequence, head, row) merge the partials into -beta/c as three bf16 terms
 // ------------------------------------------------------------------------------------------------
+// -beta/c as the three truncated bf16 terms that enter the second pass through its extra MFMA step.
+__device__ __forceinline__ uint2 split_bf16x3(float x) {
+    const uint32_t hi = __float_as_uint(x) & 0xFFFF0000u;
+    const float r1 = x - __uint_as_float(hi);
+    const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
+    const float r2 = r1 - __uint_as_float(mid);
+    const uint32_t lo = __float_as_uint(r2) & 0xFFFF0000u;
+    return make_uint2((hi >> 16) | mid, lo >> 16);
+}
+
 constexpr int kCombineLanes = 32;  // partial-lanes per query row
 __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(ScoreArgs a) {
     // one workgroup per (layer, sequence, head, tile of 32 rows); thread = (row r, partial-lane kl)
@@ -503,57 +515,7 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
     }
     // padded rows (row >= rows) get 2^(c*x) = 0
     const float x = row < a.rows ? -(M + __log2f(Z)) / a.c : -1.0e30f;
-    const uint32_t hi = __float_as_uint(x) & 0xFFFF0000u;
-    const float r1 = x - __uint_as_float(hi);
-    const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
-    const float r2 = r1 - __uint_as_float(mid);
-    const uint32_t lo = __float_as_uint(r2) & 0xFFFF0000u;
-    a.aug[((int64_t)(layer * a.n_seq + s) * a.h_kv + g) * a.RP + row] = make_uint2((hi >> 16) | mid, lo >> 16);
-}
-
-// Caller-supplied normalisers: lse[layer, seq, i, h] (natural log) becomes the same three-term
-// -beta/c that the combine step would have produced (beta = lse * log2 e, c = scale * log2 e, so
-// -beta/c = -lse / scale), in the wave's row order r = i * group + hh.
-__global__ __launch_bounds__(256) void jq_lse_to_aug_kernel(ScoreArgs a, const float* lse, float inv_scale) {
-    const int64_t n = (int64_t)a.n_layers * a.n_seq * a.h_kv * a.RP;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    if (a.zero) {
-        for (int64_t i = tid; i < (int64_t)a.zero_words; i += stride) a.zero[i] = 0u;
-    }
-    // operand-order copy of Q (no statistics pass runs in this mode): one 16-byte entry per thread and step
-    for (int64_t e = tid; e < n * 16; e += stride) {
-        const int lane = (int)(e & 63), ks = (int)((e >> 6) & 7);
-        int64_t rest = e >> 9;  // (item, row tile)
-        const int tiles = a.RP / kRowTile;
-        const int rt = (int)(rest % tiles);
-        rest /= tiles;
-        const int g = (int)(rest % a.h_kv);
-        rest /= a.h_kv;  // = layer * n_seq + s
-        const int row = rt * kRowTile + (lane & 31);
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (row < a.rows) {
-            const int i = row / a.group, h = g * a.group + row % a.group;
-            v = *(const u32x4*)((const char*)a.Q + ((rest * a.n_q + i) * a.h_q + h) * kHeadDim * 2 + ks * 32 + (lane >> 5) * 16);
-        }
-        a.qfrag[e] = v;
-    }
-    if (tid >= n) return;
-    const int r = (int)(tid % a.RP);
-    int64_t rest = tid / a.RP;
-    const int g = (int)(rest % a.h_kv);
-    rest /= a.h_kv;  // = layer * n_seq + s
-    float x = -1.0e30f;
-    if (r < a.rows) {
-        const int i = r / a.group, h = g * a.group + r % a.group;
-        x = -lse[(rest * a.n_q + i) * a.h_q + h] * inv_scale;
-    }
-    const uint32_t hi = __float_as_uint(x) & 0xFFFF0000u;
-    const float r1 = x - __uint_as_float(hi);
-    const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
-    const float r2 = r1 - __uint_as_float(mid);
-    const uint32_t lo = __float_as_uint(r2) & 0xFFFF0000u;
-    a.aug[tid] = make_uint2((hi >> 16) | mid, lo >> 16);
+    a.aug[((int64_t)(layer * a.n_seq + s) * a.h_kv + g) * a.RP + row] = split_bf16x3(x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -567,7 +529,11 @@ __device__ __forceinline__ f32x16 score_chain(const bf16x8 (&q)[8], bf16x8 qaug,
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(qaug, ones, acc, 0, 0, 0);  // - beta_r / c
 }
 
-template <int NQT>
+// FROM_LSE: the caller supplied the normalisers, no statistics pass has run: the wave gathers its query rows
+// itself (through its second LDS slot, like pass 1) and turns lse into the -beta/c terms on the fly
+// (beta = lse * log2 e, c = scale * log2 e, so -beta/c = -lse / scale); the launch also clears the words the
+// selection stage needs cleared.
+template <int NQT, bool FROM_LSE>
 __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
     WaveItem w;
@@ -587,12 +553,33 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
                    w.L - t * kKeyTile, tl, lane);
     };
     fetch(0);
-    if (w.n_tiles > 1) fetch(1);
-
     bf16x8 qf[NQT][8];
-    load_q_frags<NQT>(a, w, lane, qf);
     bf16x8 qaug[NQT];
-    {
+    if (FROM_LSE) {
+        if (a.zero) {
+            const uint64_t per = (a.zero_words + gridDim.x - 1) / gridDim.x;
+            const uint64_t z0 = per * blockIdx.x, z1 = z0 + per < a.zero_words ? z0 + per : a.zero_words;
+            for (uint64_t i = z0 + threadIdx.x; i < z1; i += blockDim.x) a.zero[i] = 0u;
+        }
+        load_q_via_lds<NQT>(a, w, lane, slots + kSlotBytes, qf);
+        wait_frags_read();
+        if (w.n_tiles > 1) fetch(1);
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
+            float x = -1.0e30f;  // padded rows get 2^(c*x) = 0
+            if (row < a.rows) {
+                const int i = row / a.group, h = w.g * a.group + row % a.group;
+                x = -a.lse[((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q + i) * a.h_q + h] * a.inv_scale;
+            }
+            const uint2 t = split_bf16x3(x);
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (half == 0) { v[0] = t.x; v[1] = t.y; }
+            qaug[qt] = as_bf16x8(v);
+        }
+    } else {
+        if (w.n_tiles > 1) fetch(1);
+        load_q_frags<NQT>(a, w, lane, qf);
         const uint2* ap = a.aug + ((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP +
                           a.row_tile0 * kRowTile + (lane & 31);
 #pragma unroll
@@ -619,7 +606,8 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         }
     };
 
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // Q, the -beta/c terms and the first two tiles are in
+    // everything older than the second tile's eight loads (first tile, Q, the -beta/c terms) is in after this
+    wait_tile_landed(w.n_tiles > 1);
     for (int k = 0; k < w.n_tiles; ++k) {
         if (k > 0) wait_tile_landed(k + 1 < w.n_tiles);
         bf16x8 kf[8];
@@ -675,13 +663,14 @@ static hipError_t launch_stats_n(int nqt, const ScoreArgs& a, dim3 grid, hipStre
     }
 }
 
+template <bool FROM_LSE>
 static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st, void* const* marks) {
     dim3 block(kScoreWaves * 64);
     switch (nqt) {
-        case 1: return launch_kernel(jq_score_kernel<1>, grid, block, 0, st, marks, kTrScore, a);
-        case 2: return launch_kernel(jq_score_kernel<2>, grid, block, 0, st, marks, kTrScore, a);
-        case 3: return launch_kernel(jq_score_kernel<3>, grid, block, 0, st, marks, kTrScore, a);
-        default: return launch_kernel(jq_score_kernel<4>, grid, block, 0, st, marks, kTrScore, a);
+        case 1: return launch_kernel(jq_score_kernel<1, FROM_LSE>, grid, block, 0, st, marks, kTrScore, a);
+        case 2: return launch_kernel(jq_score_kernel<2, FROM_LSE>, grid, block, 0, st, marks, kTrScore, a);
+        case 3: return launch_kernel(jq_score_kernel<3, FROM_LSE>, grid, block, 0, st, marks, kTrScore, a);
+        default: return launch_kernel(jq_score_kernel<4, FROM_LSE>, grid, block, 0, st, marks, kTrScore, a);
     }
 }
 
@@ -711,14 +700,9 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     const int64_t waves = (int64_t)p.n_layers * p.n_chunks * p.h_kv;
     dim3 grid((unsigned)((waves + kScoreWaves - 1) / kScoreWaves));
     hipError_t e;
-    if (lse) {  // normalisers supplied: no statistics pass over K
-        const int64_t n_rows = (int64_t)p.n_layers * p.n_seq * p.h_kv * a.RP;
-        const int64_t want = (n_rows * 16 + 255) / 256, need = (n_rows + 255) / 256;  // one Q entry per thread if possible
-        const int64_t blocks = want < 2048 ? want : (need > 2048 ? need : 2048);
-        e = launch_kernel(jq_lse_to_aug_kernel, dim3((unsigned)blocks), dim3(256), 0, st, nullptr, -1, a, lse,
-                          1.0f / p.scale);
-        if (e != hipSuccess) return e;
-    } else {
+    a.lse = lse;
+    a.inv_scale = 1.0f / p.scale;
+    if (!lse) {
         for (int rg = 0; rg < p.row_groups; ++rg) {
             a.row_tile0 = rg * kMaxRowTiles;
             const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
@@ -731,8 +715,10 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     for (int rg = 0; rg < p.row_groups; ++rg) {
         a.row_tile0 = rg * kMaxRowTiles;
         a.accumulate = rg > 0;
+        if (rg > 0) a.zero = nullptr;  // cleared once, by the first launch (normalisers supplied: no combine step does it)
         const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
-        if ((e = launch_score_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
+        e = lse ? launch_score_n<true>(nqt, a, grid, st, marks) : launch_score_n<false>(nqt, a, grid, st, marks);
+        if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
