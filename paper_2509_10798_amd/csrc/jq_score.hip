@@ -10,12 +10,12 @@
 //                    multiply, one exp2 and one add per logit.
 //
 // One wave owns one (layer, sequence, KV head) and a strided set of that sequence's 32-key tiles, and
-// keeps the head's (up to) 128 query rows in registers as MFMA operands.  Gathering them from Q costs 32 row-strided loads per
-// wave (each touches 32 cache lines), so pass 1 fetches them like a key tile (whole rows, through an LDS
-// slot) and also leaves a copy in operand order, which pass 2 reads with fully
-// coalesced loads.  Key tiles of 32 keys x 128 channels are fetched
-// asynchronously, straight from global memory into a private, XOR-swizzled 8 KiB LDS slot (buffer
-// loads with the LDS modifier, 16 B per lane, 16 lanes per 256-byte key row, so every 128-byte
+// keeps the head's (up to) 128 query rows in registers as MFMA operands.  Gathering them from Q with
+// one row per lane would cost 32 row-strided loads per wave (each touching 32 cache lines), so pass 1
+// fetches them like a key tile (whole rows, through an LDS slot) and also leaves a copy in operand
+// order, which pass 2 reads with fully coalesced loads.  Key tiles of 32 keys x 128 channels are
+// fetched asynchronously, straight from global memory into a private, XOR-swizzled 8 KiB LDS slot
+// (buffer loads with the LDS modifier, 16 B per lane, 16 lanes per 256-byte key row, so every 128-byte
 // line is requested whole), double buffered, and read back in MFMA operand order without bank
 // conflicts.  Waves never share LDS, so no workgroup barrier is needed; the only synchronisation is
 // the wave's own s_waitcnt on its outstanding loads.
