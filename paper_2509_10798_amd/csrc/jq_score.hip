@@ -111,27 +111,6 @@ __device__ __forceinline__ bool wave_item(const ScoreArgs& a, bool reverse, Wave
     return true;
 }
 
-// Query rows of the wave's KV head as MFMA operands (row r = i * group + hh  <->  Q[i, g*group + hh]).
-template <int NQT>
-__device__ __forceinline__ void load_q(const ScoreArgs& a, const WaveItem& w, int lane, bf16x8 (&qf)[NQT][8]) {
-    const int half = lane >> 5;
-    const char* qbase = (const char*)a.Q + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q) * a.h_q * kHeadDim * 2;
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-        const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
-        const bool valid = row < a.rows;
-        const int i = valid ? row / a.group : 0;
-        const int hh = valid ? row % a.group : 0;
-        const char* qp = qbase + ((int64_t)i * a.h_q + (w.g * a.group + hh)) * kHeadDim * 2 + half * 16;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            u32x4 v = *(const u32x4*)(qp + ks * 32);  // row 0 of the head when !valid: in bounds, then zeroed
-            if (!valid) v = u32x4{0u, 0u, 0u, 0u};
-            qf[qt][ks] = as_bf16x8(v);
-        }
-    }
-}
-
 // Operand-order copy of the query rows: entry ((item * RP/32 + row tile) * 8 + k-step) * 64 + lane.
 __device__ __forceinline__ int64_t qfrag_index(const ScoreArgs& a, int layer, int seq, int g, int row_tile) {
     return ((((int64_t)(layer * a.n_seq + seq) * a.h_kv + g) * (a.RP / kRowTile) + row_tile) * 8) * 64;
