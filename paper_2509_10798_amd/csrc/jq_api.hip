@@ -77,22 +77,25 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
         if (v >= kKeyTile && v <= 8192 && v % kKeyTile == 0) chunk = v;
     }
     p.chunk_keys = (int32_t)chunk;
-    int64_t nc = 0;
+    int64_t nc = 0, ng = 0;
     p.tab.cu_chunk[0] = 0;
+    p.tab.cu_cgrp[0] = 0;
     for (int s = 0; s < sh->n_seq; ++s) {
         const int64_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
-        nc += (L + chunk - 1) / chunk;
+        const int64_t waves = (L + chunk - 1) / chunk;
+        nc += waves;
+        ng += (waves + kScoreWaves - 1) / kScoreWaves;
         p.tab.cu_chunk[s + 1] = (int32_t)nc;
+        p.tab.cu_cgrp[s + 1] = (int32_t)ng;
     }
     p.n_chunks = (int32_t)nc;
-    if ((int64_t)p.n_layers * nc * p.h_kv / kScoreWaves >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
+    if ((int64_t)p.n_layers * ng * p.h_kv >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
     if ((int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
 
     const size_t RP = (size_t)p.row_tiles * kRowTile;
     size_t off = 0;
     p.off_stats = off;  off += align_up((size_t)p.n_layers * nc * p.h_kv * RP * sizeof(float2));
     p.off_aug = off;    off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * RP * sizeof(uint2));
-    p.off_qfrag = off;  off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * RP * kHeadDim * 2);
     p.off_hist = off;   off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride * sizeof(uint32_t));
     p.off_scores = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));
     p.off_pooled = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));

@@ -19,12 +19,13 @@ constexpr int kHistBins = 2048;     // level-1 radix bins (top 11 bits of the so
 constexpr int kHistStride = kHistBins + 16;  // per problem: the bins, then [0] #sure and [1] #candidate counters
 constexpr int kSelectThreads = 1024;
 
-// Per-call sequence table, passed to kernels by value (about 1.5 KiB of kernarg).
+// Per-call sequence table, passed to kernels by value (about 2 KiB of kernarg).
 struct SeqTab {
     int32_t n_seq;
     int32_t cu_seq[JQ_MAX_SEQ + 1];    // token offsets
     int32_t cu_bud[JQ_MAX_SEQ + 1];    // kept-row offsets
     int32_t cu_chunk[JQ_MAX_SEQ + 1];  // score-wave offsets (ceil(L / chunk_keys) waves per sequence and head)
+    int32_t cu_cgrp[JQ_MAX_SEQ + 1];   // score-workgroup offsets (ceil(waves / 4) workgroups per sequence and head)
 };
 
 // Everything the host derives from a jq_shape.
@@ -40,7 +41,7 @@ struct Plan {
     SeqTab tab;
     void* const* marks;   // host only: nullptr, or 2 * kTraceKernels events (start, stop) for jq_evict_traced
     // workspace layout (byte offsets, 256-aligned)
-    size_t off_stats, off_aug, off_qfrag, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
+    size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
 };
 
 // Largest s with cu[s] <= v (cu[0] = 0, strictly increasing, v < cu[n]).

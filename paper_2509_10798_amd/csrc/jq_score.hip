@@ -10,15 +10,15 @@
 //                    multiply, one exp2 and one add per logit.
 //
 // One wave owns one (layer, sequence, KV head) and a strided set of that sequence's 32-key tiles, and
-// keeps the head's (up to) 128 query rows in registers as MFMA operands.  Gathering them from Q with
-// one row per lane would cost 32 row-strided loads per wave (each touching 32 cache lines), so pass 1
-// fetches them like a key tile (whole rows, through an LDS slot) and also leaves a copy in operand
-// order, which pass 2 reads with fully coalesced loads.  Key tiles of 32 keys x 128 channels are
+// keeps the head's (up to) 128 query rows in registers as MFMA operands.  The four waves of a workgroup
+// work on the same head and fetch its query rows together (one row tile each, whole rows, turned into
+// operand order through LDS) -- gathering them one row per lane would cost every wave 32 row-strided
+// loads that touch 32 cache lines each.  Key tiles of 32 keys x 128 channels are
 // fetched asynchronously, straight from global memory into a private, XOR-swizzled 8 KiB LDS slot
 // (buffer loads with the LDS modifier, 16 B per lane, 16 lanes per 256-byte key row, so every 128-byte
 // line is requested whole), double buffered, and read back in MFMA operand order without bank
-// conflicts.  Waves never share LDS, so no workgroup barrier is needed; the only synchronisation is
-// the wave's own s_waitcnt on its outstanding loads.
+// conflicts.  After the start-up waves never share LDS, so the streaming loop has no workgroup barrier;
+// its only synchronisation is the wave's own s_waitcnt on its outstanding loads.
 //
 // MFMA 32x32x16 bf16 operand layout used here: lane l supplies row/column (l & 31) and the 8
 // contraction elements selected by (l >> 5); both operands use the same element order, so any
@@ -42,9 +42,9 @@ struct ScoreArgs {
     float inv_scale;         // 1 / scale
     float2* stats;    // [n_layers][n_chunks][h_kv][RP]: (m, Z) per score wave (n_chunks = waves per layer and head)
     uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
-    u32x4* qfrag;     // [n_layers][n_seq][h_kv][RP/32][8][64]: query rows in MFMA operand order
     float* scores;    // [n_layers][h_kv][T]
     int32_t n_layers, n_seq, n_q, h_q, h_kv, group, rows, RP, chunk_keys, n_chunks;
+    int32_t n_cgrp;       // workgroups per layer and head: sum over sequences of ceil(waves / 4)
     int32_t group_shift;  // log2(group) when group is a power of two, else -1
     int32_t row_tile0;   // first query-row tile of this launch
     int32_t accumulate;  // pass 2: add to `scores` instead of overwriting
@@ -83,57 +83,35 @@ __device__ __forceinline__ void wait_frags_read() {
 // W = ceil(L / chunk_keys) waves per head; wave w of them takes the 32-key tiles w, w + W, w + 2W, ...
 // Interleaving the tiles (instead of giving each wave one contiguous range) makes all waves that run
 // at the same time sweep one window of the key tensor, which DRAM serves at close to its streaming rate.
+// The four waves of a workgroup are consecutive waves of ONE (layer, sequence, head), so they can share
+// the head's query rows; a sequence whose W is not a multiple of four leaves the last workgroup's
+// surplus waves without tiles (they only help with the query rows).
 struct WaveItem {
-    int layer, seq, g, chunk_global;  // chunk_global: the wave's slot in the per-chunk statistics
+    int layer, seq, g, chunk_global;  // chunk_global: the wave's slot in the per-wave statistics
     int wave, n_waves;                // w and W
     int L;                            // keys in the sequence
-    int n_tiles;                      // tiles this wave owns
+    int n_tiles;                      // tiles this wave owns (0: surplus wave)
     int64_t tok0;                     // first token of the sequence in the flattened T axis
 };
 
-__device__ __forceinline__ bool wave_item(const ScoreArgs& a, bool reverse, WaveItem& w) {
-    const int64_t total = (int64_t)a.n_layers * a.n_chunks * a.h_kv;
+__device__ __forceinline__ void wave_item(const ScoreArgs& a, bool reverse, WaveItem& w) {
+    const int64_t total = (int64_t)a.n_layers * a.n_cgrp * a.h_kv;  // == gridDim.x
+    int64_t b = blockIdx.x;
+    if (reverse) b = total - 1 - b;
     // readfirstlane makes the wave index (and everything derived from it) a scalar for the compiler
-    int64_t wid = (int64_t)blockIdx.x * kScoreWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    if (wid >= total) return false;
-    if (reverse) wid = total - 1 - wid;
-    w.g = (int)(wid % a.h_kv);
-    int64_t rest = wid / a.h_kv;
-    w.chunk_global = (int)(rest % a.n_chunks);
-    w.layer = (int)(rest / a.n_chunks);
-    w.seq = find_seq(a.tab.cu_chunk, a.tab.n_seq, w.chunk_global);
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    w.g = (int)(b % a.h_kv);  // heads vary fastest: neighbouring workgroups read neighbouring 256-byte pieces of a token row
+    const int64_t rest = b / a.h_kv;
+    const int cg = (int)(rest % a.n_cgrp);
+    w.layer = (int)(rest / a.n_cgrp);
+    w.seq = find_seq(a.tab.cu_cgrp, a.tab.n_seq, cg);
     w.L = a.tab.cu_seq[w.seq + 1] - a.tab.cu_seq[w.seq];
-    w.wave = w.chunk_global - a.tab.cu_chunk[w.seq];
     w.n_waves = a.tab.cu_chunk[w.seq + 1] - a.tab.cu_chunk[w.seq];
+    w.wave = (cg - a.tab.cu_cgrp[w.seq]) * kScoreWaves + wv;
+    w.chunk_global = a.tab.cu_chunk[w.seq] + w.wave;
     const int seq_tiles = (w.L + kKeyTile - 1) / kKeyTile;  // >= n_waves, since a chunk is at least one tile
-    w.n_tiles = (seq_tiles - w.wave + w.n_waves - 1) / w.n_waves;
+    w.n_tiles = w.wave < w.n_waves ? (seq_tiles - w.wave + w.n_waves - 1) / w.n_waves : 0;
     w.tok0 = a.tab.cu_seq[w.seq];
-    return true;
-}
-
-// Operand-order copy of the query rows: entry ((item * RP/32 + row tile) * 8 + k-step) * 64 + lane.
-__device__ __forceinline__ int64_t qfrag_index(const ScoreArgs& a, int layer, int seq, int g, int row_tile) {
-    return ((((int64_t)(layer * a.n_seq + seq) * a.h_kv + g) * (a.RP / kRowTile) + row_tile) * 8) * 64;
-}
-
-template <int NQT>
-__device__ __forceinline__ void store_q_frags(const ScoreArgs& a, const WaveItem& w, int lane, const bf16x8 (&qf)[NQT][8]) {
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-        u32x4* dst = a.qfrag + qfrag_index(a, w.layer, w.seq, w.g, a.row_tile0 + qt) + lane;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) dst[ks * 64] = __builtin_bit_cast(u32x4, qf[qt][ks]);
-    }
-}
-
-template <int NQT>
-__device__ __forceinline__ void load_q_frags(const ScoreArgs& a, const WaveItem& w, int lane, bf16x8 (&qf)[NQT][8]) {
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-        const u32x4* src = a.qfrag + qfrag_index(a, w.layer, w.seq, w.g, a.row_tile0 + qt) + lane;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[qt][ks] = as_bf16x8(src[ks * 64]);
-    }
 }
 
 // ---- key tiles: global -> LDS -------------------------------------------------------------------
@@ -188,21 +166,24 @@ __device__ __forceinline__ void lds_get_frags(const char* slot, bf16x8 (&kf)[8],
     }
 }
 
-// Query rows of the wave's KV head (row r = i * group + hh  <->  Q[i, g*group + hh]) as MFMA operands,
-// fetched like a key tile: every load instruction covers four whole 256-byte rows (lane l takes 16 B of
-// row 4i + (l >> 4)), so each cache line is requested once, and an 8 KiB LDS slot turns one tile of 32
-// rows at a time into operand order.  All global loads are issued before the first LDS round trip.
+// Query rows of the workgroup's KV head (row r = i * group + hh  <->  Q[i, g*group + hh]) as MFMA operands
+// of every wave.  Wave qt fetches row tile qt like a key tile -- every load instruction covers four whole
+// 256-byte rows (lane l takes 16 B of row 4i + (l >> 4)), so each cache line is requested once -- and
+// writes it, swizzled, into its own second LDS slot; after a barrier every wave reads all tiles in operand
+// order.  The second barrier frees the slots for key tiles.  Every wave of the workgroup must call this.
 template <int NQT>
-__device__ __forceinline__ void load_q_via_lds(const ScoreArgs& a, const WaveItem& w, int lane, char* slot,
-                                               bf16x8 (&qf)[NQT][8]) {
-    const char* qbase = (const char*)a.Q + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q) * a.h_q * kHeadDim * 2;
-    u32x4 raw[NQT][8];
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
+__device__ __forceinline__ void load_q_shared(const ScoreArgs& a, const WaveItem& w, int lane, char* lds_base,
+                                              bf16x8 (&qf)[NQT][8]) {
+    static_assert(NQT <= kScoreWaves, "one wave per query-row tile");
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (wv < NQT) {
+        const char* qbase = (const char*)a.Q + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q) * a.h_q * kHeadDim * 2;
+        char* slot = lds_base + (wv * 2 + 1) * kSlotBytes;
+        u32x4 raw[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int r = 4 * i + (lane >> 4);
-            const int row = (a.row_tile0 + qt) * kRowTile + r;
+            const int row = (a.row_tile0 + wv) * kRowTile + r;
             const bool valid = row < a.rows;
             int it = 0, hh = 0;
             if (valid) {
@@ -212,15 +193,16 @@ __device__ __forceinline__ void load_q_via_lds(const ScoreArgs& a, const WaveIte
             const int c = (lane & 15) ^ (r & 15);  // logical chunk; it lands at physical chunk (lane & 15)
             u32x4 v = *(const u32x4*)(qbase + ((int64_t)it * a.h_q + (w.g * a.group + hh)) * kHeadDim * 2 + c * 16);
             if (!valid) v = u32x4{0u, 0u, 0u, 0u};  // rows past the end: row 0 of the head was read (in bounds), then zeroed
-            raw[qt][i] = v;
+            raw[i] = v;
         }
-    }
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(slot + 1024 * i + 16 * lane) = raw[qt][i];
-        lds_get_frags(slot, qf[qt], lane);  // same wave, same addresses: LDS keeps program order
+        for (int i = 0; i < 8; ++i) *(u32x4*)(slot + 1024 * i + 16 * lane) = raw[i];
     }
+    __syncthreads();
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) lds_get_frags(lds_base + (qt * 2 + 1) * kSlotBytes, qf[qt], lane);
+    wait_frags_read();
+    __syncthreads();
 }
 
 struct KeyStream {
@@ -311,7 +293,7 @@ template <int NQT>
 __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
     WaveItem w;
-    if (!wave_item(a, false, w)) return;
+    wave_item(a, false, w);
     const int lane = threadIdx.x & 63;
     const int half = lane >> 5;
     char* slots = &lds[__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))][0][0];
@@ -320,7 +302,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
     // With the soft tokens' own keys in the softmax, the sequence's first wave takes them as further tiles
     // after its prompt tiles (same row stride, n_q rows), masked causally per query row.
-    const int n_tail = (a.K_tail && w.wave == 0) ? (a.n_q + kKeyTile - 1) / kKeyTile : 0;
+    const int n_tail = (a.K_tail && w.wave == 0) ? (a.n_q + kKeyTile - 1) / kKeyTile : 0;  // wave 0 always has tiles
     const int n_all = w.n_tiles + n_tail;
     __amdgpu_buffer_rsrc_t tail_rsrc = ks.rsrc;
     if (n_tail) {
@@ -340,14 +322,13 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
                        a.n_q - t * kKeyTile, tl, lane);
         }
     };
-    // The first key tile goes to slot 0 at once; slot 1 first serves as the staging area that turns the
-    // query rows into operand order, then takes the second tile.  From then on two tiles are always in
-    // flight: a slot is refilled as soon as its fragments are in registers.
-    fetch(0);
+    // The first key tile goes to slot 0 at once; the second slots first serve as the staging area that turns
+    // the workgroup's query rows into operand order, then take the second tile.  From then on two tiles are
+    // always in flight: a slot is refilled as soon as its fragments are in registers.
+    if (n_all > 0) fetch(0);
     bf16x8 qf[NQT][8];
-    load_q_via_lds<NQT>(a, w, lane, slots + kSlotBytes, qf);
-    if (w.wave == 0) store_q_frags<NQT>(a, w, lane, qf);  // the sequence's first wave leaves the operand-order copy
-    wait_frags_read();
+    load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
+    if (n_all == 0) return;  // surplus wave of the sequence's last workgroup
     if (n_all > 1) fetch(1);
     const float c = a.c;
 
@@ -355,7 +336,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
 
-    // Every load older than the second tile's eight (first tile, query rows, operand-order copy) is covered
+    // Every load older than the second tile's eight (first tile, query rows) is covered
     // by the first wait of the sweep.  Only the sequence's last tile can be partial, and it is some wave's last.
     const int last_valid = w.L - (w.wave + (w.n_tiles - 1) * w.n_waves) * kKeyTile;
     const int n_full = last_valid >= kKeyTile ? w.n_tiles : w.n_tiles - 1;
@@ -508,15 +489,14 @@ __device__ __forceinline__ f32x16 score_chain(const bf16x8 (&q)[8], bf16x8 qaug,
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(qaug, ones, acc, 0, 0, 0);  // - beta_r / c
 }
 
-// FROM_LSE: the caller supplied the normalisers, no statistics pass has run: the wave gathers its query rows
-// itself (through its second LDS slot, like pass 1) and turns lse into the -beta/c terms on the fly
-// (beta = lse * log2 e, c = scale * log2 e, so -beta/c = -lse / scale); the launch also clears the words the
-// selection stage needs cleared.
+// FROM_LSE: the caller supplied the normalisers and no statistics pass has run: lse becomes the -beta/c terms
+// on the fly (beta = lse * log2 e, c = scale * log2 e, so -beta/c = -lse / scale), and the launch also clears
+// the words the selection stage needs cleared.
 template <int NQT, bool FROM_LSE>
 __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
     WaveItem w;
-    if (!wave_item(a, true, w)) return;  // reversed order: the keys pass 1 read last are fetched first
+    wave_item(a, true, w);  // reversed order: the keys pass 1 read last are fetched first
     const int lane = threadIdx.x & 63;
     const int half = lane >> 5;
     char* slots = &lds[__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))][0][0];
@@ -531,43 +511,34 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, (uint32_t)t * kKeyTile * ks.row_bytes, ks.row_bytes,
                    w.L - t * kKeyTile, tl, lane);
     };
-    fetch(0);
+    if (w.n_tiles > 0) fetch(0);
     bf16x8 qf[NQT][8];
     bf16x8 qaug[NQT];
-    if (FROM_LSE) {
-        if (a.zero) {
-            const uint64_t per = (a.zero_words + gridDim.x - 1) / gridDim.x;
-            const uint64_t z0 = per * blockIdx.x, z1 = z0 + per < a.zero_words ? z0 + per : a.zero_words;
-            for (uint64_t i = z0 + threadIdx.x; i < z1; i += blockDim.x) a.zero[i] = 0u;
-        }
-        load_q_via_lds<NQT>(a, w, lane, slots + kSlotBytes, qf);
-        wait_frags_read();
-        if (w.n_tiles > 1) fetch(1);
+    if (FROM_LSE && a.zero) {
+        const uint64_t per = (a.zero_words + gridDim.x - 1) / gridDim.x;
+        const uint64_t z0 = per * blockIdx.x, z1 = z0 + per < a.zero_words ? z0 + per : a.zero_words;
+        for (uint64_t i = z0 + threadIdx.x; i < z1; i += blockDim.x) a.zero[i] = 0u;
+    }
+    load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
+    if (w.n_tiles == 0) return;  // surplus wave of the sequence's last workgroup
+    if (w.n_tiles > 1) fetch(1);
 #pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-            const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
+    for (int qt = 0; qt < NQT; ++qt) {
+        const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
+        uint2 t;
+        if (FROM_LSE) {
             float x = -1.0e30f;  // padded rows get 2^(c*x) = 0
             if (row < a.rows) {
                 const int i = row / a.group, h = w.g * a.group + row % a.group;
                 x = -a.lse[((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q + i) * a.h_q + h] * a.inv_scale;
             }
-            const uint2 t = split_bf16x3(x);
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (half == 0) { v[0] = t.x; v[1] = t.y; }
-            qaug[qt] = as_bf16x8(v);
+            t = split_bf16x3(x);
+        } else {
+            t = a.aug[((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP + row];
         }
-    } else {
-        if (w.n_tiles > 1) fetch(1);
-        load_q_frags<NQT>(a, w, lane, qf);
-        const uint2* ap = a.aug + ((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP +
-                          a.row_tile0 * kRowTile + (lane & 31);
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-            const uint2 t = ap[qt * kRowTile];
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (half == 0) { v[0] = t.x; v[1] = t.y; }
-            qaug[qt] = as_bf16x8(v);
-        }
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (half == 0) { v[0] = t.x; v[1] = t.y; }
+        qaug[qt] = as_bf16x8(v);
     }
     u32x4 ones_bits = {0u, 0u, 0u, 0u};
     if (half == 0) { ones_bits[0] = 0x3F803F80u; ones_bits[1] = 0x00003F80u; }  // 1.0 at elements 0..2
@@ -662,7 +633,6 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.K_tail = (const uint16_t*)k_tail;
     a.stats = (float2*)(ws + p.off_stats);
     a.aug = (uint2*)(ws + p.off_aug);
-    a.qfrag = (u32x4*)(ws + p.off_qfrag);
     a.scores = scores;
     a.n_layers = p.n_layers; a.n_seq = p.n_seq; a.n_q = p.n_q; a.h_q = p.h_q; a.h_kv = p.h_kv;
     a.group = p.group; a.rows = p.rows; a.RP = p.row_tiles * kRowTile;
@@ -675,9 +645,9 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.zero = zero; a.zero_words = zero_words;
     a.tab = p.tab;
     a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
+    a.n_cgrp = p.tab.cu_cgrp[p.n_seq];
 
-    const int64_t waves = (int64_t)p.n_layers * p.n_chunks * p.h_kv;
-    dim3 grid((unsigned)((waves + kScoreWaves - 1) / kScoreWaves));
+    dim3 grid((unsigned)((int64_t)p.n_layers * a.n_cgrp * p.h_kv));
     hipError_t e;
     a.lse = lse;
     a.inv_scale = 1.0f / p.scale;
