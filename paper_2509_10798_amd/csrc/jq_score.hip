@@ -95,15 +95,14 @@ struct WaveItem {
 };
 
 __device__ __forceinline__ void wave_item(const ScoreArgs& a, bool reverse, WaveItem& w) {
-    const int64_t total = (int64_t)a.n_layers * a.n_cgrp * a.h_kv;  // == gridDim.x
-    int64_t b = blockIdx.x;
-    if (reverse) b = total - 1 - b;
+    uint32_t b = blockIdx.x;  // the grid is exactly n_layers * n_cgrp * h_kv workgroups (below 2^31: 32-bit arithmetic)
+    if (reverse) b = gridDim.x - 1 - b;
     // readfirstlane makes the wave index (and everything derived from it) a scalar for the compiler
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    w.g = (int)(b % a.h_kv);  // heads vary fastest: neighbouring workgroups read neighbouring 256-byte pieces of a token row
-    const int64_t rest = b / a.h_kv;
-    const int cg = (int)(rest % a.n_cgrp);
-    w.layer = (int)(rest / a.n_cgrp);
+    w.g = (int)(b % (uint32_t)a.h_kv);  // heads vary fastest: neighbouring workgroups read neighbouring 256-byte pieces of a token row
+    const uint32_t rest = b / (uint32_t)a.h_kv;
+    const int cg = (int)(rest % (uint32_t)a.n_cgrp);
+    w.layer = (int)(rest / (uint32_t)a.n_cgrp);
     w.seq = find_seq(a.tab.cu_cgrp, a.tab.n_seq, cg);
     w.L = a.tab.cu_seq[w.seq + 1] - a.tab.cu_seq[w.seq];
     w.n_waves = a.tab.cu_chunk[w.seq + 1] - a.tab.cu_chunk[w.seq];
