@@ -65,31 +65,42 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     p.TB = tb;
 
     // A sequence of L keys is worked on by ceil(L / chunk_keys) waves per head (which share its 32-key tiles
-    // round-robin).  Small calls aim at one wave per SIMD (256 CUs x 4): start-up -- gathering the head's
-    // query rows -- is paid per wave, and one wave with two tiles in flight keeps its SIMD busy.  The cap
-    // makes big calls run in several rounds.
-    int64_t chunk = ((int64_t)p.n_layers * p.h_kv * p.T + 1023) / 1024;
-    chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
-    if (chunk < 64) chunk = 64;
-    if (chunk > 1024) chunk = 1024;
-    if (const char* env = std::getenv("JQ_CHUNK_KEYS")) {  // ablation knob
-        const long v = std::atol(env);
-        if (v >= kKeyTile && v <= 8192 && v % kKeyTile == 0) chunk = v;
-    }
-    p.chunk_keys = (int32_t)chunk;
-    int64_t nc = 0, ng = 0;
-    p.tab.cu_chunk[0] = 0;
-    p.tab.cu_cgrp[0] = 0;
-    for (int s = 0; s < sh->n_seq; ++s) {
-        const int64_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
-        const int64_t waves = (L + chunk - 1) / chunk;
-        nc += waves;
-        ng += (waves + kScoreWaves - 1) / kScoreWaves;
-        p.tab.cu_chunk[s + 1] = (int32_t)nc;
-        p.tab.cu_cgrp[s + 1] = (int32_t)ng;
-    }
-    p.n_chunks = (int32_t)nc;
-    if ((int64_t)p.n_layers * ng * p.h_kv >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
+    // round-robin).  Small calls aim at one wave per SIMD (256 CUs x 4) in the pass that reads K cold (the
+    // first pass, or the only one when the normalisers are supplied): one wave with two tiles in flight keeps
+    // its SIMD busy and the window of K in flight stays small.  The second pass finds part of K in the
+    // Infinity Cache and has more arithmetic per tile; it does better with two waves per SIMD.  The cap makes
+    // big calls run in several rounds.
+    const int64_t keys = (int64_t)p.n_layers * p.h_kv * p.T;
+    auto plan_waves = [&](int64_t target_waves, const char* knob, int32_t* cu_chunk, int32_t* cu_cgrp, int32_t* chunk_keys,
+                          int32_t* n_chunks) {
+        int64_t chunk = (keys + target_waves - 1) / target_waves;
+        chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
+        if (chunk < 64) chunk = 64;
+        if (chunk > 1024) chunk = 1024;
+        if (const char* env = std::getenv(knob)) {  // ablation knob
+            const long v = std::atol(env);
+            if (v >= kKeyTile && v <= 8192 && v % kKeyTile == 0) chunk = v;
+        }
+        int64_t nc = 0, ng = 0;
+        cu_chunk[0] = 0;
+        cu_cgrp[0] = 0;
+        for (int s = 0; s < sh->n_seq; ++s) {
+            const int64_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
+            const int64_t waves = (L + chunk - 1) / chunk;
+            nc += waves;
+            ng += (waves + kScoreWaves - 1) / kScoreWaves;
+            cu_chunk[s + 1] = (int32_t)nc;
+            cu_cgrp[s + 1] = (int32_t)ng;
+        }
+        *chunk_keys = (int32_t)chunk;
+        *n_chunks = (int32_t)nc;
+        return ng;
+    };
+    const int64_t ng = plan_waves(1024, "JQ_CHUNK_KEYS", p.tab.cu_chunk, p.tab.cu_cgrp, &p.chunk_keys, &p.n_chunks);
+    const int64_t ng2 = plan_waves(2048, std::getenv("JQ_CHUNK_KEYS_2") ? "JQ_CHUNK_KEYS_2" : "JQ_CHUNK_KEYS", p.cu_chunk2,
+                                   p.cu_cgrp2, &p.chunk_keys2, &p.n_chunks2);
+    const int64_t nc = p.n_chunks;
+    if ((int64_t)p.n_layers * (ng > ng2 ? ng : ng2) * p.h_kv >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
     if ((int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
 
     const size_t RP = (size_t)p.row_tiles * kRowTile;

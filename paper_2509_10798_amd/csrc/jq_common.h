@@ -36,6 +36,9 @@ struct Plan {
     int32_t row_groups;   // ceil(row_tiles / 4): passes of the score kernels over K
     int32_t chunk_keys;   // a sequence of L keys gets ceil(L / chunk_keys) score waves per head (multiple of 32)
     int32_t n_chunks;     // such waves per layer and head, over all sequences (tab.cu_chunk counts them)
+    // the same for the second K pass when a first one has run (tab holds the first pass's tables)
+    int32_t chunk_keys2, n_chunks2;
+    int32_t cu_chunk2[JQ_MAX_SEQ + 1], cu_cgrp2[JQ_MAX_SEQ + 1];
     float scale;          // logit scale actually used
     int64_t T, TB;
     SeqTab tab;

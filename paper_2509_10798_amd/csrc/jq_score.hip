@@ -660,6 +660,12 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a);
         if (e != hipSuccess) return e;
     }
+    if (!lse) {  // the second pass cuts the sequences into its own number of waves
+        a.chunk_keys = p.chunk_keys2; a.n_chunks = p.n_chunks2;
+        for (int s = 0; s <= p.n_seq; ++s) { a.tab.cu_chunk[s] = p.cu_chunk2[s]; a.tab.cu_cgrp[s] = p.cu_cgrp2[s]; }
+        a.n_cgrp = p.cu_cgrp2[p.n_seq];
+        grid = dim3((unsigned)((int64_t)p.n_layers * a.n_cgrp * p.h_kv));
+    }
     for (int rg = 0; rg < p.row_groups; ++rg) {
         a.row_tile0 = rg * kMaxRowTiles;
         a.accumulate = rg > 0;
