@@ -99,13 +99,12 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     const int64_t ng = plan_waves(1024, "JQ_CHUNK_KEYS", p.tab.cu_chunk, p.tab.cu_cgrp, &p.chunk_keys, &p.n_chunks);
     const int64_t ng2 = plan_waves(2048, std::getenv("JQ_CHUNK_KEYS_2") ? "JQ_CHUNK_KEYS_2" : "JQ_CHUNK_KEYS", p.cu_chunk2,
                                    p.cu_cgrp2, &p.chunk_keys2, &p.n_chunks2);
-    const int64_t nc = p.n_chunks;
     if ((int64_t)p.n_layers * (ng > ng2 ? ng : ng2) * p.h_kv >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
     if ((int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
 
     const size_t RP = (size_t)p.row_tiles * kRowTile;
     size_t off = 0;
-    p.off_stats = off;  off += align_up((size_t)p.n_layers * nc * p.h_kv * RP * sizeof(float2));
+    p.off_stats = off;  off += align_up((size_t)p.n_layers * ng * p.h_kv * RP * sizeof(float2));  // one per pass-1 workgroup
     p.off_aug = off;    off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * RP * sizeof(uint2));
     p.off_hist = off;   off += align_up((size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride * sizeof(uint32_t));
     p.off_scores = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));

@@ -64,7 +64,7 @@ __device__ inline uint32_t sortable_key(float x) {
 }
 
 // Kernels whose start/stop timestamps jq_evict_traced reports, in launch order.
-enum TraceKernel { kTrStats = 0, kTrCombine, kTrScore, kTrPool, kTrScatter, kTrFinalize, kTraceKernels };
+enum TraceKernel { kTrStats = 0, kTrScore, kTrPool, kTrScatter, kTrFinalize, kTraceKernels };
 
 // Launch through hipLaunchKernel so that the status belongs to this launch alone (the sticky
 // "last error" of the runtime may hold an unrelated, earlier code from the host application).

@@ -40,11 +40,15 @@ struct ScoreArgs {
     const uint16_t* K_tail;  // [n_layers][n_seq][n_q][h_kv][d] keys of the soft tokens themselves, or null
     const float* lse;        // [n_layers][n_seq][n_q][h_q] caller-supplied natural-log normalisers, or null
     float inv_scale;         // 1 / scale
-    float2* stats;    // [n_layers][n_chunks][h_kv][RP]: (m, Z) per score wave (n_chunks = waves per layer and head)
+    float2* stats;    // [n_layers][n_cgrp of pass 1][h_kv][RP]: (m, Z) per pass-1 workgroup
     uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
     float* scores;    // [n_layers][h_kv][T]
     int32_t n_layers, n_seq, n_q, h_q, h_kv, group, rows, RP, chunk_keys, n_chunks;
     int32_t n_cgrp;       // workgroups per layer and head: sum over sequences of ceil(waves / 4)
+    // pass 2 only: where pass 1 left its per-workgroup statistics (its own n_cgrp and per-sequence offsets),
+    // and whether this launch merges them itself (otherwise jq_combine_kernel has filled `aug`)
+    int32_t n_part, fuse_combine;
+    int32_t cu_part[JQ_MAX_SEQ + 1];
     int32_t group_shift;  // log2(group) when group is a power of two, else -1
     int32_t row_tile0;   // first query-row tile of this launch
     int32_t accumulate;  // pass 2: add to `scores` instead of overwriting
@@ -327,13 +331,12 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     if (n_all > 0) fetch(0);
     bf16x8 qf[NQT][8];
     load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
-    if (n_all == 0) return;  // surplus wave of the sequence's last workgroup
-    if (n_all > 1) fetch(1);
     const float c = a.c;
-
     float m[NQT], z[NQT];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
+    if (n_all > 0) {  // not a surplus wave of the sequence's last workgroup
+    if (n_all > 1) fetch(1);
 
     // Every load older than the second tile's eight (first tile, query rows) is covered
     // by the first wait of the sweep.  Only the sequence's last tile can be partial, and it is some wave's last.
@@ -400,21 +403,34 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         sweep(std::false_type{});
     }
 
-    // lanes l and l+32 hold the same query rows over complementary keys: merge, then one partial per wave
-    float2* out = a.stats + (((int64_t)w.layer * a.n_chunks + w.chunk_global) * a.h_kv + w.g) * a.RP +
-                  a.row_tile0 * kRowTile + (lane & 31);
+    }  // n_all > 0
+
+    // Lanes l and l+32 hold the same query rows over complementary keys: merge them; then the four waves of
+    // the workgroup merge their rows through LDS (every slot is idle by now), in wave order, into the one
+    // partial the workgroup leaves per query row.
+    float2* mine = (float2*)slots;  // [NQT * 32] of this wave
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
         const float mo = __shfl_xor(m[qt], 32), zo = __shfl_xor(z[qt], 32);
         const float mm = fmaxf(m[qt], mo);
         const float zz = z[qt] * __builtin_amdgcn_exp2f(m[qt] - mm) + zo * __builtin_amdgcn_exp2f(mo - mm);
-        if (half == 0) out[qt * kRowTile] = make_float2(mm, zz);
+        if (half == 0) mine[qt * kRowTile + lane] = make_float2(mm, zz);
+    }
+    __syncthreads();
+    if (threadIdx.x < NQT * kRowTile) {
+        float M = -1.0e30f, Z = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kScoreWaves; ++wv) {
+            const float2 mz = ((const float2*)&lds[wv][0][0])[threadIdx.x];
+            const float mm = fmaxf(M, mz.x);
+            Z = Z * __builtin_amdgcn_exp2f(M - mm) + mz.y * __builtin_amdgcn_exp2f(mz.x - mm);
+            M = mm;
+        }
+        const int cg = a.tab.cu_cgrp[w.seq] + w.wave / kScoreWaves;  // this workgroup among the layer's, per head
+        a.stats[(((int64_t)w.layer * a.n_cgrp + cg) * a.h_kv + w.g) * a.RP + a.row_tile0 * kRowTile + threadIdx.x] = make_float2(M, Z);
     }
 }
 
-// ------------------------------------------------------------------------------------------------
-// combine: per (layer, sequence, head, row) merge the partials into -beta/c as three bf16 terms
-// ------------------------------------------------------------------------------------------------
 // -beta/c as the three truncated bf16 terms that enter the second pass through its extra MFMA step.
 __device__ __forceinline__ uint2 split_bf16x3(float x) {
     const uint32_t hi = __float_as_uint(x) & 0xFFFF0000u;
@@ -445,8 +461,8 @@ __global__ __launch_bounds__(kRowTile * kCombineLanes) void jq_combine_kernel(Sc
         for (uint64_t i = z0 + threadIdx.x; i < z1; i += blockDim.x) a.zero[i] = 0u;
     }
 
-    const int c0 = a.tab.cu_chunk[s], c1 = a.tab.cu_chunk[s + 1];
-    const float2* p = a.stats + (((int64_t)layer * a.n_chunks + c0) * a.h_kv + g) * a.RP + row;
+    const int c0 = a.tab.cu_cgrp[s], c1 = a.tab.cu_cgrp[s + 1];
+    const float2* p = a.stats + (((int64_t)layer * a.n_cgrp + c0) * a.h_kv + g) * a.RP + row;
     const int64_t step = (int64_t)a.h_kv * a.RP;
     float M = -1.0e30f, Z = 0.f;
     for (int k0 = kl; k0 < c1 - c0; k0 += 8 * kCombineLanes) {  // 8 independent loads in flight per thread
@@ -513,31 +529,74 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     if (w.n_tiles > 0) fetch(0);
     bf16x8 qf[NQT][8];
     bf16x8 qaug[NQT];
-    if (FROM_LSE && a.zero) {
+    if (a.zero) {
         const uint64_t per = (a.zero_words + gridDim.x - 1) / gridDim.x;
         const uint64_t z0 = per * blockIdx.x, z1 = z0 + per < a.zero_words ? z0 + per : a.zero_words;
         for (uint64_t i = z0 + threadIdx.x; i < z1; i += blockDim.x) a.zero[i] = 0u;
     }
-    load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
-    if (w.n_tiles == 0) return;  // surplus wave of the sequence's last workgroup
-    if (w.n_tiles > 1) fetch(1);
+    // Pass 1 left one (m, Z) partial per workgroup; unless a combine launch has merged them already, this
+    // workgroup merges the partials of its head's rows itself: thread t takes row t / 2 and every second
+    // partial (loads issued here, consumed after the query rows are in), pairs meet by shuffle, and the rows'
+    // -beta/c terms pass through LDS.
+    const bool fused = !FROM_LSE && a.fuse_combine;  // uniform
+    float cM = -1.0e30f, cZ = 0.f;
+    if (fused && (threadIdx.x >> 1) < NQT * kRowTile) {
+        const int crow = a.row_tile0 * kRowTile + (int)(threadIdx.x >> 1);
+        const int c0 = a.cu_part[w.seq], n_p = a.cu_part[w.seq + 1] - c0;
+        const float2* pp = a.stats + (((int64_t)w.layer * a.n_part + c0) * a.h_kv + w.g) * a.RP + crow;
+        const int64_t pstep = (int64_t)a.h_kv * a.RP;
+        for (int k0 = (int)(threadIdx.x & 1); k0 < n_p; k0 += 16) {  // 8 independent loads in flight
+            float2 mz[8];
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-        const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
-        uint2 t;
-        if (FROM_LSE) {
-            float x = -1.0e30f;  // padded rows get 2^(c*x) = 0
-            if (row < a.rows) {
-                const int i = row / a.group, h = w.g * a.group + row % a.group;
-                x = -a.lse[((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q + i) * a.h_q + h] * a.inv_scale;
+            for (int u = 0; u < 8; ++u) mz[u] = k0 + 2 * u < n_p ? pp[(k0 + 2 * u) * pstep] : make_float2(-1.0e30f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float mm = fmaxf(cM, mz[u].x);
+                cZ = cZ * __builtin_amdgcn_exp2f(cM - mm) + mz[u].y * __builtin_amdgcn_exp2f(mz[u].x - mm);
+                cM = mm;
             }
-            t = split_bf16x3(x);
-        } else {
-            t = a.aug[((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP + row];
         }
+    }
+    load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
+    if (fused) {
+        const float oM = __shfl_xor(cM, 1), oZ = __shfl_xor(cZ, 1);  // the odd neighbour's half; even threads finish the row
+        const float mm = fmaxf(cM, oM);
+        const float zz = cZ * __builtin_amdgcn_exp2f(cM - mm) + oZ * __builtin_amdgcn_exp2f(oM - mm);
+        const int crow = a.row_tile0 * kRowTile + (int)(threadIdx.x >> 1);
+        uint2* aug_s = (uint2*)&lds[0][1][0];  // the query rows have left this slot (second barrier of load_q_shared)
+        if (!(threadIdx.x & 1) && (threadIdx.x >> 1) < NQT * kRowTile)
+            aug_s[threadIdx.x >> 1] = split_bf16x3(crow < a.rows ? -(mm + __log2f(zz)) / a.c : -1.0e30f);
+        __syncthreads();
+    }
+    auto set_aug = [&](int qt, uint2 t) {  // the three bf16 terms sit in k-elements 0..2 of the extra MFMA step (lane half 0)
         u32x4 v = {0u, 0u, 0u, 0u};
         if (half == 0) { v[0] = t.x; v[1] = t.y; }
         qaug[qt] = as_bf16x8(v);
+    };
+    if (fused) {
+        const uint2* aug_s = (const uint2*)&lds[0][1][0];
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) set_aug(qt, aug_s[qt * kRowTile + (lane & 31)]);
+        wait_frags_read();
+        __syncthreads();  // the slot is refilled with a key tile next
+    }
+    if (w.n_tiles == 0) return;  // surplus wave of the sequence's last workgroup
+    if (w.n_tiles > 1) fetch(1);
+    if (!fused) {
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
+            if (FROM_LSE) {
+                float x = -1.0e30f;  // padded rows get 2^(c*x) = 0
+                if (row < a.rows) {
+                    const int i = row / a.group, h = w.g * a.group + row % a.group;
+                    x = -a.lse[((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q + i) * a.h_q + h] * a.inv_scale;
+                }
+                set_aug(qt, split_bf16x3(x));
+            } else {
+                set_aug(qt, a.aug[((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP + row]);
+            }
+        }
     }
     u32x4 ones_bits = {0u, 0u, 0u, 0u};
     if (half == 0) { ones_bits[0] = 0x3F803F80u; ones_bits[1] = 0x00003F80u; }  // 1.0 at elements 0..2
@@ -650,17 +709,29 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     hipError_t e;
     a.lse = lse;
     a.inv_scale = 1.0f / p.scale;
+    a.n_part = 0; a.fuse_combine = 0;
+    for (int s = 0; s <= p.n_seq; ++s) a.cu_part[s] = 0;
     if (!lse) {
         for (int rg = 0; rg < p.row_groups; ++rg) {
             a.row_tile0 = rg * kMaxRowTiles;
             const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
             if ((e = launch_stats_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
         }
-        const int64_t n_row_tiles = (int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles;
-        e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, marks, kTrCombine, a);
-        if (e != hipSuccess) return e;
-    }
-    if (!lse) {  // the second pass cuts the sequences into its own number of waves
+        // Pass 1 leaves one partial per workgroup.  With few of them per sequence every pass-2 workgroup merges
+        // its head's partials itself; a very long sequence has hundreds, and then one small launch merges them
+        // once (and clears the selection's words on the way).
+        int max_parts = 0;
+        for (int s = 0; s < p.n_seq; ++s) max_parts = max(max_parts, p.tab.cu_cgrp[s + 1] - p.tab.cu_cgrp[s]);
+        a.fuse_combine = max_parts <= 64;
+        if (!a.fuse_combine) {
+            const int64_t n_row_tiles = (int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles;
+            e = launch_kernel(jq_combine_kernel, dim3((unsigned)n_row_tiles), dim3(kRowTile * kCombineLanes), 0, st, nullptr, -1, a);
+            if (e != hipSuccess) return e;
+            a.zero = nullptr;  // done by the combine launch
+        }
+        // the second pass cuts the sequences into its own number of waves
+        a.n_part = a.n_cgrp;
+        for (int s = 0; s <= p.n_seq; ++s) a.cu_part[s] = p.tab.cu_cgrp[s];
         a.chunk_keys = p.chunk_keys2; a.n_chunks = p.n_chunks2;
         for (int s = 0; s <= p.n_seq; ++s) { a.tab.cu_chunk[s] = p.cu_chunk2[s]; a.tab.cu_cgrp[s] = p.cu_cgrp2[s]; }
         a.n_cgrp = p.cu_cgrp2[p.n_seq];

@@ -88,7 +88,7 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_score_tail(ctypes.byref(cs), Q, K, ws + 512, Ko, ws, need, None) == -6             # keys inside the workspace
     assert L.jq_evict_tail(ctypes.byref(cs), Q, K, V, None, Ko, Vo, None, None, ws, need, None) == -1
     assert L.jq_evict_tail(ctypes.byref(cs), Q, K, V, Vo, Ko, Vo, None, None, ws, need, None) == -6   # keys inside V_out
-    assert L.jq_evict_traced(ctypes.byref(cs), Q, K, V, Ko, Vo, None, None, ws, need, None, None, 12) == -1
+    assert L.jq_evict_traced(ctypes.byref(cs), Q, K, V, Ko, Vo, None, None, ws, need, None, None, 10) == -1
     assert L.jq_hit_rate(ctypes.byref(cs), Ko, None, None, Vo, None) == -1
     assert L.jq_hit_rate(ctypes.byref(cs), Ko, Vo, None, Ko + 8, None) == -6                       # rate inside idx_cur
     too_many = (ctypes.c_int32 * sh.n_seq)(*([10 ** 9] * sh.n_seq))

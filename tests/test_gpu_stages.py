@@ -96,6 +96,14 @@ def test_score_several_chunks_per_sequence(monkeypatch):
     run_score_case(1, [1111, 95], 16, 8, 2, seed=13)
 
 
+def test_score_with_hundreds_of_partial_statistics(monkeypatch):
+    # a sequence cut into more than 256 waves leaves more partials than the second pass merges by itself: the
+    # separate merge launch runs (here forced by 64-key chunks)
+    print("score with a merge launch", flush=True)
+    monkeypatch.setenv("JQ_CHUNK_KEYS", "64")
+    run_score_case(1, [20000, 300], 16, 8, 2, seed=14)
+
+
 def test_score_is_deterministic():
     torch = torch_()
     w = make_workload(1)
