@@ -299,6 +299,35 @@ int jqo_select_topk(long L, long B, const double* pooled, int32_t* idx) {
 }
 
 /*
+ * Top-B retention with positions that are kept no matter what they score: the
+ * baselines of Section 5.1 retain the beginning of the input and / or the local
+ * window (StreamingLLM by construction, the window-query methods because the
+ * window's own tokens stay).  Reading: the first keep_first and the last
+ * keep_last positions are in the kept set; they count towards B; the other
+ * B - keep_first - keep_last places go to the highest-scoring remaining
+ * positions (equal scores: lower position first); output ascending.
+ * Written as that definition: forced positions are copied, the rest is sorted.
+ */
+int jqo_select_topk_keep(long L, long B, long keep_first, long keep_last, const double* pooled, int32_t* idx) {
+    if (L < 1 || B < 1 || B > L || L > 2147483647L || !pooled || !idx) return -1;
+    if (keep_first < 0 || keep_last < 0 || keep_first + keep_last > B) return -1;
+    long n = 0;
+    for (long j = 0; j < keep_first; ++j) idx[n++] = (int32_t)j;
+    for (long j = L - keep_last; j < L; ++j) idx[n++] = (int32_t)j;
+    const long lo = keep_first, hi = L - keep_last;  /* the positions that compete: [lo, hi) */
+    if (hi > lo && n < B) {
+        jqo_item* it = (jqo_item*)malloc(sizeof(jqo_item) * (size_t)(hi - lo));
+        if (!it) return -1;
+        for (long j = lo; j < hi; ++j) { it[j - lo].v = pooled[j]; it[j - lo].i = (int32_t)j; }
+        qsort(it, (size_t)(hi - lo), sizeof(jqo_item), jqo_item_cmp);
+        for (long b = 0; n < B; ++b) idx[n++] = it[b].i;
+        free(it);
+    }
+    qsort(idx, (size_t)B, sizeof(int32_t), jqo_i32_cmp);
+    return 0;
+}
+
+/*
  * Pruned cache (Section 4.3: decoding continues on the pruned KV cache):
  *   K_out[b,g,:] = K[idx[g,b], g, :],   V_out likewise, as 16-bit patterns.
  * K,V [L, h_kv, d]; idx [h_kv, B]; K_out,V_out [B, h_kv, d].

@@ -42,6 +42,8 @@ def _load():
         lib.jqo_map_mse.restype = ctypes.c_int
         lib.jqo_pool.argtypes = [ctypes.c_long, ctypes.c_int, f64p, f64p]
         lib.jqo_select_topk.argtypes = [ctypes.c_long, ctypes.c_long, f64p, i32p]
+        lib.jqo_select_topk_keep.argtypes = [ctypes.c_long] * 4 + [f64p, i32p]
+        lib.jqo_select_topk_keep.restype = ctypes.c_int
         lib.jqo_compact.argtypes = [ctypes.c_long, ctypes.c_int, ctypes.c_int, ctypes.c_long, u16p, u16p, i32p, u16p, u16p]
         for f in (lib.jqo_score, lib.jqo_score_lse, lib.jqo_score_tail, lib.jqo_pool, lib.jqo_select_topk, lib.jqo_compact):
             f.restype = ctypes.c_int
@@ -109,13 +111,20 @@ def pool(scores: np.ndarray, pool_k: int) -> np.ndarray:
     return out.reshape(s.shape)
 
 
-def select_topk(pooled: np.ndarray, B: int) -> np.ndarray:
-    """pooled [h_kv, L] (or [L]) float64 -> idx [h_kv, B] (or [B]) int32, ascending."""
+def select_topk(pooled: np.ndarray, B: int, keep_first: int = 0, keep_last: int = 0) -> np.ndarray:
+    """pooled [h_kv, L] (or [L]) float64 -> idx [h_kv, B] (or [B]) int32, ascending.
+
+    With keep_first / keep_last the first / last positions are kept regardless of their scores and
+    count towards B."""
     p = np.ascontiguousarray(pooled, dtype=np.float64)
     flat = p.reshape(-1, p.shape[-1])
     out = np.empty((flat.shape[0], int(B)), dtype=np.int32)
     for g in range(flat.shape[0]):
-        _check(_load().jqo_select_topk(flat.shape[1], int(B), flat[g], out[g]), "select_topk")
+        if keep_first or keep_last:
+            _check(_load().jqo_select_topk_keep(flat.shape[1], int(B), int(keep_first), int(keep_last), flat[g], out[g]),
+                   "select_topk_keep")
+        else:
+            _check(_load().jqo_select_topk(flat.shape[1], int(B), flat[g], out[g]), "select_topk")
     return out.reshape(p.shape[:-1] + (int(B),))
 
 
@@ -132,7 +141,8 @@ def compact(K: np.ndarray, V: np.ndarray, idx: np.ndarray):
     return Ko, Vo
 
 
-def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None, K_tail=None):
+def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None, K_tail=None, keep_first: int = 0,
+          keep_last: int = 0):
     """One (layer, sequence): score -> pool -> top-B -> gather.  Returns a dict.
 
     With `lse` the scores are the slice-of-a-wider-softmax variant (score_lse), with `K_tail` the
@@ -144,12 +154,12 @@ def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None, K_tail=Non
     else:
         s = score(Q, K, scale)
     p = pool(s, pool_k)
-    idx = select_topk(p, B)
+    idx = select_topk(p, B, keep_first, keep_last)
     Ko, Vo = compact(K, V, idx)
     return {"scores": s, "pooled": p, "idx": idx, "K_out": Ko, "V_out": Vo}
 
 
-def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0):
+def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0, keep_first: int = 0, keep_last: int = 0):
     """Layers x ragged sequences, one problem at a time.
 
     Q [nl,n_seq,n_q,h_q,d], K/V [nl,T,h_kv,d] uint16.  Returns pooled [nl,h_kv,T],
@@ -164,7 +174,8 @@ def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0):
     Ko = np.empty((nl, TB, h_kv, d), dtype=np.uint16); Vo = np.empty_like(Ko)
     for l in range(nl):
         for s in range(len(cu) - 1):
-            r = evict(Q[l, s], K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], int(budgets[s]), pool_k, scale)
+            r = evict(Q[l, s], K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], int(budgets[s]), pool_k, scale,
+                      keep_first=keep_first, keep_last=keep_last)
             scores[l, :, cu[s]:cu[s + 1]] = r["scores"]
             pooled[l, :, cu[s]:cu[s + 1]] = r["pooled"]
             idx[l, :, cb[s]:cb[s + 1]] = r["idx"]

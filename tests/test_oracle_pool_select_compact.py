@@ -96,6 +96,56 @@ def test_select_rejects_bad_budget():
             oracle.select_topk(np.ones(5), B)
 
 
+# ---------------------------------------------------------------- top-B with forced positions
+def test_select_keep_exhaustive():
+    """Brute force: among all B-subsets that contain the forced positions, the kept set has the largest
+    score mass over the free positions (random scores: no ties)."""
+    rng = np.random.default_rng(21)
+    for L in (6, 9, 11):
+        x = rng.random(L)
+        for kf, kl in ((0, 2), (1, 0), (2, 3), (1, 1)):
+            forced = set(range(kf)) | set(range(L - kl, L))
+            for B in range(kf + kl, L + 1):
+                if B < 1:
+                    continue
+                idx = oracle.select_topk(x, B, kf, kl)
+                cands = [c for c in itertools.combinations(range(L), B) if forced <= set(c)]
+                best = max(cands, key=lambda c: sum(x[j] for j in c if j not in forced))
+                assert list(idx) == list(best)
+
+
+def test_select_keep_hand_cases():
+    x = np.array([0.0, 0.9, 0.1, 0.8, 0.2, 0.7, 0.0, 0.0])
+    np.testing.assert_array_equal(oracle.select_topk(x, 3, 1, 1), [0, 1, 7])       # sink + newest + best of the rest
+    np.testing.assert_array_equal(oracle.select_topk(x, 4, 0, 2), [1, 3, 6, 7])    # window of two zeros is still kept
+    np.testing.assert_array_equal(oracle.select_topk(x, 2, 1, 1), [0, 7])          # nothing left to compete for
+    np.testing.assert_array_equal(oracle.select_topk(x, 8, 3, 3), np.arange(8))    # B = L
+    # forced positions do not take part in the tie rule: of the free 0.5s the lowest positions win
+    t = np.full(8, 0.5)
+    np.testing.assert_array_equal(oracle.select_topk(t, 5, 1, 2), [0, 1, 2, 6, 7])
+    # a forced position that would have been chosen anyway changes nothing
+    np.testing.assert_array_equal(oracle.select_topk(x, 3, 0, 0), oracle.select_topk(x[:6], 3))
+    np.testing.assert_array_equal(oracle.select_topk(x, 3, 2, 0), [0, 1, 3])
+
+
+def test_select_keep_reduces_to_plain_selection_on_the_free_span():
+    rng = np.random.default_rng(22)
+    x = np.round(rng.random((3, 400)), 2)                                          # exact ties
+    kf, kl, B = 4, 32, 100
+    got = oracle.select_topk(x, B, kf, kl)
+    inner = oracle.select_topk(np.ascontiguousarray(x[:, kf:400 - kl]), B - kf - kl) + kf
+    for g in range(3):
+        want = np.concatenate([np.arange(kf), inner[g], np.arange(400 - kl, 400)])
+        np.testing.assert_array_equal(got[g], want)
+
+
+def test_select_keep_rejects_more_forced_than_budget():
+    with pytest.raises(ValueError):
+        oracle.select_topk(np.ones(10), 4, 3, 2)
+    with pytest.raises(ValueError):
+        oracle.select_topk(np.ones(10), 4, -1, 2)
+
+
 # ---------------------------------------------------------------- gather
 def test_compact_is_a_gather():
     rng = np.random.default_rng(4)
