@@ -64,7 +64,7 @@ typedef enum jq_status {
     JQ_OK = 0,
     JQ_ERR_NULL = -1,        /* a required pointer is NULL                               */
     JQ_ERR_SHAPE = -2,       /* a dimension, pool_k, scale or cu_seqlens is malformed    */
-    JQ_ERR_BUDGET = -3,      /* some budget is outside 1..L_s                            */
+    JQ_ERR_BUDGET = -3,      /* some budget is outside 1..L_s, or below keep_first+keep_last */
     JQ_ERR_UNSUPPORTED = -4, /* valid but not implemented (d != 128, too many sequences, */
                              /* a sequence of 4 GiB or more of keys, a misaligned tensor) */
     JQ_ERR_WORKSPACE = -5,   /* workspace missing, misaligned (16 B) or too small        */
@@ -89,6 +89,11 @@ typedef struct jq_shape {
                                /* keys (L_s * h_kv * d * 2 bytes) must stay below 4 GiB           */
     const int32_t* budgets;    /* HOST [n_seq]; 1 <= budgets[s] <= L_s.  May be NULL for      */
                                /* jq_score and jq_pool, which do not use it.                  */
+    int32_t keep_first;        /* >= 0: the first keep_first and the last keep_last positions  */
+    int32_t keep_last;         /* of every sequence are kept whatever they score (the sinks    */
+                               /* and the local window of the Section 5.1 baselines); they     */
+                               /* count towards the budget: keep_first + keep_last <=          */
+                               /* budgets[s].  Read by jq_select_topk and jq_evict* only.      */
 } jq_shape;
 
 /* Bytes of device workspace that jq_score, jq_select_topk and jq_evict need for
@@ -136,7 +141,9 @@ int jq_pool(const jq_shape* shape, const float* scores, float* pooled, void* str
 /* For every (layer, sequence, KV head): the budgets[s] positions with the largest
  * pooled value; equal values are resolved towards the lower position; positions
  * are written in ascending order.  Exact for any finite fp32 input (-0 == +0).
- * Uses `ws` as scratch. */
+ * The first keep_first and last keep_last positions of a sequence are always among
+ * them (their values are ignored); the remaining places go to the largest values
+ * of the other positions.  Uses `ws` as scratch. */
 int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx,
                    void* ws, size_t ws_bytes, void* stream);
 

@@ -37,7 +37,8 @@ class _CShape(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("n_seq", ctypes.c_int32), ("n_q", ctypes.c_int32),
                 ("h_q", ctypes.c_int32), ("h_kv", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("pool_k", ctypes.c_int32), ("scale", ctypes.c_float),
-                ("cu_seqlens", ctypes.POINTER(ctypes.c_int32)), ("budgets", ctypes.POINTER(ctypes.c_int32))]
+                ("cu_seqlens", ctypes.POINTER(ctypes.c_int32)), ("budgets", ctypes.POINTER(ctypes.c_int32)),
+                ("keep_first", ctypes.c_int32), ("keep_last", ctypes.c_int32)]
 
 
 def lib() -> ctypes.CDLL:
@@ -91,6 +92,8 @@ class Shape:
     pool_k: int = 7
     budgets: Optional[Sequence[int]] = None
     scale: float = 0.0
+    keep_first: int = 0   # positions at the start / end of every sequence that the selection always keeps
+    keep_last: int = 0
     _keep: list = field(default_factory=list, repr=False)
 
     @property
@@ -107,7 +110,7 @@ class Shape:
 
     def c_struct(self) -> _CShape:
         key = (self.n_layers, tuple(self.seq_lens), self.n_q, self.h_q, self.h_kv, self.d, self.pool_k,
-               None if self.budgets is None else tuple(self.budgets), float(self.scale))
+               None if self.budgets is None else tuple(self.budgets), float(self.scale), self.keep_first, self.keep_last)
         if self._keep and self._keep[0] == key:  # marshalled once per distinct description
             return self._keep[3]
         cu = np.concatenate([[0], np.cumsum(np.asarray(self.seq_lens, dtype=np.int64))]).astype(np.int32)
@@ -115,7 +118,8 @@ class Shape:
         i32p = ctypes.POINTER(ctypes.c_int32)
         cs = _CShape(self.n_layers, self.n_seq, self.n_q, self.h_q, self.h_kv, self.d, self.pool_k,
                      float(self.scale), cu.ctypes.data_as(i32p),
-                     bud.ctypes.data_as(i32p) if bud is not None else ctypes.cast(None, i32p))
+                     bud.ctypes.data_as(i32p) if bud is not None else ctypes.cast(None, i32p),
+                     int(self.keep_first), int(self.keep_last))
         self._keep = [key, cu, bud, cs]  # the host arrays must outlive the struct
         return cs
 

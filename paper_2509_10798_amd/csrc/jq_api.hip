@@ -27,6 +27,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     if (sh->h_q % sh->h_kv != 0) return JQ_ERR_SHAPE;
     if (sh->pool_k < 1 || sh->pool_k % 2 == 0) return JQ_ERR_SHAPE;
     if (!std::isfinite(sh->scale) || sh->scale < 0.0f) return JQ_ERR_SHAPE;
+    if (sh->keep_first < 0 || sh->keep_last < 0) return JQ_ERR_SHAPE;
     if (sh->n_seq > JQ_MAX_SEQ) return JQ_ERR_UNSUPPORTED;
     if (sh->d != kHeadDim) return JQ_ERR_UNSUPPORTED;
     if (sh->n_layers > 65535 || sh->h_kv > 256) return JQ_ERR_UNSUPPORTED;  // grid dimensions
@@ -37,6 +38,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     Plan p{};
     p.n_layers = sh->n_layers; p.n_seq = sh->n_seq; p.n_q = sh->n_q; p.h_q = sh->h_q; p.h_kv = sh->h_kv;
     p.d = sh->d; p.group = sh->h_q / sh->h_kv; p.pool_k = sh->pool_k;
+    p.keep_first = sh->keep_first; p.keep_last = sh->keep_last;
     p.scale = sh->scale > 0.0f ? sh->scale : (float)(1.0 / std::sqrt((double)sh->d));
     const int64_t rows = (int64_t)p.n_q * p.group;
     if (rows > (1 << 20)) return JQ_ERR_UNSUPPORTED;
@@ -55,7 +57,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
         if (sh->budgets) {
             b = sh->budgets[s];
             const int32_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
-            if (need_budgets && (b < 1 || b > L)) return JQ_ERR_BUDGET;
+            if (need_budgets && (b < 1 || b > L || (int64_t)sh->keep_first + sh->keep_last > b)) return JQ_ERR_BUDGET;
             if (b < 1 || b > L) b = 1;  // entry points that ignore budgets still get a sane table
         }
         tb += b;
@@ -353,7 +355,7 @@ const char* jq_status_string(int status) {
         case JQ_OK: return "ok";
         case JQ_ERR_NULL: return "a required pointer is NULL";
         case JQ_ERR_SHAPE: return "malformed shape (dimension, pool_k, scale or cu_seqlens)";
-        case JQ_ERR_BUDGET: return "a budget is outside 1..L";
+        case JQ_ERR_BUDGET: return "a budget is outside 1..L or below keep_first + keep_last";
         case JQ_ERR_UNSUPPORTED: return "valid but unsupported (d != 128, too many sequences, or misaligned tensor)";
         case JQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case JQ_ERR_ALIAS: return "an output overlaps an input or another output";

@@ -31,6 +31,7 @@ struct SeqTab {
 // Everything the host derives from a jq_shape.
 struct Plan {
     int32_t n_layers, n_seq, n_q, h_q, h_kv, d, group, pool_k;
+    int32_t keep_first, keep_last;  // positions at either end of a sequence that the selection always keeps
     int32_t rows;         // n_q * group: query rows that share one KV head
     int32_t row_tiles;    // ceil(rows / 32)
     int32_t row_groups;   // ceil(row_tiles / 4): passes of the score kernels over K
@@ -61,6 +62,12 @@ __host__ __device__ inline int find_seq(const int32_t* cu, int n, int64_t v) {
 __device__ inline uint32_t sortable_key(float x) {
     uint32_t b = __float_as_uint(x + 0.0f);
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Key the top-B selection ranks position j of an L-token sequence by: always-kept positions outrank
+// every score.
+__device__ inline uint32_t select_key(float x, int j, int L, int keep_first, int keep_last) {
+    return (j < keep_first || j >= L - keep_last) ? 0xFFFFFFFFu : sortable_key(x);
 }
 
 // Kernels whose start/stop timestamps jq_evict_traced reports, in launch order.

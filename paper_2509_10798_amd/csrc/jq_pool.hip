@@ -26,6 +26,7 @@ struct PoolArgs {
     float* out;        // same shape (null for the histogram-only kernel)
     uint32_t* hist;    // [n_layers][n_seq][h_kv][kHistStride] or null
     int32_t n_layers, h_kv, pool_k;
+    int32_t keep_first, keep_last;  // always-kept positions (they land in the histogram's top bin)
     float inv_k;
     int64_t T;
     SeqTab tab;
@@ -132,7 +133,8 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const bool in = p0 + j0 + u < p1;
-                bin[4 * h + u] = in ? (sortable_key(v[u]) >> 21) : 0xFFFFFFFFu;  // 0xFFFFFFFF: no element
+                bin[4 * h + u] = in ? (select_key(v[u], (int)(p0 - lo) + j0 + u, (int)(hi - lo), a.keep_first, a.keep_last) >> 21)
+                                    : 0xFFFFFFFFu;  // 0xFFFFFFFF: no element
                 if (in) top = max(top, bin[4 * h + u]);
             }
         }
@@ -235,6 +237,7 @@ static PoolArgs make_args(const Plan& p, const float* in, float* out, uint32_t* 
     PoolArgs a;
     a.in = in; a.out = out; a.hist = hist;
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.pool_k = p.pool_k;
+    a.keep_first = p.keep_first; a.keep_last = p.keep_last;
     a.inv_k = 1.0f / (float)p.pool_k;
     a.T = p.T;
     a.tab = p.tab;

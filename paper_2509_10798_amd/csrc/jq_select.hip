@@ -29,6 +29,7 @@ struct SelectArgs {
     uint2* cand;          // [n_layers][h_kv][T]    (key, position) inside bin b1 (unordered)
     int32_t* idx;         // [n_layers][h_kv][TB]
     int32_t n_layers, h_kv;
+    int32_t keep_first, keep_last;  // always-kept positions at either end of every sequence
     int64_t T, TB;
     // fused gather (all four null when the kept rows are not wanted): K,V [n_layers][T][h_kv][d] bf16,
     // K_out,V_out [n_layers][TB][h_kv][d]
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_stream_kernel(Select
     for (int b = threadIdx.x; b < kHistBins; b += kSelectThreads) bins[b] = 0;
     __syncthreads();
     for (int j = threadIdx.x; j < L; j += kSelectThreads) {
-        const uint32_t k = sortable_key(x[j]);
+        const uint32_t k = select_key(x[j], j, L, a.keep_first, a.keep_last);
         if ((k >> 21) == b1) atomicAdd(&bins[(k >> 10) & 2047u], 1u);
     }
     __syncthreads();
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_stream_kernel(Select
     for (int b = threadIdx.x; b < 1024; b += kSelectThreads) bins[b] = 0;
     __syncthreads();
     for (int j = threadIdx.x; j < L; j += kSelectThreads) {
-        const uint32_t k = sortable_key(x[j]);
+        const uint32_t k = select_key(x[j], j, L, a.keep_first, a.keep_last);
         if ((k >> 10) == prefix22) atomicAdd(&bins[k & 1023u], 1u);
     }
     __syncthreads();
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_stream_kernel(Select
         uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            kk[e] = (j0 + e < L) ? sortable_key(x[j0 + e]) : 0u;
+            kk[e] = (j0 + e < L) ? select_key(x[j0 + e], j0 + e, L, a.keep_first, a.keep_last) : 0u;
             n_gt += (j0 + e < L) && kk[e] > tau;
             n_eq += (j0 + e < L) && kk[e] == tau;
         }
@@ -230,6 +231,8 @@ __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(Sele
         for (int e = 0; e < kScatterPerThread; ++e) {
             const int64_t t = t0 + (int64_t)e * kScatterThreads;
             const bool in = t >= q0 && t < q1;
+            const int j = (int)(t - a.tab.cu_seq[s]);
+            if (in && (j < a.keep_first || j >= Ls - a.keep_last)) key[e] = 0xFFFFFFFFu;  // always kept
             n_s += in && (key[e] >> 21) > b1;
             n_c += in && (key[e] >> 21) == b1;
         }
@@ -426,6 +429,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     a.sure = (int32_t*)(ws + p.off_sure);
     a.cand = (uint2*)(ws + p.off_cand);
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
+    a.keep_first = p.keep_first; a.keep_last = p.keep_last;
     a.tab = p.tab;
     const unsigned n_prob = (unsigned)((int64_t)p.n_layers * p.n_seq * p.h_kv);
 

@@ -56,3 +56,19 @@ def assert_kept_set_ok(pooled_ref: np.ndarray, idx_ref: np.ndarray, idx_gpu: np.
     m_gpu, m_ref = pooled_ref[idx_gpu].sum(), pooled_ref[idx_ref].sum()
     assert abs(m_gpu - m_ref) <= MASS_RTOL * m_ref, what + ": kept mass differs by %.3e" % (abs(m_gpu - m_ref) / m_ref)
     return "contested"
+
+
+def assert_kept_set_ok_keep(pooled_ref, idx_ref, idx_gpu, keep_first, keep_last, what=""):
+    """The same check when the first keep_first / last keep_last positions are kept unconditionally:
+    they must all be present, and the rest is judged as a selection among the other positions."""
+    L, B = pooled_ref.shape[0], idx_ref.shape[0]
+    idx_gpu = np.asarray(idx_gpu, dtype=np.int64)
+    assert idx_gpu.shape == (B,), what
+    forced = np.concatenate([np.arange(keep_first), np.arange(L - keep_last, L)])
+    assert np.isin(forced, idx_gpu).all(), what + ": an always-kept position is missing"
+    assert np.isin(forced, idx_ref).all(), what
+    if B == forced.size:
+        assert (np.diff(idx_gpu) > 0).all(), what
+        return "forced only"
+    free = lambda idx: np.asarray([j - keep_first for j in idx if keep_first <= j < L - keep_last], dtype=np.int64)
+    return assert_kept_set_ok(pooled_ref[keep_first:L - keep_last], free(idx_ref), free(idx_gpu), what)

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 import paper_2509_10798_amd as jq
-from parity import assert_kept_set_ok, assert_scores_close, from_dev_bf16, to_dev_bf16
+from parity import assert_kept_set_ok, assert_kept_set_ok_keep, assert_scores_close, from_dev_bf16, to_dev_bf16
 from workloads import f32_to_bf16_bits, make_workload
 
 pytestmark = pytest.mark.gpu
@@ -132,16 +132,17 @@ def test_pool_matches_oracle(seq_lens, k):
         np.testing.assert_allclose(got[:, :, cu[s]:cu[s + 1]], ref, rtol=2e-6, atol=0)
 
 
-def run_select_case(x, seq_lens, budgets):
+def run_select_case(x, seq_lens, budgets, keep_first=0, keep_last=0):
     torch = torch_()
     nl, h_kv, T = x.shape
-    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, budgets=budgets)
+    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, budgets=budgets, keep_first=keep_first,
+                  keep_last=keep_last)
     idx = jq.select_topk(sh, torch.from_numpy(x).cuda())
     torch.cuda.synchronize()
     idx = idx.cpu().numpy()
     cu = np.concatenate([[0], np.cumsum(seq_lens)]); cb = np.concatenate([[0], np.cumsum(budgets)])
     for s in range(len(seq_lens)):
-        ref = oracle.select_topk(x[:, :, cu[s]:cu[s + 1]].astype(np.float64), budgets[s])
+        ref = oracle.select_topk(x[:, :, cu[s]:cu[s + 1]].astype(np.float64), budgets[s], keep_first, keep_last)
         np.testing.assert_array_equal(idx[:, :, cb[s]:cb[s + 1]], ref)
 
 
@@ -181,6 +182,33 @@ def test_select_wide_dynamic_range():
     run_select_case(x, [20000], [64])
     run_select_case(x, [20000], [15000])
     run_select_case(x, [12000, 8000], [9000, 100])
+
+
+@pytest.mark.parametrize("seq_lens,budgets,kf,kl", [
+    ([5000], [256], 4, 32), ([5000], [36], 4, 32),            # the forced positions fill the budget exactly
+    ([100], [10], 0, 10), ([100], [10], 10, 0), ([7], [7], 3, 4),
+    ([4097, 40, 9000], [512, 40, 33], 1, 32),                  # ragged batch; a sequence kept whole; one nearly all forced
+    ([70000], [2048], 16, 1000),
+    ([700000], [3000], 4, 64),                                 # streaming path
+])
+def test_select_with_always_kept_ends(seq_lens, budgets, kf, kl):
+    # sinks and local window of the Section 5.1 baselines: kept whatever they score, counted in the budget
+    rng = np.random.default_rng(35)
+    x = rng.random((2, 3, sum(seq_lens))).astype(np.float32)
+    cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    for s in range(len(seq_lens)):                             # make the forced positions the WORST candidates
+        x[:, :, cu[s]:cu[s] + kf] = 0.0
+        x[:, :, cu[s + 1] - kl:cu[s + 1]] = -1.0
+    run_select_case(x, seq_lens, budgets, kf, kl)
+
+
+def test_select_with_always_kept_ends_and_ties():
+    rng = np.random.default_rng(36)
+    x = np.round(rng.random((1, 4, 6000)).astype(np.float32), 2)
+    x[0, 1] = 0.5                                              # all equal: forced ends, then the lowest free positions
+    x[0, 2, :50] = 2.0                                         # forced positions that would have won anyway
+    run_select_case(x, [6000], [1000], 8, 100)
+    run_select_case(x, [2500, 3500], [2500, 120], 8, 100)
 
 
 def test_compact_is_bit_exact():
@@ -249,6 +277,41 @@ def test_layer_dependent_budgets_by_one_call_per_layer():
         rk, rv = oracle.compact(K[layer], V[layer], np.ascontiguousarray(idx[0].cpu().numpy()))
         np.testing.assert_array_equal(from_dev_bf16(Ko)[0], rk)
         np.testing.assert_array_equal(from_dev_bf16(Vo)[0], rv)
+
+
+def test_evict_with_always_kept_ends():
+    # the fused call with attention sinks and a recent window forced into the kept set
+    torch = torch_()
+    w = make_workload(1, seq_lens=[1500, 700], budget=[200, 64], n_layers=2)
+    Q, K, V = w.assemble()
+    kf, kl = 4, 32
+    sh = jq.Shape(n_layers=2, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets,
+                  keep_first=kf, keep_last=kl)
+    Qd, Kd, Vd = to_dev_bf16(Q), to_dev_bf16(K), to_dev_bf16(V)
+    Ko, Vo, idx, pooled = jq.evict(sh, Qd, Kd, Vd)
+    i1 = jq.select_topk(sh, pooled)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, i1)
+    ref = oracle.evict_batch(Q, K, V, w.cu_seqlens, w.budgets, w.pool_k, keep_first=kf, keep_last=kl)
+    pooled_h, idx_h = pooled.cpu().numpy(), idx.cpu().numpy()
+    Ko_h, Vo_h = from_dev_bf16(Ko), from_dev_bf16(Vo)
+    cu, cb = w.cu_seqlens, w.cu_budgets
+    for l in range(2):
+        for s in range(2):
+            L = w.seq_lens[s]
+            # the reported scores are the plain pooled scores: forcing changes the kept set only
+            assert_scores_close(pooled_h[l, :, cu[s]:cu[s + 1]], ref["pooled"][l, :, cu[s]:cu[s + 1]], w.n_q * w.group / L)
+            for g in range(w.h_kv):
+                assert_kept_set_ok_keep(ref["pooled"][l, g, cu[s]:cu[s + 1]], ref["idx"][l, g, cb[s]:cb[s + 1]],
+                                        idx_h[l, g, cb[s]:cb[s + 1]], kf, kl, "l%d s%d g%d" % (l, s, g))
+            rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], idx_h[l, :, cb[s]:cb[s + 1]])
+            np.testing.assert_array_equal(Ko_h[l, cb[s]:cb[s + 1]], rk)
+            np.testing.assert_array_equal(Vo_h[l, cb[s]:cb[s + 1]], rv)
+    # the forced window really changes the outcome here: without it some of those rows are dropped
+    sh0 = jq.Shape(n_layers=2, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    idx0 = jq.evict(sh0, Qd, Kd, Vd)[2]
+    torch.cuda.synchronize()
+    assert not torch.equal(idx0, idx)
 
 
 def test_evict_equals_stage_composition_and_oracle():
