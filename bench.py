@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--buffers", type=int, default=4, help="distinct K/V sets rotated over")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--trace-steps", type=int, default=50)
+    ap.add_argument("--page-size", type=int, default=256, help="tokens per page of the paged-cache leg")
     ap.add_argument("--probe-copy", action="store_true",
                     help="only run the plain 256 MiB copy kernel a few times (reference for profiler byte counters)")
     args = ap.parse_args()
@@ -143,6 +144,37 @@ def main():
     torch.cuda.synchronize()
     ms_tail = (time.perf_counter() - t0) / args.steps * 1e3
 
+    # the same eviction on a paged cache (jq_evict_paged): pools of 256-token pages handed out in a random order
+    ms_paged, page_size = None, args.page_size
+    if all(L % page_size == 0 for L in w.seq_lens):
+        n_pages = w.total_tokens // page_size
+        gen = torch.Generator(device="cpu"); gen.manual_seed(w.seed)
+        perm = torch.randperm(n_pages, generator=gen).cuda()
+        table = torch.full((w.n_seq, max(w.seq_lens) // page_size), -1, dtype=torch.int32, device="cuda")
+        first = 0
+        for s_, L in enumerate(w.seq_lens):
+            table[s_, :L // page_size] = perm[first:first + L // page_size].to(torch.int32)
+            first += L // page_size
+        pages = jq.Pages(page_size=page_size, n_pages=n_pages, block_table=table)
+        psets = []
+        for Kd, Vd in sets:
+            Kp = torch.empty((w.n_layers, n_pages, page_size, w.h_kv, w.d), dtype=torch.bfloat16, device="cuda")
+            Vp = torch.empty_like(Kp)
+            Kp[:, perm] = Kd.view(w.n_layers, n_pages, page_size, w.h_kv, w.d)
+            Vp[:, perm] = Vd.view(w.n_layers, n_pages, page_size, w.h_kv, w.d)
+            psets.append((Kp, Vp))
+        for i in range(5):
+            Kp, Vp = psets[i % len(psets)]
+            jq.evict_paged(sh, pages, Qd, Kp, Vp, K_out=Ko, V_out=Vo, idx_out=idx, scores_out=pooled, ws=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            Kp, Vp = psets[i % len(psets)]
+            jq.evict_paged(sh, pages, Qd, Kp, Vp, K_out=Ko, V_out=Vo, idx_out=idx, scores_out=pooled, ws=ws)
+        torch.cuda.synchronize()
+        ms_paged = (time.perf_counter() - t0) / args.steps * 1e3
+        del psets
+
     # ---- per-kernel times: every kernel of a traced step carries its own start/stop events, which
     # ---- receive the dispatch's begin/end timestamps on the launch stream
     # (one event set per traced step, no host synchronisation in between: the GPU stays busy as in the timed loop)
@@ -197,6 +229,9 @@ def main():
         "kernel_us": kernels_us,
         "roofline": roofline,
     }
+    if ms_paged is not None:
+        out["paged_cache"] = {"entry": "jq_evict_paged", "page_size": page_size, "ms_per_step": round(ms_paged, 5),
+                              "tokens_per_s_per_layer": round(w.total_tokens * w.n_layers / (ms_paged * 1e-3), 1)}
 
     if not args.no_cpu:
         import oracle

@@ -15,6 +15,7 @@
  *   jq_evict        all of the above for n_layers x n_seq problems in one call
  *   jq_score_lse, jq_evict_lse    the same with caller-supplied softmax normalisers
  *   jq_score_tail, jq_evict_tail  the same with the soft tokens' own keys in the softmax
+ *   jq_score_paged, jq_evict_paged  the same on a paged cache (pools + block table)
  *   jq_hit_rate     critical-KV hit rate between two kept sets (Eq. 6)
  *   jq_map_mse      forward value of the training objective (Eq. 5) from two score maps
  *
@@ -189,6 +190,35 @@ int jq_evict_lse(const jq_shape* shape, const void* Q, const void* K, const void
 int jq_evict_tail(const jq_shape* shape, const void* Q, const void* K, const void* V, const void* K_tail,
                   void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
                   void* ws, size_t ws_bytes, void* stream);
+
+/* The same eviction (Section 4.3) on a PAGED key-value cache, the layout serving engines keep:
+ * each layer's keys live in a pool of fixed-size pages, and a per-sequence block table says which
+ * page holds which stretch of the sequence.
+ *   K_pool, V_pool  DEVICE bf16 [n_layers, n_pages, page_size, h_kv, d]
+ *   token t of sequence s is row (t % page_size) of page block_table[s, t / page_size]
+ * Everything else -- Q, scores, idx (sequence-local LOGICAL positions), the dense K_out / V_out
+ * [n_layers, sum budgets, h_kv, d], cu_seqlens, budgets, keep_first / keep_last -- is as in jq_evict.
+ * Rows of a page beyond the sequence's end are never read.  A block-table entry outside
+ * 0..n_pages-1 is clamped into that range (never dereferenced out of bounds); the table is read
+ * on the device only, so its entries cannot be validated here. */
+typedef struct jq_pages {
+    int32_t page_size;          /* tokens per page: a power of two, 32..65536                       */
+    int32_t n_pages;            /* pages in each layer's pool; n_pages * page_size * h_kv * d * 2   */
+                                /* bytes must stay below 4 GiB                                      */
+    int32_t max_pages_per_seq;  /* row length of block_table; >= ceil(L_s / page_size) for every s  */
+    const int32_t* block_table; /* DEVICE int32 [n_seq, max_pages_per_seq]                          */
+} jq_pages;
+
+/* jq_score / jq_score_lse on a paged cache: `lse` NULL selects the two-pass softmax over the
+ * prompt keys, otherwise the supplied normalisers are used and K is read once. */
+int jq_score_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, const void* K_pool,
+                   const float* lse, float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/* jq_evict / jq_evict_lse on a paged cache (`lse` as above); the kept rows are gathered out of the
+ * pools into the dense K_out / V_out. */
+int jq_evict_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, const void* K_pool,
+                   const void* V_pool, const float* lse, void* K_out, void* V_out, int32_t* idx_out,
+                   float* scores_out, void* ws, size_t ws_bytes, void* stream);
 
 /* jq_evict with kernel timing (the measurement hook of the benchmark): `marks` is a
  * HOST array of JQ_TRACE_MARKS hipEvent_t (passed as void*), created by the caller.

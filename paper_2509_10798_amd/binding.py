@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
            "jq_copy_probe", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel", "jq_select_finalize_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
@@ -39,6 +39,11 @@ class _CShape(ctypes.Structure):
                 ("pool_k", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("cu_seqlens", ctypes.POINTER(ctypes.c_int32)), ("budgets", ctypes.POINTER(ctypes.c_int32)),
                 ("keep_first", ctypes.c_int32), ("keep_last", ctypes.c_int32)]
+
+
+class _CPages(ctypes.Structure):
+    _fields_ = [("page_size", ctypes.c_int32), ("n_pages", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
+                ("block_table", ctypes.c_void_p)]
 
 
 def lib() -> ctypes.CDLL:
@@ -66,6 +71,9 @@ def lib() -> ctypes.CDLL:
         L.jq_select_topk.argtypes = [shp, vp, vp, vp, sz, vp]
         L.jq_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp]
         L.jq_evict.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        pgp = ctypes.POINTER(_CPages)
+        L.jq_score_paged.argtypes = [shp, pgp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_evict_paged.argtypes = [shp, pgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_traced.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp), ctypes.c_int]
         L.jq_copy_probe.argtypes = [vp, vp, sz, vp]
         L.jq_status_string.argtypes = [ctypes.c_int]
@@ -239,6 +247,54 @@ def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_ou
         return K_out, V_out, idx_out, scores_out
     _check(lib().jq_evict(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(idx_out),
                           _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict")
+    return K_out, V_out, idx_out, scores_out
+
+
+@dataclass
+class Pages:
+    """A paged K/V cache; mirrors ``jq_pages``.  `block_table`: int32 device tensor [n_seq, max_pages_per_seq]."""
+    page_size: int
+    n_pages: int
+    block_table: object
+
+    def c_struct(self) -> _CPages:
+        bt = self.block_table
+        return _CPages(int(self.page_size), int(self.n_pages), int(bt.shape[1]) if bt is not None else 0,
+                       _ptr(bt) if bt is not None else None)
+
+
+def score_paged(shape: Shape, pages: Pages, Q, K_pool, lse=None, scores=None, ws=None, stream=None):
+    """Unpooled scores from a paged cache: K_pool [n_layers, n_pages, page_size, h_kv, d] bf16."""
+    import torch
+    if scores is None:
+        scores = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=K_pool.device)
+    if ws is None:
+        ws = alloc_workspace(shape, K_pool.device)
+    cs, cp = shape.c_struct(), pages.c_struct()
+    _check(lib().jq_score_paged(ctypes.byref(cs), ctypes.byref(cp), _ptr(Q), _ptr(K_pool), _ptr(lse), _ptr(scores), _ptr(ws),
+                                ws.numel(), _stream(stream)), "jq_score_paged")
+    return scores
+
+
+def evict_paged(shape: Shape, pages: Pages, Q, K_pool, V_pool, lse=None, K_out=None, V_out=None, idx_out=None,
+                scores_out=None, ws=None, stream=None, want_idx=True, want_scores=True):
+    """Fused eviction on a paged cache.  Returns (K_out, V_out, idx_out, pooled scores); K_out / V_out are dense."""
+    import torch
+    dev = K_pool.device
+    if K_out is None:
+        K_out = torch.empty((shape.n_layers, shape.TB, shape.h_kv, shape.d), dtype=K_pool.dtype, device=dev)
+    if V_out is None:
+        V_out = torch.empty_like(K_out)
+    if idx_out is None and want_idx:
+        idx_out = torch.empty((shape.n_layers, shape.h_kv, shape.TB), dtype=torch.int32, device=dev)
+    if scores_out is None and want_scores:
+        scores_out = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = alloc_workspace(shape, dev)
+    cs, cp = shape.c_struct(), pages.c_struct()
+    _check(lib().jq_evict_paged(ctypes.byref(cs), ctypes.byref(cp), _ptr(Q), _ptr(K_pool), _ptr(V_pool), _ptr(lse),
+                                _ptr(K_out), _ptr(V_out), _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(),
+                                _stream(stream)), "jq_evict_paged")
     return K_out, V_out, idx_out, scores_out
 
 

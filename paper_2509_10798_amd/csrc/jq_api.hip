@@ -119,13 +119,37 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     return JQ_OK;
 }
 
+// Validates a paged-cache description against the plan and records it there.
+int apply_pages(const jq_pages* pg, Plan* p) {
+    if (!pg || !pg->block_table) return JQ_ERR_NULL;
+    if (pg->page_size < kKeyTile || pg->page_size > 65536 || (pg->page_size & (pg->page_size - 1)) != 0) return JQ_ERR_SHAPE;
+    if (pg->n_pages < 1 || pg->max_pages_per_seq < 1) return JQ_ERR_SHAPE;
+    for (int s = 0; s < p->n_seq; ++s) {
+        const int64_t L = p->tab.cu_seq[s + 1] - p->tab.cu_seq[s];
+        if ((L + pg->page_size - 1) / pg->page_size > pg->max_pages_per_seq) return JQ_ERR_SHAPE;
+    }
+    // the score kernels address a layer's whole pool through one 32-bit buffer offset
+    if ((int64_t)pg->n_pages * pg->page_size * p->h_kv * kHeadDim * 2 > (int64_t)UINT32_MAX) return JQ_ERR_UNSUPPORTED;
+    if (misaligned(pg->block_table, 4)) return JQ_ERR_UNSUPPORTED;
+    p->block_table = pg->block_table;
+    p->page_shift = 0;
+    while ((1 << p->page_shift) < pg->page_size) ++p->page_shift;
+    p->n_pages = pg->n_pages;
+    p->max_pages = pg->max_pages_per_seq;
+    return JQ_OK;
+}
+
 int check_ws(const Plan& p, const void* ws, size_t ws_bytes) {
     if (!ws) return JQ_ERR_NULL;
     if (misaligned(ws, 16) || ws_bytes < p.ws_bytes) return JQ_ERR_WORKSPACE;
     return JQ_OK;
 }
 
-size_t kv_bytes(const Plan& p) { return (size_t)p.n_layers * p.T * p.h_kv * p.d * 2; }
+size_t kv_bytes(const Plan& p) {  // bytes of K (or V) as the caller holds it: dense rows, or the pools of all layers
+    const size_t rows = p.block_table ? ((size_t)p.n_pages << p.page_shift) : (size_t)p.T;
+    return (size_t)p.n_layers * rows * p.h_kv * p.d * 2;
+}
+size_t table_bytes(const Plan& p) { return p.block_table ? (size_t)p.n_seq * p.max_pages * 4 : 0; }
 size_t kv_out_bytes(const Plan& p) { return (size_t)p.n_layers * p.TB * p.h_kv * p.d * 2; }
 size_t q_bytes(const Plan& p) { return (size_t)p.n_layers * p.n_seq * p.n_q * p.h_q * p.d * 2; }
 size_t score_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.T * 4; }
@@ -157,10 +181,12 @@ int jq_workspace_bytes(const jq_shape* shape, size_t* bytes) {
 
 // `extra` is the variant's additional input: normalisers (lse) or the soft tokens' keys (k_tail), at most one.
 static int score_impl(const jq_shape* shape, const void* Q, const void* K, const float* lse, const void* k_tail,
-                      bool want_extra, float* scores, void* ws, size_t ws_bytes, void* stream) {
+                      bool want_extra, float* scores, void* ws, size_t ws_bytes, void* stream,
+                      const jq_pages* pages = nullptr, bool paged = false) {
     Plan p;
     int rc = make_plan(shape, false, &p);
     if (rc != JQ_OK) return rc;
+    if (paged && (rc = apply_pages(pages, &p)) != JQ_OK) return rc;
     const void* extra = lse ? (const void*)lse : k_tail;
     if (!Q || !K || !scores || (want_extra && !extra)) return JQ_ERR_NULL;
     if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
@@ -171,7 +197,9 @@ static int score_impl(const jq_shape* shape, const void* Q, const void* K, const
     if (overlaps(scores, score_bytes(p), K, kv_bytes(p)) || overlaps(scores, score_bytes(p), Q, q_bytes(p)) ||
         overlaps(scores, score_bytes(p), ws, p.ws_bytes) || overlaps(ws, p.ws_bytes, Q, q_bytes(p)) ||
         overlaps(ws, p.ws_bytes, K, kv_bytes(p)) ||
-        (extra && (overlaps(scores, score_bytes(p), extra, extra_bytes) || overlaps(ws, p.ws_bytes, extra, extra_bytes))))
+        (extra && (overlaps(scores, score_bytes(p), extra, extra_bytes) || overlaps(ws, p.ws_bytes, extra, extra_bytes))) ||
+        (paged && (overlaps(scores, score_bytes(p), p.block_table, table_bytes(p)) ||
+                   overlaps(ws, p.ws_bytes, p.block_table, table_bytes(p)))))
         return JQ_ERR_ALIAS;
     return launch_status(launch_score(p, Q, K, scores, (char*)ws, (hipStream_t)stream, nullptr, 0, lse, k_tail));
 }
@@ -238,10 +266,12 @@ int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_
 
 static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,
                       const void* k_tail, void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
-                      size_t ws_bytes, void* stream, void* const* marks) {
+                      size_t ws_bytes, void* stream, void* const* marks, const jq_pages* pages = nullptr,
+                      bool paged = false) {
     Plan p;
     int rc = make_plan(shape, true, &p);
     if (rc != JQ_OK) return rc;
+    if (paged && (rc = apply_pages(pages, &p)) != JQ_OK) return rc;
     if (!Q || !K || !V || !K_out || !V_out) return JQ_ERR_NULL;
     if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(K_out, 16) || misaligned(V_out, 16) ||
@@ -249,13 +279,13 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
         (k_tail && misaligned(k_tail, 16)))
         return JQ_ERR_UNSUPPORTED;
     const size_t nin = kv_bytes(p), nout = kv_out_bytes(p);
-    const void* ins[4] = {Q, K, V, lse ? (const void*)lse : k_tail};
-    const size_t in_bytes[4] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p)};
+    const void* ins[5] = {Q, K, V, lse ? (const void*)lse : k_tail, p.block_table};
+    const size_t in_bytes[5] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p), table_bytes(p)};
     const void* outs[5] = {K_out, V_out, idx_out, scores_out, ws};
     const size_t out_bytes[5] = {nout, nout, idx_bytes(p), score_bytes(p), p.ws_bytes};
     for (int o = 0; o < 5; ++o) {
         if (!outs[o]) continue;
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 5; ++i)
             if (ins[i] && overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return JQ_ERR_ALIAS;
         for (int o2 = o + 1; o2 < 5; ++o2)
             if (outs[o2] && overlaps(outs[o], out_bytes[o], outs[o2], out_bytes[o2])) return JQ_ERR_ALIAS;
@@ -292,6 +322,18 @@ int jq_evict_tail(const jq_shape* shape, const void* Q, const void* K, const voi
                   void* V_out, int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
     if (!K_tail) return JQ_ERR_NULL;
     return evict_impl(shape, Q, K, V, nullptr, K_tail, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
+}
+
+int jq_score_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, const void* K_pool, const float* lse,
+                   float* scores, void* ws, size_t ws_bytes, void* stream) {
+    return score_impl(shape, Q, K_pool, lse, nullptr, false, scores, ws, ws_bytes, stream, pages, true);
+}
+
+int jq_evict_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, const void* K_pool, const void* V_pool,
+                   const float* lse, void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
+                   size_t ws_bytes, void* stream) {
+    return evict_impl(shape, Q, K_pool, V_pool, lse, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream,
+                      nullptr, pages, true);
 }
 
 int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,

@@ -28,6 +28,13 @@ struct SeqTab {
     int32_t cu_cgrp[JQ_MAX_SEQ + 1];   // score-workgroup offsets (ceil(waves / 4) workgroups per sequence and head)
 };
 
+// Where a layer's K / V rows live: dense [T] rows per layer (block_table null), or a pool of n_pages pages of
+// 1 << page_shift rows per layer with a per-sequence block table.
+struct PageMap {
+    const int32_t* block_table;  // DEVICE [n_seq][max_pages], or null
+    int32_t page_shift, n_pages, max_pages;
+};
+
 // Everything the host derives from a jq_shape.
 struct Plan {
     int32_t n_layers, n_seq, n_q, h_q, h_kv, d, group, pool_k;
@@ -41,8 +48,12 @@ struct Plan {
     int32_t chunk_keys2, n_chunks2;
     int32_t cu_chunk2[JQ_MAX_SEQ + 1], cu_cgrp2[JQ_MAX_SEQ + 1];
     float scale;          // logit scale actually used
+    // paged cache (block_table null: dense K, V): page = 1 << page_shift tokens, n_pages per layer's pool
+    const int32_t* block_table;  // DEVICE [n_seq][max_pages]
+    int32_t page_shift, n_pages, max_pages;
     int64_t T, TB;
     SeqTab tab;
+    PageMap page_map() const { return PageMap{block_table, page_shift, n_pages, max_pages}; }
     void* const* marks;   // host only: nullptr, or 2 * kTraceKernels events (start, stop) for jq_evict_traced
     // workspace layout (byte offsets, 256-aligned)
     size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
@@ -62,6 +73,15 @@ __host__ __device__ inline int find_seq(const int32_t* cu, int n, int64_t v) {
 __device__ inline uint32_t sortable_key(float x) {
     uint32_t b = __float_as_uint(x + 0.0f);
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Row (in units of token rows, over all layers) of token `pos` of sequence `s`.  A table entry outside the pool is
+// clamped into it.
+__device__ inline int64_t kv_row(const PageMap& pm, const SeqTab& tab, int64_t T, int layer, int s, int pos) {
+    if (!pm.block_table) return (int64_t)layer * T + tab.cu_seq[s] + pos;
+    const int32_t e = pm.block_table[(int64_t)s * pm.max_pages + (pos >> pm.page_shift)];
+    const int64_t page = (int64_t)layer * pm.n_pages + min(max(e, 0), pm.n_pages - 1);
+    return (page << pm.page_shift) + (pos & ((1 << pm.page_shift) - 1));
 }
 
 // Key the top-B selection ranks position j of an L-token sequence by: always-kept positions outrank

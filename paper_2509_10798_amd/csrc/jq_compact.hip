@@ -13,6 +13,7 @@ struct CompactArgs {
     const int32_t* idx;  // [n_layers][h_kv][TB], sequence-local
     int32_t n_layers, h_kv;
     int64_t T, TB;
+    PageMap pm;  // where the rows of K and V live (dense or paged)
     SeqTab tab;
 };
 
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_kernel(CompactArgs
     const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
     int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
     j = min(max(j, 0), L - 1);  // never read outside the sequence
-    const int64_t src = ((((int64_t)layer * a.T + a.tab.cu_seq[s] + j) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
+    const int64_t src = ((kv_row(a.pm, a.tab, a.T, layer, s, j) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
     const int64_t dst = item * (kHeadDim * 2) + part * 16;
     const u32x4 kv = *(const u32x4*)(a.K + src);
     const u32x4 vv = *(const u32x4*)(a.V + src);
@@ -47,6 +48,7 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
     a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
     a.idx = idx;
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
+    a.pm = p.page_map();
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
     return launch_kernel(jq_compact_kernel, dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads)),

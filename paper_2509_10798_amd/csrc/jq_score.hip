@@ -56,6 +56,10 @@ struct ScoreArgs {
     int64_t T;
     uint32_t* zero;      // combine: words to clear for the later selection stage (nullable)
     uint64_t zero_words;
+    // paged K (PAGED kernels): K is [n_layers][n_pages][1 << page_shift][h_kv][d]; token t of sequence s lives in
+    // page block_table[s * max_pages + (t >> page_shift)]
+    const int32_t* block_table;
+    int32_t page_shift, n_pages, max_pages;
     SeqTab tab;
 };
 
@@ -209,19 +213,47 @@ __device__ __forceinline__ void load_q_shared(const ScoreArgs& a, const WaveItem
 }
 
 struct KeyStream {
-    __amdgpu_buffer_rsrc_t rsrc;  // this head's rows of the whole sequence
+    __amdgpu_buffer_rsrc_t rsrc;  // this head's rows of the whole sequence (PAGED: of the layer's whole pool)
     uint32_t row_bytes;
+    const int32_t* pages;         // PAGED: the sequence's row of the block table
+    uint32_t page_shift, page_mask, last_page;
 };
 
+template <bool PAGED>
 __device__ __forceinline__ KeyStream key_stream(const ScoreArgs& a, const WaveItem& w) {
     KeyStream ks;
     ks.row_bytes = (uint32_t)a.h_kv * kHeadDim * 2;
-    const char* kseq = (const char*)a.K + (((int64_t)w.layer * a.T + w.tok0) * a.h_kv + w.g) * kHeadDim * 2;
-    // the resource covers exactly this head's rows of the sequence (the host checks that this is below
-    // 4 GiB); every generated offset stays inside it
-    const uint32_t bytes = (uint32_t)(w.L - 1) * ks.row_bytes + kHeadDim * 2;
+    // the resource covers exactly this head's rows of the sequence, or of the layer's pool (the host checks
+    // that this is below 4 GiB); every generated offset stays inside it
+    const int64_t first_row = PAGED ? ((int64_t)w.layer * a.n_pages) << a.page_shift : (int64_t)w.layer * a.T + w.tok0;
+    const uint32_t n_rows = PAGED ? (uint32_t)a.n_pages << a.page_shift : (uint32_t)w.L;
+    const char* kseq = (const char*)a.K + (first_row * a.h_kv + w.g) * kHeadDim * 2;
+    const uint32_t bytes = (n_rows - 1) * ks.row_bytes + kHeadDim * 2;
     ks.rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kseq, 0, (int)bytes, 0x00020000);
+    ks.pages = PAGED ? a.block_table + (int64_t)w.seq * a.max_pages : nullptr;
+    ks.page_shift = (uint32_t)a.page_shift;
+    ks.page_mask = (1u << a.page_shift) - 1u;
+    ks.last_page = (uint32_t)a.n_pages - 1u;
     return ks;
+}
+
+// Byte offset of sequence tile t inside the key stream's resource.  A page holds a whole number of 32-key
+// tiles, so a tile never straddles pages; `page` is the block-table entry of the tile's page (clamped here,
+// so that a corrupt table cannot send a load outside the pool).
+template <bool PAGED>
+__device__ __forceinline__ uint32_t tile_offset(const KeyStream& ks, int t, int page) {
+    const uint32_t tok = (uint32_t)t * kKeyTile;
+    if (!PAGED) return tok * ks.row_bytes;
+    const uint32_t p = min((uint32_t)page, ks.last_page);
+    return ((p << ks.page_shift) + (tok & ks.page_mask)) * ks.row_bytes;
+}
+// One table word per tile, at a wave-uniform address.  The table is read-only for the whole launch, so it is
+// read through the constant address space: that makes the load a scalar one with a wait of its own -- a
+// vector load would have to be waited for together with every key tile in flight.
+typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+template <bool PAGED>
+__device__ __forceinline__ int tile_page(const KeyStream& ks, int t) {
+    return PAGED ? ((const_i32_ptr)ks.pages)[((uint32_t)t * kKeyTile) >> ks.page_shift] : 0;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -292,7 +324,7 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
     }
 }
 
-template <int NQT>
+template <int NQT, bool PAGED>
 __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
     WaveItem w;
@@ -301,7 +333,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     const int half = lane >> 5;
     char* slots = &lds[__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))][0][0];
 
-    const KeyStream ks = key_stream(a, w);
+    const KeyStream ks = key_stream<PAGED>(a, w);
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
     // With the soft tokens' own keys in the softmax, the sequence's first wave takes them as further tiles
     // after its prompt tiles (same row stride, n_q rows), masked causally per query row.
@@ -313,11 +345,17 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         tail_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kt, 0, (int)((uint32_t)(a.n_q - 1) * ks.row_bytes + kHeadDim * 2),
                                                       0x00020000);
     }
-    // the wave's k-th tile is tile w.wave + k * w.n_waves of the sequence and uses slot k & 1
-    auto fetch = [&](int k) {
+    // the wave's k-th tile is tile w.wave + k * w.n_waves of the sequence and uses slot k & 1.  PAGED: tiles are
+    // requested in the order k = 0, 1, 2, ...; the table word of the NEXT request is loaded while this one is
+    // issued, so its latency never sits in front of a tile's loads (`first_page` primes the sequence).
+    int page_next = 0;
+    auto first_page = [&]() __attribute__((always_inline)) { if (PAGED && w.n_tiles > 0) page_next = tile_page<PAGED>(ks, w.wave); };
+    auto fetch = [&](int k) __attribute__((always_inline)) {
         if (k < w.n_tiles) {
             const int t = w.wave + k * w.n_waves;
-            fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, (uint32_t)t * kKeyTile * ks.row_bytes, ks.row_bytes,
+            const int page = page_next;
+            if (PAGED && k + 1 < w.n_tiles) page_next = tile_page<PAGED>(ks, t + w.n_waves);
+            fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, tile_offset<PAGED>(ks, t, page), ks.row_bytes,
                        w.L - t * kKeyTile, tl, lane);
         } else {
             const int t = k - w.n_tiles;
@@ -328,6 +366,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     // The first key tile goes to slot 0 at once; the second slots first serve as the staging area that turns
     // the workgroup's query rows into operand order, then take the second tile.  From then on two tiles are
     // always in flight: a slot is refilled as soon as its fragments are in registers.
+    first_page();
     if (n_all > 0) fetch(0);
     bf16x8 qf[NQT][8];
     load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
@@ -348,7 +387,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     for (int qt = 0; qt < NQT; ++qt) soft_i[qt] = ((a.row_tile0 + qt) * kRowTile + (lane & 31)) / a.group;
     // One sweep over the wave's tiles (the first two are already requested).  FAST: the first tile sets each
     // lane's offset m to the maximum of its logits there, later tiles keep it -- no maximum to track.
-    auto full_tile = [&](int k, auto fixed) {
+    auto full_tile = [&](int k, auto fixed) __attribute__((always_inline)) {
         wait_tile_landed(k + 1 < n_all);
         bf16x8 kf[8];
         lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
@@ -361,7 +400,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         for (int qt = 0; qt < NQT; ++qt) valid[qt] = kKeyTile;
         stats_tile<NQT, false, decltype(fixed)::value>(kf, qf, m, z, c, valid, half);
     };
-    auto masked_tile = [&](int k, const int (&valid)[NQT], bool fixed) {
+    auto masked_tile = [&](int k, const int (&valid)[NQT], bool fixed) __attribute__((always_inline)) {
         wait_tile_landed(k + 1 < n_all);
         bf16x8 kf[8];
         lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
@@ -372,7 +411,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         if (fixed) stats_tile<NQT, true, true>(kf, qf, m, z, c, valid, half);
         else stats_tile<NQT, true, false>(kf, qf, m, z, c, valid, half);
     };
-    auto sweep = [&](auto fast) {
+    auto sweep = [&](auto fast) __attribute__((always_inline)) {
         if (n_full > 0) full_tile(0, std::false_type{});
         for (int k = 1; k < n_full; ++k) full_tile(k, fast);
         int valid[NQT];
@@ -398,6 +437,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
         wait_frags_read();
+        first_page();
         fetch(0);
         if (n_all > 1) fetch(1);
         sweep(std::false_type{});
@@ -507,7 +547,7 @@ __device__ __forceinline__ f32x16 score_chain(const bf16x8 (&q)[8], bf16x8 qaug,
 // FROM_LSE: the caller supplied the normalisers and no statistics pass has run: lse becomes the -beta/c terms
 // on the fly (beta = lse * log2 e, c = scale * log2 e, so -beta/c = -lse / scale), and the launch also clears
 // the words the selection stage needs cleared.
-template <int NQT, bool FROM_LSE>
+template <int NQT, bool FROM_LSE, bool PAGED>
 __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
     WaveItem w;
@@ -516,14 +556,18 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     const int half = lane >> 5;
     char* slots = &lds[__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))][0][0];
 
-    const KeyStream ks = key_stream(a, w);
+    const KeyStream ks = key_stream<PAGED>(a, w);
     const TileLanes tl = tile_lanes(lane, ks.row_bytes);
     // The wave walks its tiles from the last to the first (pass 1 swept the keys front to back, so the end
     // of the sequence is what the caches still hold): its k-th tile here is sequence tile tile_of(k).
     auto tile_of = [&](int k) { return w.wave + (w.n_tiles - 1 - k) * w.n_waves; };
-    auto fetch = [&](int k) {
+    // PAGED: as in the first pass, the table word of the next request (k + 1) is loaded one request ahead
+    int page_next = (PAGED && w.n_tiles > 0) ? tile_page<PAGED>(ks, tile_of(0)) : 0;
+    auto fetch = [&](int k) __attribute__((always_inline)) {
         const int t = tile_of(k);
-        fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, (uint32_t)t * kKeyTile * ks.row_bytes, ks.row_bytes,
+        const int page = page_next;
+        if (PAGED && k + 1 < w.n_tiles) page_next = tile_page<PAGED>(ks, t - w.n_waves);
+        fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, tile_offset<PAGED>(ks, t, page), ks.row_bytes,
                    w.L - t * kKeyTile, tl, lane);
     };
     if (w.n_tiles > 0) fetch(0);
@@ -661,24 +705,25 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
+template <bool PAGED>
 static hipError_t launch_stats_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st, void* const* marks) {
     dim3 block(kScoreWaves * 64);
     switch (nqt) {
-        case 1: return launch_kernel(jq_stats_kernel<1>, grid, block, 0, st, marks, kTrStats, a);
-        case 2: return launch_kernel(jq_stats_kernel<2>, grid, block, 0, st, marks, kTrStats, a);
-        case 3: return launch_kernel(jq_stats_kernel<3>, grid, block, 0, st, marks, kTrStats, a);
-        default: return launch_kernel(jq_stats_kernel<4>, grid, block, 0, st, marks, kTrStats, a);
+        case 1: return launch_kernel(jq_stats_kernel<1, PAGED>, grid, block, 0, st, marks, kTrStats, a);
+        case 2: return launch_kernel(jq_stats_kernel<2, PAGED>, grid, block, 0, st, marks, kTrStats, a);
+        case 3: return launch_kernel(jq_stats_kernel<3, PAGED>, grid, block, 0, st, marks, kTrStats, a);
+        default: return launch_kernel(jq_stats_kernel<4, PAGED>, grid, block, 0, st, marks, kTrStats, a);
     }
 }
 
-template <bool FROM_LSE>
+template <bool FROM_LSE, bool PAGED>
 static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st, void* const* marks) {
     dim3 block(kScoreWaves * 64);
     switch (nqt) {
-        case 1: return launch_kernel(jq_score_kernel<1, FROM_LSE>, grid, block, 0, st, marks, kTrScore, a);
-        case 2: return launch_kernel(jq_score_kernel<2, FROM_LSE>, grid, block, 0, st, marks, kTrScore, a);
-        case 3: return launch_kernel(jq_score_kernel<3, FROM_LSE>, grid, block, 0, st, marks, kTrScore, a);
-        default: return launch_kernel(jq_score_kernel<4, FROM_LSE>, grid, block, 0, st, marks, kTrScore, a);
+        case 1: return launch_kernel(jq_score_kernel<1, FROM_LSE, PAGED>, grid, block, 0, st, marks, kTrScore, a);
+        case 2: return launch_kernel(jq_score_kernel<2, FROM_LSE, PAGED>, grid, block, 0, st, marks, kTrScore, a);
+        case 3: return launch_kernel(jq_score_kernel<3, FROM_LSE, PAGED>, grid, block, 0, st, marks, kTrScore, a);
+        default: return launch_kernel(jq_score_kernel<4, FROM_LSE, PAGED>, grid, block, 0, st, marks, kTrScore, a);
     }
 }
 
@@ -702,6 +747,8 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.T = p.T;
     a.zero = zero; a.zero_words = zero_words;
     a.tab = p.tab;
+    a.block_table = p.block_table; a.page_shift = p.page_shift; a.n_pages = p.n_pages; a.max_pages = p.max_pages;
+    const bool paged = p.block_table != nullptr;
     a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
     a.n_cgrp = p.tab.cu_cgrp[p.n_seq];
 
@@ -715,7 +762,8 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         for (int rg = 0; rg < p.row_groups; ++rg) {
             a.row_tile0 = rg * kMaxRowTiles;
             const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
-            if ((e = launch_stats_n(nqt, a, grid, st, marks)) != hipSuccess) return e;
+            e = paged ? launch_stats_n<true>(nqt, a, grid, st, marks) : launch_stats_n<false>(nqt, a, grid, st, marks);
+            if (e != hipSuccess) return e;
         }
         // Pass 1 leaves one partial per workgroup.  With few of them per sequence every pass-2 workgroup merges
         // its head's partials itself; a very long sequence has hundreds, and then one small launch merges them
@@ -742,7 +790,8 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         a.accumulate = rg > 0;
         if (rg > 0) a.zero = nullptr;  // cleared once, by the first launch (normalisers supplied: no combine step does it)
         const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
-        e = lse ? launch_score_n<true>(nqt, a, grid, st, marks) : launch_score_n<false>(nqt, a, grid, st, marks);
+        if (paged) e = lse ? launch_score_n<true, true>(nqt, a, grid, st, marks) : launch_score_n<false, true>(nqt, a, grid, st, marks);
+        else e = lse ? launch_score_n<true, false>(nqt, a, grid, st, marks) : launch_score_n<false, false>(nqt, a, grid, st, marks);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

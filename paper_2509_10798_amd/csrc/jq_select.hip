@@ -35,6 +35,7 @@ struct SelectArgs {
     // K_out,V_out [n_layers][TB][h_kv][d]
     const char* K; const char* V;
     char* K_out; char* V_out;
+    PageMap pm;  // where the rows of K and V live (dense or paged)
     SeqTab tab;
 };
 
@@ -406,7 +407,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         const uint32_t n_rows = min((uint32_t)kFinThreads, o_end - o0);
         const int part = threadIdx.x & 15;
         for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
-            const int64_t src = ((((int64_t)p.layer * a.T + a.tab.cu_seq[p.s] + slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+            const int64_t src = ((kv_row(a.pm, a.tab, a.T, p.layer, p.s, (int)slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
             const int64_t dst = ((((int64_t)p.layer * a.TB + a.tab.cu_bud[p.s] + o0 + rr) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
             const uint4 kv = *(const uint4*)(a.K + src);
             const uint4 vv = *(const uint4*)(a.V + src);
@@ -430,6 +431,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     a.cand = (uint2*)(ws + p.off_cand);
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.keep_first = p.keep_first; a.keep_last = p.keep_last;
+    a.pm = p.page_map();
     a.tab = p.tab;
     const unsigned n_prob = (unsigned)((int64_t)p.n_layers * p.n_seq * p.h_kv);
 

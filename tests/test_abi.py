@@ -117,3 +117,33 @@ def test_cu_seqlens_must_start_at_zero():
     cs = _CShape(1, 1, 4, 4, 2, 128, 7, 0.0, cu.ctypes.data_as(i32p), bud.ctypes.data_as(i32p))
     n = ctypes.c_size_t()
     assert L.jq_workspace_bytes(ctypes.byref(cs), ctypes.byref(n)) == -2
+
+
+def test_paged_descriptor_errors_come_before_any_launch():
+    from paper_2509_10798_amd.binding import _CPages
+    L = jq.lib()
+    sh = shape(seq_lens=[300, 64], budgets=[8, 8])
+    cs = sh.c_struct()
+    need = jq.workspace_bytes(sh)
+    big = 1 << 40
+    Q, K, V, Ko, Vo, ws, tab, sc = (big + (i << 30) for i in range(8))
+
+    def score(pg, table=tab, k=K):
+        cp = _CPages(*pg, table)
+        return L.jq_score_paged(ctypes.byref(cs), ctypes.byref(cp), Q, k, None, sc, ws, need, None)
+
+    def evict(pg, table=tab, ko=Ko):
+        cp = _CPages(*pg, table)
+        return L.jq_evict_paged(ctypes.byref(cs), ctypes.byref(cp), Q, K, V, None, ko, Vo, None, None, ws, need, None)
+
+    assert L.jq_score_paged(ctypes.byref(cs), None, Q, K, None, sc, ws, need, None) == -1          # no descriptor
+    assert score((64, 16, 5), table=None) == -1                                                    # no block table
+    assert score((48, 16, 8)) == -2 and score((16, 32, 32)) == -2 and score((1 << 17, 4, 1)) == -2  # page size
+    assert score((64, 0, 5)) == -2 and score((64, 16, 0)) == -2
+    assert score((64, 16, 4)) == -2                                     # 300 tokens need 5 pages of 64
+    assert score((65536, 1 << 20, 5)) == -4                             # pool beyond the 32-bit offset range
+    assert score((64, 16, 5), table=tab + 2) == -4                      # misaligned table
+    assert score((64, 16, 5), table=ws + 1024) == -6                    # table inside the workspace (aliasing is checked
+                                                                        # last, so this descriptor passed everything else)
+    assert evict((64, 16, 5), ko=K + 256) == -6                         # K_out inside the pool
+    assert evict((64, 16, 5), table=Ko) == -6                           # table inside an output

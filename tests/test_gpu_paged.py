@@ -1,0 +1,122 @@
+"""GPU parity of the paged-cache entry points: the same eviction (Section 4.3) when K and V live in pools of
+fixed-size pages behind a block table.  The oracle sees the dense tensors the pools were filled from."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2509_10798_amd as jq
+from parity import assert_kept_set_ok, assert_scores_close, from_dev_bf16, to_dev_bf16
+from workloads import bf16_bits_to_f64, make_workload, page_out
+
+pytestmark = pytest.mark.gpu
+
+
+def torch_():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def paged_inputs(w, page_size, seed=0, n_layers=None):
+    torch = torch_()
+    Q, K, V = w.assemble()
+    Kp, Vp, table = page_out(K, V, w.seq_lens, page_size, seed)
+    pages = jq.Pages(page_size=page_size, n_pages=Kp.shape[1], block_table=torch.from_numpy(table).cuda())
+    return Q, K, V, to_dev_bf16(Kp), to_dev_bf16(Vp), pages
+
+
+@pytest.mark.parametrize("seq_lens,page_size,n_layers", [
+    ([2048], 32, 1),            # one tile per page
+    ([1000], 64, 1),            # ragged tail inside the last page
+    ([517, 64, 3001], 256, 2),  # layers x ragged batch; a sequence shorter than a page
+    ([5000], 1024, 1),
+    ([33], 4096, 1),            # page far larger than the sequence
+])
+def test_score_paged_matches_oracle_and_dense(seq_lens, page_size, n_layers):
+    torch = torch_()
+    print("paged score case", seq_lens, page_size, n_layers, flush=True)
+    w = make_workload(1, seq_lens=seq_lens, budget=[1] * len(seq_lens), n_layers=n_layers)
+    Q, K, V, Kp, Vp, pages = paged_inputs(w, page_size, seed=page_size)
+    sh = jq.Shape(n_layers=n_layers, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv)
+    got = jq.score_paged(sh, pages, to_dev_bf16(Q), Kp)
+    dense = jq.score(sh, to_dev_bf16(Q), to_dev_bf16(K))
+    torch.cuda.synchronize()
+    assert torch.equal(got, dense)          # same tiles, same arithmetic, same order: only the addresses differ
+    got = got.cpu().numpy()
+    cu = w.cu_seqlens
+    for l in range(n_layers):
+        for s, L in enumerate(seq_lens):
+            ref = oracle.score(Q[l, s], K[l, cu[s]:cu[s + 1]])
+            assert_scores_close(got[l, :, cu[s]:cu[s + 1]], ref, w.n_q * w.group / L, "layer %d seq %d" % (l, s))
+
+
+def test_score_paged_with_supplied_normalisers():
+    torch = torch_()
+    w = make_workload(1, seq_lens=[1500, 300], budget=[1, 1], n_layers=1)
+    Q, K, V, Kp, Vp, pages = paged_inputs(w, 128, seed=5)
+    sh = jq.Shape(n_layers=1, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv)
+    # normalisers of a softmax that is a little wider than the prompt: log-sum-exp over the prompt plus log(1.25)
+    cu = w.cu_seqlens
+    lse = np.empty((1, 2, w.n_q, w.h_q), dtype=np.float32)
+    for s in range(2):
+        q, k = bf16_bits_to_f64(Q[0, s]), bf16_bits_to_f64(K[0, cu[s]:cu[s + 1]])
+        for h in range(w.h_q):
+            t = (q[:, h, :] @ k[:, h // w.group, :].T) / np.sqrt(128.0)
+            m = t.max(axis=1)
+            lse[0, s, :, h] = m + np.log(np.exp(t - m[:, None]).sum(axis=1)) + np.log(1.25)
+    lse_d = torch.from_numpy(lse).cuda()
+    got = jq.score_paged(sh, pages, to_dev_bf16(Q), Kp, lse=lse_d)
+    dense = jq.score(sh, to_dev_bf16(Q), to_dev_bf16(K), lse=lse_d)
+    torch.cuda.synchronize()
+    assert torch.equal(got, dense)
+    for s, L in enumerate(w.seq_lens):
+        ref = oracle.score_lse(Q[0, s], K[0, cu[s]:cu[s + 1]], lse[0, s].astype(np.float64))
+        assert_scores_close(got[0, :, cu[s]:cu[s + 1]].cpu().numpy(), ref, w.n_q * w.group / L, "seq %d" % s)
+
+
+@pytest.mark.parametrize("page_size", [32, 512])
+def test_evict_paged_matches_oracle_and_dense(page_size):
+    torch = torch_()
+    w = make_workload(1, seq_lens=[1500, 700], budget=[200, 64], n_layers=2)
+    Q, K, V, Kp, Vp, pages = paged_inputs(w, page_size, seed=page_size + 1)
+    sh = jq.Shape(n_layers=2, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets,
+                  keep_first=2, keep_last=8)
+    Qd = to_dev_bf16(Q)
+    Ko, Vo, idx, pooled = jq.evict_paged(sh, pages, Qd, Kp, Vp)
+    Ko1, Vo1, idx1, pooled1 = jq.evict(sh, Qd, to_dev_bf16(K), to_dev_bf16(V))
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled1) and torch.equal(idx, idx1)
+    assert torch.equal(Ko.view(torch.int16), Ko1.view(torch.int16)) and torch.equal(Vo.view(torch.int16), Vo1.view(torch.int16))
+    ref = oracle.evict_batch(Q, K, V, w.cu_seqlens, w.budgets, w.pool_k, keep_first=2, keep_last=8)
+    idx_h, Ko_h, Vo_h = idx.cpu().numpy(), from_dev_bf16(Ko), from_dev_bf16(Vo)
+    cu, cb = w.cu_seqlens, w.cu_budgets
+    for l in range(2):
+        for s in range(2):
+            rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], idx_h[l, :, cb[s]:cb[s + 1]])
+            np.testing.assert_array_equal(Ko_h[l, cb[s]:cb[s + 1]], rk)
+            np.testing.assert_array_equal(Vo_h[l, cb[s]:cb[s + 1]], rv)
+            assert_scores_close(pooled[l, :, cu[s]:cu[s + 1]].cpu().numpy(), ref["pooled"][l, :, cu[s]:cu[s + 1]],
+                                w.n_q * w.group / w.seq_lens[s])
+
+
+def test_evict_paged_very_long_sequence_takes_the_separate_gather():
+    # beyond the selection's LDS bitmaps the kept rows are gathered by the stand-alone copy kernel, which
+    # has to follow the block table as well
+    torch = torch_()
+    L, B = 660000, 300
+    rng = np.random.default_rng(9)
+    Q = rng.integers(0, 65536, (1, 1, 4, 2, 128)).astype(np.uint16) & np.uint16(0xBF7F)   # finite, modest magnitudes
+    K = rng.integers(0, 65536, (1, L, 1, 128)).astype(np.uint16) & np.uint16(0xBF7F)
+    V = rng.integers(0, 65536, (1, L, 1, 128)).astype(np.uint16)
+    Kp, Vp, table = page_out(K, V, [L], 2048, seed=3)
+    pages = jq.Pages(page_size=2048, n_pages=Kp.shape[1], block_table=torch.from_numpy(table).cuda())
+    sh = jq.Shape(n_layers=1, seq_lens=[L], n_q=4, h_q=2, h_kv=1, budgets=[B])
+    Qd = to_dev_bf16(Q)
+    Ko, Vo, idx, pooled = jq.evict_paged(sh, pages, Qd, to_dev_bf16(Kp), to_dev_bf16(Vp))
+    Ko1, Vo1, idx1, pooled1 = jq.evict(sh, Qd, to_dev_bf16(K), to_dev_bf16(V))
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled1) and torch.equal(idx, idx1)
+    assert torch.equal(Ko.view(torch.int16), Ko1.view(torch.int16)) and torch.equal(Vo.view(torch.int16), Vo1.view(torch.int16))
+    rk, rv = oracle.compact(K[0], V[0], np.ascontiguousarray(idx[0].cpu().numpy()))
+    np.testing.assert_array_equal(from_dev_bf16(Ko)[0], rk)
+    np.testing.assert_array_equal(from_dev_bf16(Vo)[0], rv)

@@ -2,7 +2,7 @@
 import numpy as np
 
 import oracle
-from workloads import CONFIGS, bf16_bits_to_f32, f32_to_bf16_bits, make_workload
+from workloads import CONFIGS, bf16_bits_to_f32, f32_to_bf16_bits, make_workload, page_out
 
 
 def test_bf16_round_to_nearest_even():
@@ -77,3 +77,25 @@ def test_spans_are_contiguous():
     assert len(pos) == 512
     runs = np.split(pos, np.where(np.diff(pos) != 1)[0] + 1)
     assert all(len(r) % 64 == 0 for r in runs)
+
+
+def test_page_out_round_trip():
+    rng = np.random.default_rng(5)
+    seq_lens = [100, 7, 260]
+    K = rng.integers(0, 60000, (2, sum(seq_lens), 3, 128)).astype(np.uint16)
+    V = rng.integers(0, 60000, K.shape).astype(np.uint16)
+    Kp, Vp, table = page_out(K, V, seq_lens, 64, seed=1)
+    assert Kp.shape == (2, 2 + 1 + 5 + 3, 64, 3, 128) and table.shape == (3, 5)
+    used = table[table >= 0]
+    assert len(set(used.tolist())) == used.size == 8                      # every page belongs to one place only
+    assert (table[1, 1:] == -1).all() and (table[0, 2:] == -1).all()
+    tok = 0
+    for s, L in enumerate(seq_lens):
+        for t in range(L):
+            np.testing.assert_array_equal(Kp[:, table[s, t // 64], t % 64], K[:, tok + t])
+            np.testing.assert_array_equal(Vp[:, table[s, t // 64], t % 64], V[:, tok + t])
+        tok += L
+    assert (Kp[:, table[1, 0], 7:] == 0x7FC0).all()                       # rows past a sequence's end are poisoned
+    a = page_out(K, V, seq_lens, 64, seed=1)[2]
+    b = page_out(K, V, seq_lens, 64, seed=2)[2]
+    assert np.array_equal(a, table) and not np.array_equal(b, table)

@@ -12,4 +12,5 @@ from .generate import (  # noqa: F401
     bf16_bits_to_f64,
     f32_to_bf16_bits,
     make_workload,
+    page_out,
 )

@@ -246,3 +246,32 @@ def make_workload(config_id: int, *, budget=None, seq_lens=None, n_layers=None, 
         d=int(c["d"]), pool_k=int(c["pool_k"]), plant=c["plant"], seed=seed, outliers=bool(c["outliers"]),
         densities=dens, outlier_channels=out_ch,
     )
+
+
+def page_out(K: np.ndarray, V: np.ndarray, seq_lens, page_size: int, seed: int = 0, spare_pages: int = 3):
+    """Lay dense K/V [nl, T, h_kv, d] (uint16) out as a paged cache.
+
+    Returns (K_pool, V_pool, block_table): pools [nl, n_pages, page_size, h_kv, d], block_table int32
+    [n_seq, max_pages].  Pages are handed out in a seeded random order, the same for every layer; page
+    rows past a sequence's end, and `spare_pages` pages that belong to no sequence, hold bf16 NaN patterns
+    (a consumer that reads them shows it); table entries past a sequence's last page are -1.
+    """
+    nl, T, h_kv, d = K.shape
+    seq_lens = [int(x) for x in seq_lens]
+    assert sum(seq_lens) == T
+    per_seq = [(L + page_size - 1) // page_size for L in seq_lens]
+    n_pages = sum(per_seq) + int(spare_pages)
+    order = np.random.default_rng([BASE_SEED, 77, int(seed)]).permutation(n_pages)
+    table = np.full((len(seq_lens), max(per_seq)), -1, dtype=np.int32)
+    Kp = np.full((nl, n_pages, page_size, h_kv, d), 0x7FC0, dtype=np.uint16)
+    Vp = np.full_like(Kp, 0x7FC0)
+    nxt, tok = 0, 0
+    for s, L in enumerate(seq_lens):
+        for i in range(per_seq[s]):
+            pg = int(order[nxt]); nxt += 1
+            table[s, i] = pg
+            n = min(page_size, L - i * page_size)
+            Kp[:, pg, :n] = K[:, tok + i * page_size: tok + i * page_size + n]
+            Vp[:, pg, :n] = V[:, tok + i * page_size: tok + i * page_size + n]
+        tok += L
+    return Kp, Vp, table
