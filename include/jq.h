@@ -12,6 +12,7 @@
  *                   Section 5.1, Baselines)
  *   jq_select_topk  top-B retention per KV head (Section 4.3)
  *   jq_compact      gather of the kept K/V rows into a dense pruned cache
+ *   jq_compact_inplace  the same, written over the front of K and V themselves
  *   jq_evict        all of the above for n_layers x n_seq problems in one call
  *   jq_score_lse, jq_evict_lse    the same with caller-supplied softmax normalisers
  *   jq_score_tail, jq_evict_tail  the same with the soft tokens' own keys in the softmax
@@ -153,6 +154,18 @@ int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx,
  * into that range (never dereferenced out of bounds). */
 int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_t* idx,
                void* K_out, void* V_out, void* stream);
+
+/* The pruned cache written over the front of the cache it was taken from (Section 4.3: decoding
+ * continues on the pruned cache, so a server can hand the rest of the memory back): after the call
+ *   K[l, cu_budgets[s]+b, g, :] = (old) K[l, cu_seqlens[s] + idx[l,g,cu_budgets[s]+b], g, :]
+ * for every kept row, likewise V; rows from sum(budgets) on are left as they were.  K and V keep
+ * their [n_layers, T, h_kv, d] strides.  Kept rows whose source lies inside the overwritten front are
+ * first copied to `ws` (DEVICE, 16-byte aligned, at least jq_compact_inplace_workspace_bytes), then
+ * every row is written, so no order between workgroups is assumed.  Indices are clamped as in
+ * jq_compact; idx must not overlap K, V or ws. */
+int jq_compact_inplace_workspace_bytes(const jq_shape* shape, size_t* bytes);
+int jq_compact_inplace(const jq_shape* shape, void* K, void* V, const int32_t* idx,
+                       void* ws, size_t ws_bytes, void* stream);
 
 /* Critical-KV hit rate (Eq. 6): for every (layer, sequence, KV head)
  *   rate[l,s,g] = |I_cur & I_ref| / |I_ref|

@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_evict", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
            "jq_copy_probe", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel", "jq_select_finalize_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.jq_pool.argtypes = [shp, vp, vp, vp]
         L.jq_select_topk.argtypes = [shp, vp, vp, vp, sz, vp]
         L.jq_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+        L.jq_compact_inplace_workspace_bytes.argtypes = [shp, ctypes.POINTER(sz)]
+        L.jq_compact_inplace.argtypes = [shp, vp, vp, vp, vp, sz, vp]
         L.jq_evict.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         pgp = ctypes.POINTER(_CPages)
         L.jq_score_paged.argtypes = [shp, pgp, vp, vp, vp, vp, vp, sz, vp]
@@ -209,6 +211,19 @@ def compact(shape: Shape, K, V, idx, K_out=None, V_out=None, stream=None):
     cs = shape.c_struct()
     _check(lib().jq_compact(ctypes.byref(cs), _ptr(K), _ptr(V), _ptr(idx), _ptr(K_out), _ptr(V_out), _stream(stream)), "jq_compact")
     return K_out, V_out
+
+
+def compact_inplace(shape: Shape, K, V, idx, ws=None, stream=None):
+    """Kept rows written over the front of K and V themselves (rows 0..TB-1 of every layer)."""
+    import torch
+    cs = shape.c_struct()
+    if ws is None:
+        n = ctypes.c_size_t(0)
+        _check(lib().jq_compact_inplace_workspace_bytes(ctypes.byref(cs), ctypes.byref(n)), "jq_compact_inplace_workspace_bytes")
+        ws = torch.empty(int(n.value), dtype=torch.uint8, device=K.device)
+    _check(lib().jq_compact_inplace(ctypes.byref(cs), _ptr(K), _ptr(V), _ptr(idx), _ptr(ws), ws.numel(), _stream(stream)),
+           "jq_compact_inplace")
+    return K, V
 
 
 def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_out=None, ws=None, stream=None,

@@ -264,6 +264,31 @@ int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_
     return launch_status(launch_compact(p, K, V, idx, K_out, V_out, (hipStream_t)stream));
 }
 
+int jq_compact_inplace_workspace_bytes(const jq_shape* shape, size_t* bytes) {
+    if (!bytes) return JQ_ERR_NULL;
+    Plan p;
+    const int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    *bytes = align_up(2 * kv_out_bytes(p));
+    return JQ_OK;
+}
+
+int jq_compact_inplace(const jq_shape* shape, void* K, void* V, const int32_t* idx, void* ws, size_t ws_bytes,
+                       void* stream) {
+    Plan p;
+    const int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if (!K || !V || !idx || !ws) return JQ_ERR_NULL;
+    if (misaligned(K, 16) || misaligned(V, 16) || misaligned(idx, 4)) return JQ_ERR_UNSUPPORTED;
+    const size_t need = 2 * kv_out_bytes(p);
+    if (misaligned(ws, 16) || ws_bytes < need) return JQ_ERR_WORKSPACE;
+    const size_t nin = kv_bytes(p);
+    if (overlaps(K, nin, V, nin) || overlaps(ws, need, K, nin) || overlaps(ws, need, V, nin) ||
+        overlaps(idx, idx_bytes(p), K, nin) || overlaps(idx, idx_bytes(p), V, nin) || overlaps(idx, idx_bytes(p), ws, need))
+        return JQ_ERR_ALIAS;
+    return launch_status(launch_compact_inplace(p, K, V, idx, ws, (hipStream_t)stream));
+}
+
 static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,
                       const void* k_tail, void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
                       size_t ws_bytes, void* stream, void* const* marks, const jq_pages* pages = nullptr,

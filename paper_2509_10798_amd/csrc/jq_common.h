@@ -126,6 +126,8 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
                          bool* gathered = nullptr);
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
                           hipStream_t st);
+// In place: kept rows land at the front of K / V themselves; `stage` holds 2 * n_layers * TB * h_kv rows.
+hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st);
 
 // `cu_ref_budgets`: n_seq + 1 prefix sums of the reference list lengths, `tb_ref` their total.
 hipError_t launch_hit_rate(const Plan& p, const int32_t* cu_ref_budgets, int64_t tb_ref, const int32_t* cur,

@@ -55,6 +55,63 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
                          dim3(kCompactThreads), 0, st, nullptr, -1, a);
 }
 
+// In-place variant: the kept rows of a layer land in rows 0..TB-1 of that layer's own K / V.  A kept row
+// whose source is one of those rows could be overwritten by another workgroup before it is read, so such
+// rows go through a staging buffer: launch 1 copies them out, launch 2 writes every kept row, taking it from
+// the staging buffer or from its (never overwritten) source beyond the front.
+struct InplaceArgs {
+    char* K; char* V;
+    char* stage;         // [2][n_layers][TB][h_kv][d] bf16: K rows, then V rows
+    const int32_t* idx;  // [n_layers][h_kv][TB], sequence-local
+    int32_t n_layers, h_kv;
+    int64_t T, TB;
+    SeqTab tab;
+};
+
+template <bool WRITE>
+__global__ __launch_bounds__(kCompactThreads) void jq_compact_inplace_kernel(InplaceArgs a) {
+    const int64_t n_items = (int64_t)a.n_layers * a.TB * a.h_kv;
+    const int64_t item = ((int64_t)blockIdx.x * kCompactThreads + threadIdx.x) / kLanesPerRow;
+    if (item >= n_items) return;
+    const int part = threadIdx.x % kLanesPerRow;
+    const int g = (int)(item % a.h_kv);
+    const int64_t rest = item / a.h_kv;
+    const int64_t tb = rest % a.TB;
+    const int layer = (int)(rest / a.TB);
+    const int s = find_seq(a.tab.cu_bud, a.tab.n_seq, tb);
+    const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
+    int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
+    j = min(max(j, 0), L - 1);
+    const int64_t src_row = (int64_t)a.tab.cu_seq[s] + j;  // within the layer
+    const bool staged = src_row < a.TB;                     // the source is a row that this call overwrites
+    const int64_t src = ((((int64_t)layer * a.T + src_row) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
+    const int64_t stg = item * (kHeadDim * 2) + part * 16;
+    const int64_t v_stage = n_items * (kHeadDim * 2);
+    if (!WRITE) {
+        if (!staged) return;
+        *(u32x4*)(a.stage + stg) = *(const u32x4*)(a.K + src);
+        *(u32x4*)(a.stage + v_stage + stg) = *(const u32x4*)(a.V + src);
+    } else {
+        const int64_t dst = ((((int64_t)layer * a.T + tb) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
+        const u32x4 kv = staged ? *(const u32x4*)(a.stage + stg) : *(const u32x4*)(a.K + src);
+        const u32x4 vv = staged ? *(const u32x4*)(a.stage + v_stage + stg) : *(const u32x4*)(a.V + src);
+        *(u32x4*)(a.K + dst) = kv;
+        *(u32x4*)(a.V + dst) = vv;
+    }
+}
+
+hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st) {
+    InplaceArgs a;
+    a.K = (char*)K; a.V = (char*)V; a.stage = (char*)stage; a.idx = idx;
+    a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
+    a.tab = p.tab;
+    const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
+    const dim3 grid((unsigned)((threads + kCompactThreads - 1) / kCompactThreads));
+    hipError_t e = launch_kernel(jq_compact_inplace_kernel<false>, grid, dim3(kCompactThreads), 0, st, nullptr, -1, a);
+    if (e != hipSuccess) return e;
+    return launch_kernel(jq_compact_inplace_kernel<true>, grid, dim3(kCompactThreads), 0, st, nullptr, -1, a);
+}
+
 // Critical-KV hit rate (paper Eq. 6): |I_cur & I_ref| / |I_ref| per (layer, sequence, KV head) for two kept
 // sets given as ascending position lists.  One workgroup per problem; every position of the reference
 // list is looked up in the current list by binary search.  Integer work; the quotient is the only rounding.

@@ -103,6 +103,15 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_copy_probe(K, K + 64, 1024, None) == -6 and L.jq_copy_probe(K, Ko, 24, None) == -2
     assert L.jq_compact(ctypes.byref(cs), K, V, ws, V, Vo, None) == -6
     assert L.jq_pool(ctypes.byref(cs), K, K, None) == -6
+    n_in = ctypes.c_size_t()
+    assert L.jq_compact_inplace_workspace_bytes(ctypes.byref(cs), ctypes.byref(n_in)) == 0
+    assert n_in.value == 2 * 8 * 2 * 128 * 2                                                       # K and V rows of the budget
+    assert L.jq_compact_inplace_workspace_bytes(ctypes.byref(cs), None) == -1
+    assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, None, n_in.value, None) == -1
+    assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, ws, n_in.value - 1, None) == -5
+    assert L.jq_compact_inplace(ctypes.byref(cs), K, K + 256, Ko, ws, n_in.value, None) == -6      # V inside K
+    assert L.jq_compact_inplace(ctypes.byref(cs), K, V, K + 512, ws, n_in.value, None) == -6       # idx inside K
+    assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, V + 1024, n_in.value, None) == -6      # staging inside V
     cs2 = shape(budgets=None).c_struct()
     assert L.jq_compact(ctypes.byref(cs2), K, V, ws, Ko, Vo, None) == -1                           # budgets required
     bad = _CShape(1, 1, 4, 4, 2, 128, 7, 0.0, ctypes.cast(None, ctypes.POINTER(ctypes.c_int32)),

@@ -235,6 +235,46 @@ def test_compact_is_bit_exact():
             np.testing.assert_array_equal(Vo[l, cb[s]:cb[s + 1]], rv)
 
 
+@pytest.mark.parametrize("seq_lens,budgets,mode", [
+    ([3000], [500], "random"),            # sources on both sides of the overwritten front
+    ([3000], [500], "front"),             # every source lies inside the front: all rows are staged
+    ([3000], [500], "back"),              # no source inside the front
+    ([900, 40, 2000], [300, 40, 700], "random"),   # a later sequence's rows land on an earlier sequence's sources
+    ([64], [64], "random"),               # everything kept: a permutation-free identity
+])
+def test_compact_inplace_matches_out_of_place_gather(seq_lens, budgets, mode):
+    torch = torch_()
+    rng = np.random.default_rng(43)
+    nl, h_kv, d = 2, 3, 128
+    T, TB = sum(seq_lens), sum(budgets)
+    K = rng.integers(0, 65536, (nl, T, h_kv, d)).astype(np.uint16)
+    V = rng.integers(0, 65536, (nl, T, h_kv, d)).astype(np.uint16)
+    idx = np.empty((nl, h_kv, TB), dtype=np.int32)
+    cb = np.concatenate([[0], np.cumsum(budgets)]); cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    for l in range(nl):
+        for g in range(h_kv):
+            for s, (L, B) in enumerate(zip(seq_lens, budgets)):
+                if mode == "front":
+                    pick = np.arange(B)
+                elif mode == "back":
+                    pick = np.arange(L - B, L)
+                else:
+                    pick = np.sort(rng.choice(L, size=B, replace=False))
+                idx[l, g, cb[s]:cb[s + 1]] = pick
+    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, budgets=budgets)
+    Kd, Vd = to_dev_bf16(K), to_dev_bf16(V)
+    jq.compact_inplace(sh, Kd, Vd, torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    Kh, Vh = from_dev_bf16(Kd), from_dev_bf16(Vd)
+    for l in range(nl):
+        for s in range(len(seq_lens)):
+            rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], idx[l, :, cb[s]:cb[s + 1]])
+            np.testing.assert_array_equal(Kh[l, cb[s]:cb[s + 1]], rk)
+            np.testing.assert_array_equal(Vh[l, cb[s]:cb[s + 1]], rv)
+    np.testing.assert_array_equal(Kh[:, TB:], K[:, TB:])        # the rest of the cache is untouched
+    np.testing.assert_array_equal(Vh[:, TB:], V[:, TB:])
+
+
 def test_sink_and_recent_window_retention_through_compact():
     # position-based retention (attention sinks + recent window, the StreamingLLM baseline of Section 5.1)
     # needs no scores: the caller writes the positions and jq_compact prunes the cache
