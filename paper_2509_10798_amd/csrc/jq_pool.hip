@@ -13,9 +13,10 @@
 namespace jq {
 
 constexpr int kPoolThreads = 256;
-constexpr int kPoolPerThread = 8;
-constexpr int kPoolBlockPos = kPoolThreads * kPoolPerThread;  // 2048 positions per block (8192 were slower: fewer
-                                                              // resident blocks hide less latency)
+constexpr int kPoolPerThread = 4;                              // a multiple of 4
+constexpr int kPoolBlockPos = kPoolThreads * kPoolPerThread;  // 1024 positions per block (2048 and 8192 were slower:
+                                                              // the kernel is one latency chain per block, and more,
+                                                              // shorter chains overlap better)
 constexpr int kPoolMaxHalo = 32;                               // (pool_k - 1) / 2 up to here uses the LDS path
 constexpr int kWinBins = 128;                                  // histogram window below the block's top bin
 constexpr int kWinCopies = 16;
@@ -73,8 +74,8 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
             }
         }
         __syncthreads();
-        // Thread t owns two runs of four consecutive positions, 4t.. and 1024 + 4t..: with the taps unrolled a
-        // run reads its 4 + 2r inputs as a few 16-byte LDS loads (lanes 16 B apart: no bank conflict) instead
+        // Thread t owns runs of four consecutive positions (4t.., then 4 * threads + 4t.., ...): with the taps unrolled
+        // a run reads its 4 + 2r inputs as a few 16-byte LDS loads (lanes 16 B apart: no bank conflict) instead
         // of 2r + 1 loads per output, and stores one 16-byte vector when the row allows it.
         uint32_t bin[kPoolPerThread];
         uint32_t top = 0;

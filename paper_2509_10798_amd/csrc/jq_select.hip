@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_stream_kernel(Select
 // fast path, step 1: scatter positions above / inside the level-1 threshold bin
 // ------------------------------------------------------------------------------------------------
 constexpr int kScatterThreads = 256;
-constexpr int kScatterPerThread = 16;
+constexpr int kScatterPerThread = 8;  // 2048 positions per block (4096: +1.5 us, 1024: +1.5 us on the 128K layer)
 constexpr int kScatterBlockPos = kScatterThreads * kScatterPerThread;
 
 __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(SelectArgs a) {
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(Sele
         }
         // one pair of global atomics per block: prefix sums inside the block, then a block base
         uint32_t total;
-        const uint32_t packed = n_s | (n_c << 16);  // at most 4096 per field
+        const uint32_t packed = n_s | (n_c << 16);  // at most kScatterBlockPos per field
         const uint32_t excl = block_scan_incl<kScatterThreads>(packed, tmp, &total) - packed;
         if (threadIdx.x == 0) {
             base[0] = (total & 0xFFFFu) ? atomicAdd(hist + kHistBins, total & 0xFFFFu) : 0u;
