@@ -106,6 +106,34 @@ def test_config3_mistral_layer_128k():
                                  from_dev_bf16(Ko)[0], from_dev_bf16(Vo)[0], "config 3")
 
 
+def test_config3_paged_cache_with_sinks_and_window():
+    # the headline layer again, out of a paged cache (256-token pages in random order) and with attention sinks
+    # and a local window forced into the kept set: bit-identical to the dense call, whose kept sets are
+    # checked against the oracle's forced selection on the oracle's own pooled scores
+    torch = torch_()
+    from workloads import page_out
+    w = make_workload(3)
+    Q, K, V = w.assemble()
+    kf, kl = 4, 32
+    sh = jq.Shape(n_layers=1, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets,
+                  keep_first=kf, keep_last=kl)
+    Qd, Kd, Vd = to_dev_bf16(Q), to_dev_bf16(K), to_dev_bf16(V)
+    Ko, Vo, idx, pooled = jq.evict(sh, Qd, Kd, Vd)
+    Kp, Vp, table = page_out(K, V, w.seq_lens, 256, seed=3)
+    pages = jq.Pages(page_size=256, n_pages=Kp.shape[1], block_table=torch.from_numpy(table).cuda())
+    Ko2, Vo2, idx2, pooled2 = jq.evict_paged(sh, pages, Qd, to_dev_bf16(Kp), to_dev_bf16(Vp))
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled2) and torch.equal(idx, idx2)
+    assert torch.equal(Ko.view(torch.int16), Ko2.view(torch.int16)) and torch.equal(Vo.view(torch.int16), Vo2.view(torch.int16))
+    check_properties_on_device(torch, w, Kd, Vd, Ko, Vo, idx, pooled)
+    ref_p = oracle.pool(oracle.score(Q[0, 0], K[0]), w.pool_k)
+    ref_idx = oracle.select_topk(ref_p, w.budgets[0], kf, kl)
+    idx_h = idx[0].cpu().numpy()
+    from parity import assert_kept_set_ok_keep
+    for g in range(w.h_kv):
+        assert_kept_set_ok_keep(ref_p[g], ref_idx[g], idx_h[g], kf, kl, "config 3 forced head %d" % g)
+
+
 def test_config4_thirty_two_layers():
     torch = torch_()
     w = make_workload(4)
