@@ -227,11 +227,18 @@ typedef struct jq_pages {
 int jq_score_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, const void* K_pool,
                    const float* lse, float* scores, void* ws, size_t ws_bytes, void* stream);
 
-/* jq_evict / jq_evict_lse on a paged cache (`lse` as above); the kept rows are gathered out of the
- * pools into the dense K_out / V_out. */
-int jq_evict_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, const void* K_pool,
-                   const void* V_pool, const float* lse, void* K_out, void* V_out, int32_t* idx_out,
-                   float* scores_out, void* ws, size_t ws_bytes, void* stream);
+/* jq_evict / jq_evict_lse on a paged cache (`lse` as above).  With `out_pages` NULL the kept rows are
+ * gathered out of the pools into the dense K_out / V_out [n_layers, sum budgets, h_kv, d].  Otherwise
+ * K_out / V_out are pools of their own, [n_layers, out_pages->n_pages, out_pages->page_size, h_kv, d],
+ * and kept row b of sequence s (0 <= b < budgets[s]) goes to row (b % page_size) of page
+ * out_pages->block_table[s, b / page_size]: the pruned cache is paged again and can be handed to the
+ * attention kernels as it is.  For the output the page size may be any power of two (1..65536), the pool may
+ * exceed 4 GiB, and max_pages_per_seq must cover ceil(budgets[s] / page_size); the output pools must not
+ * overlap the input pools (different pages of one pool are not supported: a kept row could land on a page
+ * that is still being read). */
+int jq_evict_paged(const jq_shape* shape, const jq_pages* pages, const jq_pages* out_pages, const void* Q,
+                   const void* K_pool, const void* V_pool, const float* lse, void* K_out, void* V_out,
+                   int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream);
 
 /* jq_evict with kernel timing (the measurement hook of the benchmark): `marks` is a
  * HOST array of JQ_TRACE_MARKS hipEvent_t (passed as void*), created by the caller.

@@ -75,7 +75,7 @@ def lib() -> ctypes.CDLL:
         L.jq_evict.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         pgp = ctypes.POINTER(_CPages)
         L.jq_score_paged.argtypes = [shp, pgp, vp, vp, vp, vp, vp, sz, vp]
-        L.jq_evict_paged.argtypes = [shp, pgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_evict_paged.argtypes = [shp, pgp, pgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_traced.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp), ctypes.c_int]
         L.jq_copy_probe.argtypes = [vp, vp, sz, vp]
         L.jq_status_string.argtypes = [ctypes.c_int]
@@ -292,14 +292,18 @@ def score_paged(shape: Shape, pages: Pages, Q, K_pool, lse=None, scores=None, ws
 
 
 def evict_paged(shape: Shape, pages: Pages, Q, K_pool, V_pool, lse=None, K_out=None, V_out=None, idx_out=None,
-                scores_out=None, ws=None, stream=None, want_idx=True, want_scores=True):
-    """Fused eviction on a paged cache.  Returns (K_out, V_out, idx_out, pooled scores); K_out / V_out are dense."""
+                scores_out=None, ws=None, stream=None, want_idx=True, want_scores=True, out_pages: Optional[Pages] = None):
+    """Fused eviction on a paged cache.  Returns (K_out, V_out, idx_out, pooled scores); K_out / V_out are dense, or
+    pools [n_layers, out_pages.n_pages, out_pages.page_size, h_kv, d] when `out_pages` describes a paged output."""
     import torch
     dev = K_pool.device
+    if K_out is None and out_pages is not None:
+        K_out = torch.zeros((shape.n_layers, out_pages.n_pages, out_pages.page_size, shape.h_kv, shape.d), dtype=K_pool.dtype,
+                            device=dev)
     if K_out is None:
         K_out = torch.empty((shape.n_layers, shape.TB, shape.h_kv, shape.d), dtype=K_pool.dtype, device=dev)
     if V_out is None:
-        V_out = torch.empty_like(K_out)
+        V_out = torch.zeros_like(K_out) if out_pages is not None else torch.empty_like(K_out)
     if idx_out is None and want_idx:
         idx_out = torch.empty((shape.n_layers, shape.h_kv, shape.TB), dtype=torch.int32, device=dev)
     if scores_out is None and want_scores:
@@ -307,7 +311,9 @@ def evict_paged(shape: Shape, pages: Pages, Q, K_pool, V_pool, lse=None, K_out=N
     if ws is None:
         ws = alloc_workspace(shape, dev)
     cs, cp = shape.c_struct(), pages.c_struct()
-    _check(lib().jq_evict_paged(ctypes.byref(cs), ctypes.byref(cp), _ptr(Q), _ptr(K_pool), _ptr(V_pool), _ptr(lse),
+    co = out_pages.c_struct() if out_pages is not None else None
+    _check(lib().jq_evict_paged(ctypes.byref(cs), ctypes.byref(cp), ctypes.byref(co) if co is not None else None, _ptr(Q),
+                                _ptr(K_pool), _ptr(V_pool), _ptr(lse),
                                 _ptr(K_out), _ptr(V_out), _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(),
                                 _stream(stream)), "jq_evict_paged")
     return K_out, V_out, idx_out, scores_out

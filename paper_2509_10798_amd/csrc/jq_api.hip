@@ -139,6 +139,24 @@ int apply_pages(const jq_pages* pg, Plan* p) {
     return JQ_OK;
 }
 
+// The same for the description of a paged output (no tile or 32-bit-offset constraint there).
+int apply_out_pages(const jq_pages* pg, Plan* p) {
+    if (!pg || !pg->block_table) return JQ_ERR_NULL;
+    if (pg->page_size < 1 || pg->page_size > 65536 || (pg->page_size & (pg->page_size - 1)) != 0) return JQ_ERR_SHAPE;
+    if (pg->n_pages < 1 || pg->max_pages_per_seq < 1) return JQ_ERR_SHAPE;
+    for (int s = 0; s < p->n_seq; ++s) {
+        const int64_t b = p->tab.cu_bud[s + 1] - p->tab.cu_bud[s];
+        if ((b + pg->page_size - 1) / pg->page_size > pg->max_pages_per_seq) return JQ_ERR_SHAPE;
+    }
+    if (misaligned(pg->block_table, 4)) return JQ_ERR_UNSUPPORTED;
+    p->out_map.block_table = pg->block_table;
+    p->out_map.page_shift = 0;
+    while ((1 << p->out_map.page_shift) < pg->page_size) ++p->out_map.page_shift;
+    p->out_map.n_pages = pg->n_pages;
+    p->out_map.max_pages = pg->max_pages_per_seq;
+    return JQ_OK;
+}
+
 int check_ws(const Plan& p, const void* ws, size_t ws_bytes) {
     if (!ws) return JQ_ERR_NULL;
     if (misaligned(ws, 16) || ws_bytes < p.ws_bytes) return JQ_ERR_WORKSPACE;
@@ -150,7 +168,11 @@ size_t kv_bytes(const Plan& p) {  // bytes of K (or V) as the caller holds it: d
     return (size_t)p.n_layers * rows * p.h_kv * p.d * 2;
 }
 size_t table_bytes(const Plan& p) { return p.block_table ? (size_t)p.n_seq * p.max_pages * 4 : 0; }
-size_t kv_out_bytes(const Plan& p) { return (size_t)p.n_layers * p.TB * p.h_kv * p.d * 2; }
+size_t kv_out_bytes(const Plan& p) {  // bytes of K_out (or V_out): dense kept rows, or the output pools of all layers
+    const size_t rows = p.out_map.block_table ? ((size_t)p.out_map.n_pages << p.out_map.page_shift) : (size_t)p.TB;
+    return (size_t)p.n_layers * rows * p.h_kv * p.d * 2;
+}
+size_t out_table_bytes(const Plan& p) { return p.out_map.block_table ? (size_t)p.n_seq * p.out_map.max_pages * 4 : 0; }
 size_t q_bytes(const Plan& p) { return (size_t)p.n_layers * p.n_seq * p.n_q * p.h_q * p.d * 2; }
 size_t score_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.T * 4; }
 size_t idx_bytes(const Plan& p) { return (size_t)p.n_layers * p.h_kv * p.TB * 4; }
@@ -292,11 +314,12 @@ int jq_compact_inplace(const jq_shape* shape, void* K, void* V, const int32_t* i
 static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,
                       const void* k_tail, void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
                       size_t ws_bytes, void* stream, void* const* marks, const jq_pages* pages = nullptr,
-                      bool paged = false) {
+                      bool paged = false, const jq_pages* out_pages = nullptr) {
     Plan p;
     int rc = make_plan(shape, true, &p);
     if (rc != JQ_OK) return rc;
     if (paged && (rc = apply_pages(pages, &p)) != JQ_OK) return rc;
+    if (out_pages && (rc = apply_out_pages(out_pages, &p)) != JQ_OK) return rc;
     if (!Q || !K || !V || !K_out || !V_out) return JQ_ERR_NULL;
     if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(K_out, 16) || misaligned(V_out, 16) ||
@@ -304,13 +327,13 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
         (k_tail && misaligned(k_tail, 16)))
         return JQ_ERR_UNSUPPORTED;
     const size_t nin = kv_bytes(p), nout = kv_out_bytes(p);
-    const void* ins[5] = {Q, K, V, lse ? (const void*)lse : k_tail, p.block_table};
-    const size_t in_bytes[5] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p), table_bytes(p)};
+    const void* ins[6] = {Q, K, V, lse ? (const void*)lse : k_tail, p.block_table, p.out_map.block_table};
+    const size_t in_bytes[6] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p), table_bytes(p), out_table_bytes(p)};
     const void* outs[5] = {K_out, V_out, idx_out, scores_out, ws};
     const size_t out_bytes[5] = {nout, nout, idx_bytes(p), score_bytes(p), p.ws_bytes};
     for (int o = 0; o < 5; ++o) {
         if (!outs[o]) continue;
-        for (int i = 0; i < 5; ++i)
+        for (int i = 0; i < 6; ++i)
             if (ins[i] && overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return JQ_ERR_ALIAS;
         for (int o2 = o + 1; o2 < 5; ++o2)
             if (outs[o2] && overlaps(outs[o], out_bytes[o], outs[o2], out_bytes[o2])) return JQ_ERR_ALIAS;
@@ -354,11 +377,11 @@ int jq_score_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, 
     return score_impl(shape, Q, K_pool, lse, nullptr, false, scores, ws, ws_bytes, stream, pages, true);
 }
 
-int jq_evict_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, const void* K_pool, const void* V_pool,
-                   const float* lse, void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
-                   size_t ws_bytes, void* stream) {
+int jq_evict_paged(const jq_shape* shape, const jq_pages* pages, const jq_pages* out_pages, const void* Q, const void* K_pool,
+                   const void* V_pool, const float* lse, void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
+                   void* ws, size_t ws_bytes, void* stream) {
     return evict_impl(shape, Q, K_pool, V_pool, lse, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream,
-                      nullptr, pages, true);
+                      nullptr, pages, true, out_pages);
 }
 
 int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,

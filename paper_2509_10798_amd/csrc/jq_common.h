@@ -54,6 +54,7 @@ struct Plan {
     int64_t T, TB;
     SeqTab tab;
     PageMap page_map() const { return PageMap{block_table, page_shift, n_pages, max_pages}; }
+    PageMap out_map;      // where the pruned cache goes (block_table null: dense [n_layers][TB] rows)
     void* const* marks;   // host only: nullptr, or 2 * kTraceKernels events (start, stop) for jq_evict_traced
     // workspace layout (byte offsets, 256-aligned)
     size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
@@ -75,10 +76,11 @@ __device__ inline uint32_t sortable_key(float x) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// Row (in units of token rows, over all layers) of token `pos` of sequence `s`.  A table entry outside the pool is
-// clamped into it.
-__device__ inline int64_t kv_row(const PageMap& pm, const SeqTab& tab, int64_t T, int layer, int s, int pos) {
-    if (!pm.block_table) return (int64_t)layer * T + tab.cu_seq[s] + pos;
+// Row (in units of token rows, over all layers) of token `pos` of sequence `s`; `cu` holds the sequences' dense
+// offsets (token offsets for the cache, kept-row offsets for the pruned cache) and T their total.  A table entry
+// outside the pool is clamped into it.
+__device__ inline int64_t kv_row(const PageMap& pm, const int32_t* cu, int64_t T, int layer, int s, int pos) {
+    if (!pm.block_table) return (int64_t)layer * T + cu[s] + pos;
     const int32_t e = pm.block_table[(int64_t)s * pm.max_pages + (pos >> pm.page_shift)];
     const int64_t page = (int64_t)layer * pm.n_pages + min(max(e, 0), pm.n_pages - 1);
     return (page << pm.page_shift) + (pos & ((1 << pm.page_shift) - 1));

@@ -13,7 +13,8 @@ struct CompactArgs {
     const int32_t* idx;  // [n_layers][h_kv][TB], sequence-local
     int32_t n_layers, h_kv;
     int64_t T, TB;
-    PageMap pm;  // where the rows of K and V live (dense or paged)
+    PageMap pm;      // where the rows of K and V live (dense or paged)
+    PageMap pm_out;  // where the kept rows go
     SeqTab tab;
 };
 
@@ -34,8 +35,8 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_kernel(CompactArgs
     const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
     int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
     j = min(max(j, 0), L - 1);  // never read outside the sequence
-    const int64_t src = ((kv_row(a.pm, a.tab, a.T, layer, s, j) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
-    const int64_t dst = item * (kHeadDim * 2) + part * 16;
+    const int64_t src = ((kv_row(a.pm, a.tab.cu_seq, a.T, layer, s, j) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
+    const int64_t dst = ((kv_row(a.pm_out, a.tab.cu_bud, a.TB, layer, s, (int)(tb - a.tab.cu_bud[s])) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
     const u32x4 kv = *(const u32x4*)(a.K + src);
     const u32x4 vv = *(const u32x4*)(a.V + src);
     *(u32x4*)(a.K_out + dst) = kv;
@@ -49,6 +50,7 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
     a.idx = idx;
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.pm = p.page_map();
+    a.pm_out = p.out_map;
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
     return launch_kernel(jq_compact_kernel, dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads)),

@@ -35,7 +35,8 @@ struct SelectArgs {
     // K_out,V_out [n_layers][TB][h_kv][d]
     const char* K; const char* V;
     char* K_out; char* V_out;
-    PageMap pm;  // where the rows of K and V live (dense or paged)
+    PageMap pm;      // where the rows of K and V live (dense or paged)
+    PageMap pm_out;  // where the kept rows go
     SeqTab tab;
 };
 
@@ -297,12 +298,25 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
     for (int e = 0; e < kFinCache; ++e)
         if (threadIdx.x + e * kFinThreads >= n_cand) cc[e].y = 0xFFFFFFFFu;  // position 0xFFFFFFFF marks "none"
     const uint32_t spill0 = kFinCache * kFinThreads;
+    // the same for the head of the "sure" list (its storage spans B entries)
+    constexpr int kSureCache = 4;
+    int32_t sc[kSureCache];
+#pragma unroll
+    for (int e = 0; e < kSureCache; ++e) {
+        const uint32_t i = threadIdx.x + e * kFinThreads;
+        sc[e] = i < p.B ? sure[i] : 0;
+    }
 
     for (int w = threadIdx.x; w < words; w += kFinThreads) { keep[w] = 0; ties[w] = 0; }
     for (int b = threadIdx.x; b < 3072; b += kFinThreads) bins2[b] = 0;  // both histograms
     __syncthreads();
 
-    for (uint32_t i = threadIdx.x; i < n_sure; i += kFinThreads) {
+#pragma unroll
+    for (int e = 0; e < kSureCache; ++e) {
+        const uint32_t j = (uint32_t)sc[e];
+        if (threadIdx.x + e * kFinThreads < n_sure && j < (uint32_t)p.L) atomicOr(&keep[j >> 5], 1u << (j & 31));
+    }
+    for (uint32_t i = kSureCache * kFinThreads + threadIdx.x; i < n_sure; i += kFinThreads) {
         const uint32_t j = (uint32_t)sure[i];
         if (j < (uint32_t)p.L) atomicOr(&keep[j >> 5], 1u << (j & 31));
     }
@@ -407,8 +421,8 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         const uint32_t n_rows = min((uint32_t)kFinThreads, o_end - o0);
         const int part = threadIdx.x & 15;
         for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
-            const int64_t src = ((kv_row(a.pm, a.tab, a.T, p.layer, p.s, (int)slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
-            const int64_t dst = ((((int64_t)p.layer * a.TB + a.tab.cu_bud[p.s] + o0 + rr) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+            const int64_t src = ((kv_row(a.pm, a.tab.cu_seq, a.T, p.layer, p.s, (int)slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+            const int64_t dst = ((kv_row(a.pm_out, a.tab.cu_bud, a.TB, p.layer, p.s, (int)(o0 + rr)) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
             const uint4 kv = *(const uint4*)(a.K + src);
             const uint4 vv = *(const uint4*)(a.V + src);
             *(uint4*)(a.K_out + dst) = kv;
@@ -432,6 +446,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.keep_first = p.keep_first; a.keep_last = p.keep_last;
     a.pm = p.page_map();
+    a.pm_out = p.out_map;
     a.tab = p.tab;
     const unsigned n_prob = (unsigned)((int64_t)p.n_layers * p.n_seq * p.h_kv);
 

@@ -141,9 +141,10 @@ def test_paged_descriptor_errors_come_before_any_launch():
         cp = _CPages(*pg, table)
         return L.jq_score_paged(ctypes.byref(cs), ctypes.byref(cp), Q, k, None, sc, ws, need, None)
 
-    def evict(pg, table=tab, ko=Ko):
+    def evict(pg, table=tab, ko=Ko, out=None):
         cp = _CPages(*pg, table)
-        return L.jq_evict_paged(ctypes.byref(cs), ctypes.byref(cp), Q, K, V, None, ko, Vo, None, None, ws, need, None)
+        co = ctypes.byref(_CPages(*out)) if out is not None else None
+        return L.jq_evict_paged(ctypes.byref(cs), ctypes.byref(cp), co, Q, K, V, None, ko, Vo, None, None, ws, need, None)
 
     assert L.jq_score_paged(ctypes.byref(cs), None, Q, K, None, sc, ws, need, None) == -1          # no descriptor
     assert score((64, 16, 5), table=None) == -1                                                    # no block table
@@ -156,3 +157,10 @@ def test_paged_descriptor_errors_come_before_any_launch():
                                                                         # last, so this descriptor passed everything else)
     assert evict((64, 16, 5), ko=K + 256) == -6                         # K_out inside the pool
     assert evict((64, 16, 5), table=Ko) == -6                           # table inside an output
+    otab = big + (9 << 30)
+    assert evict((64, 16, 5), out=(16, 4, 1, None)) == -1               # output descriptor without a table
+    assert evict((64, 16, 5), out=(24, 4, 1, otab)) == -2               # page size not a power of two
+    assert evict((64, 16, 5), out=(4, 4, 1, otab)) == -2                # budgets of 8 need 2 pages of 4
+    assert evict((64, 16, 5), out=(4, 4, 2, otab + 2)) == -4            # misaligned output table
+    assert evict((64, 16, 5), out=(4, 4, 2, Ko + 64)) == -6             # output table inside the output pool
+    assert evict((64, 16, 5), out=(4, 1 << 20, 2, otab), ko=K - (1 << 29)) == -6   # a large output pool reaches into K

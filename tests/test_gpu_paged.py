@@ -120,3 +120,35 @@ def test_evict_paged_very_long_sequence_takes_the_separate_gather():
     rk, rv = oracle.compact(K[0], V[0], np.ascontiguousarray(idx[0].cpu().numpy()))
     np.testing.assert_array_equal(from_dev_bf16(Ko)[0], rk)
     np.testing.assert_array_equal(from_dev_bf16(Vo)[0], rv)
+
+
+@pytest.mark.parametrize("out_page", [1, 16, 256])
+def test_evict_paged_into_a_paged_pruned_cache(out_page):
+    # the kept rows land in pages again: read back through the output table they are the dense pruned cache
+    torch = torch_()
+    w = make_workload(1, seq_lens=[1500, 700], budget=[200, 70], n_layers=2)
+    Q, K, V, Kp, Vp, pages = paged_inputs(w, 64, seed=11)
+    sh = jq.Shape(n_layers=2, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    Qd = to_dev_bf16(Q)
+    Ko, Vo, idx, pooled = jq.evict_paged(sh, pages, Qd, Kp, Vp)                       # dense output
+    per_seq = [(b + out_page - 1) // out_page for b in w.budgets]
+    n_out = sum(per_seq) + 2
+    order = np.random.default_rng(12).permutation(n_out)
+    otab = np.full((2, max(per_seq)), -1, dtype=np.int32)
+    nxt = 0
+    for s in range(2):
+        otab[s, :per_seq[s]] = order[nxt:nxt + per_seq[s]]; nxt += per_seq[s]
+    out_pages = jq.Pages(page_size=out_page, n_pages=n_out, block_table=torch.from_numpy(otab).cuda())
+    Kop, Vop, idx2, pooled2 = jq.evict_paged(sh, pages, Qd, Kp, Vp, out_pages=out_pages)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(pooled, pooled2)
+    Ko_h, Vo_h, Kop_h, Vop_h = from_dev_bf16(Ko), from_dev_bf16(Vo), from_dev_bf16(Kop), from_dev_bf16(Vop)
+    used = np.zeros((n_out, out_page), dtype=bool)
+    cb = w.cu_budgets
+    for s in range(2):
+        for b in range(w.budgets[s]):
+            pg, r = otab[s, b // out_page], b % out_page
+            np.testing.assert_array_equal(Kop_h[:, pg, r], Ko_h[:, cb[s] + b])
+            np.testing.assert_array_equal(Vop_h[:, pg, r], Vo_h[:, cb[s] + b])
+            used[pg, r] = True
+    assert not Kop_h[:, ~used].any() and not Vop_h[:, ~used].any()                      # nothing else was written
