@@ -224,6 +224,49 @@ int jqo_score_tail(int n_q, int h_q, int h_kv, int d, long L, double scale, cons
 }
 
 /*
+ * The same map when the queries are the prompt's OWN last n_q tokens -- the observation window of the
+ * window-query baselines of Section 5.1 (H2O as implemented there, SnapKV, PyramidKV): K holds all L
+ * prompt keys, its last n_q rows being the window tokens' keys, Q the window tokens' queries.  Window token i
+ * sits at position w_i = L - n_q + i and, the model being causal, attends to positions 0..w_i only:
+ *
+ *   Z[h,i]     = sum_{j <= w_i} exp(scale * Q[i,h,:] . K[j,g,:])
+ *   score[g,j] = sum_{h in group g} sum_i exp(scale * Q[i,h,:] . K[j,g,:]) / Z[h,i]   for j < L - n_q
+ *   score[g,j] = 0                                                                    for the window itself
+ *
+ * (the window's own positions are observers, not candidates: they are kept unconditionally).
+ */
+int jqo_score_window(int n_q, int h_q, int h_kv, int d, long L, double scale, const uint16_t* Q, const uint16_t* K,
+                     double* score) {
+    if (n_q < 1 || h_q < 1 || h_kv < 1 || d < 1 || L < n_q || h_q % h_kv != 0 || !Q || !K || !score) return -1;
+    const int G = h_q / h_kv;
+    const long P = L - n_q;  /* prefix length */
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
+    for (size_t x = 0; x < (size_t)h_kv * (size_t)L; ++x) score[x] = 0.0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int g = 0; g < h_kv; ++g) {
+        double* s = (double*)malloc(sizeof(double) * (size_t)L);
+        for (int hh = 0; hh < G && s; ++hh)
+            for (int i = 0; i < n_q; ++i) {
+                const int h = g * G + hh;
+                const long last = P + i;  /* the row's last visible key (itself) */
+                const uint16_t* q = Q + ((size_t)i * h_q + h) * d;
+                double m = -INFINITY, z = 0.0;
+                for (long j = 0; j <= last; ++j) {
+                    const uint16_t* k = K + ((size_t)j * h_kv + g) * d;
+                    double acc = 0.0;
+                    for (int c = 0; c < d; ++c) acc += bf16_to_f64(q[c]) * bf16_to_f64(k[c]);
+                    s[j] = acc * scale;
+                    if (s[j] > m) m = s[j];
+                }
+                for (long j = 0; j <= last; ++j) z += exp(s[j] - m);
+                for (long j = 0; j < P; ++j) score[(size_t)g * L + j] += exp(s[j] - m) / z;
+            }
+        free(s);
+    }
+    return 0;
+}
+
+/*
  * 1-D average pooling of one head's scores ("pooling configurations",
  * Section 5.1 baselines paragraph).  Reading: stride 1, same-length output,
  * zeros outside [0, L), divisor always pool_k (so the first and last

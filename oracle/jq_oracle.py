@@ -38,6 +38,8 @@ def _load():
         lib.jqo_score.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p]
         lib.jqo_score_lse.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p, f64p]
         lib.jqo_score_tail.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, u16p, f64p]
+        lib.jqo_score_window.argtypes = [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_double, u16p, u16p, f64p]
+        lib.jqo_score_window.restype = ctypes.c_int
         lib.jqo_map_mse.argtypes = [ctypes.c_long, ctypes.c_int, ctypes.c_double, ctypes.c_double, f64p, f64p, f64p]
         lib.jqo_map_mse.restype = ctypes.c_int
         lib.jqo_pool.argtypes = [ctypes.c_long, ctypes.c_int, f64p, f64p]
@@ -101,6 +103,20 @@ def score_tail(Q: np.ndarray, K: np.ndarray, K_tail: np.ndarray, scale: float = 
     return out
 
 
+def score_window(Q: np.ndarray, K: np.ndarray, scale: float = 0.0) -> np.ndarray:
+    """Scores of a prompt under its own last n_q tokens (causal inside the window; the window's own positions get 0).
+    Q [n_q,h_q,d], K [L,h_kv,d] uint16 bf16 bits with the window's keys as its last n_q rows -> [h_kv, L] float64."""
+    Q = np.ascontiguousarray(Q, dtype=np.uint16)
+    K = np.ascontiguousarray(K, dtype=np.uint16)
+    n_q, h_q, d = Q.shape
+    L, h_kv, d2 = K.shape
+    if d != d2:
+        raise ValueError("head dimension mismatch")
+    out = np.empty((h_kv, L), dtype=np.float64)
+    _check(_load().jqo_score_window(n_q, h_q, h_kv, d, L, float(scale), Q, K, out), "score_window")
+    return out
+
+
 def pool(scores: np.ndarray, pool_k: int) -> np.ndarray:
     """scores [h_kv, L] (or [L]) float64 -> pooled, same shape."""
     s = np.ascontiguousarray(scores, dtype=np.float64)
@@ -142,12 +158,15 @@ def compact(K: np.ndarray, V: np.ndarray, idx: np.ndarray):
 
 
 def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None, K_tail=None, keep_first: int = 0,
-          keep_last: int = 0):
+          keep_last: int = 0, window: bool = False):
     """One (layer, sequence): score -> pool -> top-B -> gather.  Returns a dict.
 
     With `lse` the scores are the slice-of-a-wider-softmax variant (score_lse), with `K_tail` the
     variant whose softmax also covers the soft tokens' own keys (score_tail)."""
-    if lse is not None:
+    if window:  # the queries are the prompt's own last n_q tokens, which are always kept
+        s = score_window(Q, K, scale)
+        keep_last = max(keep_last, Q.shape[0])
+    elif lse is not None:
         s = score_lse(Q, K, lse, scale)
     elif K_tail is not None:
         s = score_tail(Q, K, K_tail, scale)
@@ -159,7 +178,8 @@ def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None, K_tail=Non
     return {"scores": s, "pooled": p, "idx": idx, "K_out": Ko, "V_out": Vo}
 
 
-def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0, keep_first: int = 0, keep_last: int = 0):
+def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0, keep_first: int = 0, keep_last: int = 0,
+                window: bool = False):
     """Layers x ragged sequences, one problem at a time.
 
     Q [nl,n_seq,n_q,h_q,d], K/V [nl,T,h_kv,d] uint16.  Returns pooled [nl,h_kv,T],
@@ -175,7 +195,7 @@ def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0, k
     for l in range(nl):
         for s in range(len(cu) - 1):
             r = evict(Q[l, s], K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], int(budgets[s]), pool_k, scale,
-                      keep_first=keep_first, keep_last=keep_last)
+                      keep_first=keep_first, keep_last=keep_last, window=window)
             scores[l, :, cu[s]:cu[s + 1]] = r["scores"]
             pooled[l, :, cu[s]:cu[s + 1]] = r["pooled"]
             idx[l, :, cb[s]:cb[s + 1]] = r["idx"]

@@ -278,3 +278,58 @@ def test_score_tail_rejects_wrong_shape():
     Q = np.zeros((2, 2, 4), dtype=np.uint16); K = np.zeros((3, 2, 4), dtype=np.uint16)
     with pytest.raises(ValueError):
         oracle.score_tail(Q, K, np.zeros((3, 2, 4), dtype=np.uint16))
+
+
+# ---------------------------------------------------------------- the prompt's own last tokens as queries (observation window)
+def test_score_window_hand_worked_powers_of_two(golden_dir):
+    # the hand-worked tail case read as ONE key tensor: prompt keys (0, 1) followed by the window's keys (2, 0)
+    want = np.loadtxt(os.path.join(golden_dir, "softmax_with_soft_token_tail.txt"))
+    q = bits([[[1.0]], [[1.0]]])
+    k = bits([[[0.0]], [[1.0]], [[2.0]], [[0.0]]])
+    got = oracle.score_window(q, k, scale=math.log(2.0))
+    np.testing.assert_allclose(got[0, :2], want, rtol=1e-15)
+    np.testing.assert_array_equal(got[0, 2:], [0.0, 0.0])             # the window's own positions are not scored
+
+
+def test_score_window_equals_the_tail_variant_on_the_split_keys():
+    rng = np.random.default_rng(31)
+    n_q, h_q, h_kv, d, L = 5, 6, 2, 8, 40
+    Q, K = rand_bits(rng, (n_q, h_q, d), 1.5), rand_bits(rng, (L, h_kv, d))
+    got = oracle.score_window(Q, K)
+    np.testing.assert_allclose(got[:, :L - n_q], oracle.score_tail(Q, K[:L - n_q], K[L - n_q:]), rtol=1e-12)
+    assert not got[:, L - n_q:].any()
+
+
+def test_score_window_matches_numpy_with_a_causal_mask():
+    rng = np.random.default_rng(32)
+    n_q, h_q, h_kv, d, L = 4, 4, 2, 8, 21
+    Q, K = rand_bits(rng, (n_q, h_q, d), 1.5), rand_bits(rng, (L, h_kv, d))
+    s = numpy_logits(Q, K)                                            # [n_q, h_q, L]
+    pos = np.arange(L)[None, None, :]
+    visible = pos <= (L - n_q + np.arange(n_q))[:, None, None]
+    e = np.where(visible, np.exp(s), 0.0)
+    p = e / e.sum(axis=2, keepdims=True)
+    want = p.sum(axis=0).reshape(h_kv, h_q // h_kv, L).sum(axis=1)
+    want[:, L - n_q:] = 0.0
+    np.testing.assert_allclose(oracle.score_window(Q, K), want, rtol=1e-12)
+
+
+def test_score_window_single_query_is_the_plain_softmax_and_later_keys_stay_invisible():
+    rng = np.random.default_rng(33)
+    Q, K = rand_bits(rng, (1, 4, 16)), rand_bits(rng, (30, 2, 16))
+    np.testing.assert_allclose(oracle.score_window(Q, K)[:, :29], oracle.score(Q, K)[:, :29], rtol=1e-12)
+    # three window tokens: the first two rows never see the last key
+    Q3 = rand_bits(rng, (3, 4, 16))
+    base = oracle.score_window(Q3[:2], K[:29])                        # window = positions 27, 28
+    K2 = K.copy(); K2[29] = bits(rng.standard_normal((2, 16)).astype(np.float32) * 4)
+    a, b = oracle.score_window(Q3, K), oracle.score_window(Q3, K2)    # window = positions 27, 28, 29
+    only_last_a = a[:, :27] - base[:, :27]
+    only_last_b = b[:, :27] - base[:, :27]
+    assert not np.allclose(only_last_a, only_last_b)                  # the last row does see its own key ...
+    assert (only_last_a > 0).all() and (only_last_b > 0).all()        # ... and the first two rows are unchanged by it
+
+
+def test_score_window_rejects_more_queries_than_keys():
+    Q = np.zeros((5, 2, 4), dtype=np.uint16); K = np.zeros((3, 2, 4), dtype=np.uint16)
+    with pytest.raises(ValueError):
+        oracle.score_window(Q, K)
