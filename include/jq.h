@@ -96,6 +96,14 @@ typedef struct jq_shape {
                                /* and the local window of the Section 5.1 baselines); they     */
                                /* count towards the budget: keep_first + keep_last <=          */
                                /* budgets[s].  Read by jq_select_topk and jq_evict* only.      */
+    int32_t window;            /* 0: the queries are soft tokens appended after the prompt (the */
+                               /* paper's method).  1: the queries are the prompt's OWN last    */
+                               /* n_q tokens (the observation window of the window-query        */
+                               /* baselines of Section 5.1): K holds their keys as the last n_q */
+                               /* rows of every sequence (n_q <= L_s), query i attends to       */
+                               /* positions 0 .. L_s - n_q + i only (causal), the window's own  */
+                               /* positions score 0 and are always kept (keep_last counts as    */
+                               /* at least n_q).  Not with jq_score_tail / jq_evict_tail.       */
 } jq_shape;
 
 /* Bytes of device workspace that jq_score, jq_select_topk and jq_evict need for

@@ -28,6 +28,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     if (sh->pool_k < 1 || sh->pool_k % 2 == 0) return JQ_ERR_SHAPE;
     if (!std::isfinite(sh->scale) || sh->scale < 0.0f) return JQ_ERR_SHAPE;
     if (sh->keep_first < 0 || sh->keep_last < 0) return JQ_ERR_SHAPE;
+    if (sh->window != 0 && sh->window != 1) return JQ_ERR_SHAPE;
     if (sh->n_seq > JQ_MAX_SEQ) return JQ_ERR_UNSUPPORTED;
     if (sh->d != kHeadDim) return JQ_ERR_UNSUPPORTED;
     if (sh->n_layers > 65535 || sh->h_kv > 256) return JQ_ERR_UNSUPPORTED;  // grid dimensions
@@ -39,6 +40,12 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     p.n_layers = sh->n_layers; p.n_seq = sh->n_seq; p.n_q = sh->n_q; p.h_q = sh->h_q; p.h_kv = sh->h_kv;
     p.d = sh->d; p.group = sh->h_q / sh->h_kv; p.pool_k = sh->pool_k;
     p.keep_first = sh->keep_first; p.keep_last = sh->keep_last;
+    p.window = sh->window;
+    if (p.window) {  // the window's own positions are always kept
+        if (p.keep_last < sh->n_q) p.keep_last = sh->n_q;
+        for (int s = 0; s < sh->n_seq; ++s)
+            if (sh->cu_seqlens[s + 1] - sh->cu_seqlens[s] < sh->n_q) return JQ_ERR_SHAPE;
+    }
     p.scale = sh->scale > 0.0f ? sh->scale : (float)(1.0 / std::sqrt((double)sh->d));
     const int64_t rows = (int64_t)p.n_q * p.group;
     if (rows > (1 << 20)) return JQ_ERR_UNSUPPORTED;
@@ -57,7 +64,7 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
         if (sh->budgets) {
             b = sh->budgets[s];
             const int32_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
-            if (need_budgets && (b < 1 || b > L || (int64_t)sh->keep_first + sh->keep_last > b)) return JQ_ERR_BUDGET;
+            if (need_budgets && (b < 1 || b > L || (int64_t)p.keep_first + p.keep_last > b)) return JQ_ERR_BUDGET;
             if (b < 1 || b > L) b = 1;  // entry points that ignore budgets still get a sane table
         }
         tb += b;
@@ -210,6 +217,7 @@ static int score_impl(const jq_shape* shape, const void* Q, const void* K, const
     if (rc != JQ_OK) return rc;
     if (paged && (rc = apply_pages(pages, &p)) != JQ_OK) return rc;
     const void* extra = lse ? (const void*)lse : k_tail;
+    if (p.window && k_tail) return JQ_ERR_SHAPE;  // the window's keys are part of K already
     if (!Q || !K || !scores || (want_extra && !extra)) return JQ_ERR_NULL;
     if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(scores, 4) || (lse && misaligned(lse, 4)) ||
@@ -320,6 +328,7 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
     if (rc != JQ_OK) return rc;
     if (paged && (rc = apply_pages(pages, &p)) != JQ_OK) return rc;
     if (out_pages && (rc = apply_out_pages(out_pages, &p)) != JQ_OK) return rc;
+    if (p.window && k_tail) return JQ_ERR_SHAPE;  // the window's keys are part of K already
     if (!Q || !K || !V || !K_out || !V_out) return JQ_ERR_NULL;
     if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
     if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(K_out, 16) || misaligned(V_out, 16) ||

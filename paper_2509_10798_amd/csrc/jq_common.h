@@ -39,6 +39,7 @@ struct PageMap {
 struct Plan {
     int32_t n_layers, n_seq, n_q, h_q, h_kv, d, group, pool_k;
     int32_t keep_first, keep_last;  // positions at either end of a sequence that the selection always keeps
+    int32_t window;                 // 1: the queries are the last n_q tokens of every sequence (causal inside them)
     int32_t rows;         // n_q * group: query rows that share one KV head
     int32_t row_tiles;    // ceil(rows / 32)
     int32_t row_groups;   // ceil(row_tiles / 4): passes of the score kernels over K

@@ -50,6 +50,7 @@ struct ScoreArgs {
     int32_t n_part, fuse_combine;
     int32_t cu_part[JQ_MAX_SEQ + 1];
     int32_t group_shift;  // log2(group) when group is a power of two, else -1
+    int32_t window;       // 1: the queries are the sequence's own last n_q tokens; query i sees keys 0 .. L - n_q + i
     int32_t row_tile0;   // first query-row tile of this launch
     int32_t accumulate;  // pass 2: add to `scores` instead of overwriting
     float c;             // scale * log2(e)
@@ -378,9 +379,13 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     if (n_all > 1) fetch(1);
 
     // Every load older than the second tile's eight (first tile, query rows) is covered
-    // by the first wait of the sweep.  Only the sequence's last tile can be partial, and it is some wave's last.
-    const int last_valid = w.L - (w.wave + (w.n_tiles - 1) * w.n_waves) * kKeyTile;
-    const int n_full = last_valid >= kKeyTile ? w.n_tiles : w.n_tiles - 1;
+    // by the first wait of the sweep.  Tiles that lie entirely inside the keys every query row sees (all L
+    // prompt keys, or the L - n_q keys in front of the window when the queries are the prompt's own last
+    // tokens) need no mask; the others -- the sequence's partial last tile, the window's tiles -- are the
+    // last of the tiles of whichever waves own them.
+    const int n_common = a.window ? w.L - a.n_q : w.L;
+    const int common_tiles = n_common / kKeyTile;  // sequence tiles 0 .. common_tiles - 1 are unmasked
+    const int n_full = common_tiles > w.wave ? min(w.n_tiles, (common_tiles - 1 - w.wave) / w.n_waves + 1) : 0;
     // soft token of this lane's query row in each query tile (row r = i * group + hh): it sees soft tokens 0..i
     int soft_i[NQT];
 #pragma unroll
@@ -415,10 +420,11 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         if (n_full > 0) full_tile(0, std::false_type{});
         for (int k = 1; k < n_full; ++k) full_tile(k, fast);
         int valid[NQT];
-        if (n_full < w.n_tiles) {  // partial last tile of the prompt
+        for (int k = n_full; k < w.n_tiles; ++k) {  // partial last tile of the prompt, tiles that reach into the window
+            const int t0 = (w.wave + k * w.n_waves) * kKeyTile;
 #pragma unroll
-            for (int qt = 0; qt < NQT; ++qt) valid[qt] = last_valid;
-            masked_tile(n_full, valid, decltype(fast)::value && n_full > 0);
+            for (int qt = 0; qt < NQT; ++qt) valid[qt] = (a.window ? n_common + soft_i[qt] + 1 : w.L) - t0;
+            masked_tile(k, valid, decltype(fast)::value && k > 0);
         }
         for (int t = 0; t < n_tail; ++t) {  // soft token t * 32 + j is visible to the row of soft token i iff it is <= i
 #pragma unroll
@@ -650,10 +656,12 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     const float c = a.c;
     float pending = 0.f;  // previous tile's result, stored one iteration late so that the store has a
                           // whole tile of compute to retire before the next wait on outstanding loads
+    const int n_scored = a.window ? w.L - a.n_q : w.L;  // the window's own positions report 0
     auto store_tile = [&](int k, float v) {  // only the sequence's last tile can be partial
         const int t = tile_of(k);
         if (lane < 32 && t * kKeyTile + lane < w.L) {
             float* o = out + t * kKeyTile + lane;
+            if (t * kKeyTile + lane >= n_scored) v = 0.f;
             *o = a.accumulate ? *o + v : v;
         }
     };
@@ -739,6 +747,7 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.scores = scores;
     a.n_layers = p.n_layers; a.n_seq = p.n_seq; a.n_q = p.n_q; a.h_q = p.h_q; a.h_kv = p.h_kv;
     a.group = p.group; a.rows = p.rows; a.RP = p.row_tiles * kRowTile;
+    a.window = p.window;
     a.group_shift = -1;
     for (int sh = 0; sh < 16; ++sh)
         if (p.group == (1 << sh)) a.group_shift = sh;

@@ -58,6 +58,10 @@ def test_workspace_size_grows_with_problem():
     (dict(keep_first=5, keep_last=4), -3),                       # more always-kept positions than the budget
     (dict(seq_lens=[64, 64], budgets=[40, 8], keep_last=9), -3), # ... in any sequence
     (dict(keep_first=4, keep_last=4), 0),
+    (dict(window=True), 0),                                      # 4 window tokens inside a budget of 8
+    (dict(window=True, budgets=[3]), -3),                        # the window alone exceeds the budget
+    (dict(window=True, keep_first=5), -3),
+    (dict(window=True, seq_lens=[64, 3], budgets=[8, 3]), -2),   # a sequence shorter than its window
 ])
 def test_shape_errors(kw, code):
     assert ws_status(shape(**kw)) == code
@@ -90,6 +94,9 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_score_tail(ctypes.byref(cs), Q, K, None, Ko, ws, need, None) == -1                 # soft-token keys required
     assert L.jq_score_tail(ctypes.byref(cs), Q, K, kt + 2, Ko, ws, need, None) == -4
     assert L.jq_score_tail(ctypes.byref(cs), Q, K, ws + 512, Ko, ws, need, None) == -6             # keys inside the workspace
+    cs_w = shape(window=True).c_struct()                                                           # the window's keys are in K already
+    assert L.jq_score_tail(ctypes.byref(cs_w), Q, K, kt, Ko, ws, need, None) == -2
+    assert L.jq_evict_tail(ctypes.byref(cs_w), Q, K, V, kt, Ko, Vo, None, None, ws, need, None) == -2
     assert L.jq_evict_tail(ctypes.byref(cs), Q, K, V, None, Ko, Vo, None, None, ws, need, None) == -1
     assert L.jq_evict_tail(ctypes.byref(cs), Q, K, V, Vo, Ko, Vo, None, None, ws, need, None) == -6   # keys inside V_out
     assert L.jq_evict_traced(ctypes.byref(cs), Q, K, V, Ko, Vo, None, None, ws, need, None, None, 10) == -1
