@@ -108,6 +108,17 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s_layer = w.total_tokens / (dt / args.steps / w.n_layers)
 
+    # each call between its own pair of events (the GPU stays busy: no host synchronisation inside the loop)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(min(args.steps, 400) + 1)]
+    for i in range(50):
+        run(i)
+    evs[0].record()
+    for i in range(len(evs) - 1):
+        run(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per_call = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(len(evs) - 1)])
+
     # same buffers every step (what a cache-warm caller would see)
     for i in range(50):
         run(0)
@@ -226,6 +237,8 @@ def main():
                    "pool_k": w.pool_k, "kv_buffers_rotated": len(sets), "seed": w.seed},
         "frac_hbm_peak_vs_bytes_min": round(ab["total"] * w.n_layers / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "bytes_min_per_layer": ab["total"],
+        "ms_per_call_event_timed": {"median": round(float(np.median(per_call)), 5), "mean": round(float(per_call.mean()), 5),
+                                    "calls": int(per_call.size)},
         "ms_per_step_same_buffers": round(ms_same, 5),
         "supplied_lse_one_pass": {"entry": "jq_evict_lse", "ms_per_step": round(ms_lse, 5),
                                   "tokens_per_s_per_layer": round(w.total_tokens * w.n_layers / (ms_lse * 1e-3), 1)},
