@@ -412,8 +412,11 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
                 const uint32_t c = __popc((k >> pos) & ((1u << sft) - 1u));
                 if (r >= c) { r -= c; pos += sft; }
             }
-            p.out[o] = (lo << 5) + (int)pos;
-            slot_pos[threadIdx.x] = (uint32_t)(lo << 5) + pos;
+            // (with consistent counts this is a kept position; the clamp keeps the gather inside the sequence whatever
+            // the lists hold)
+            const uint32_t at = min((uint32_t)(lo << 5) + pos, (uint32_t)p.L - 1u);
+            p.out[o] = (int)at;
+            slot_pos[threadIdx.x] = at;
         }
         if (a.K_out == nullptr) continue;  // uniform
         // Pruned cache (paper Section 4.3): the kept rows of this batch, 16 lanes x 16 B per 256-byte head row.
