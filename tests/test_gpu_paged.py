@@ -152,3 +152,38 @@ def test_evict_paged_into_a_paged_pruned_cache(out_page):
             np.testing.assert_array_equal(Vop_h[:, pg, r], Vo_h[:, cb[s] + b])
             used[pg, r] = True
     assert not Kop_h[:, ~used].any() and not Vop_h[:, ~used].any()                      # nothing else was written
+
+
+def test_sequences_that_share_prefix_pages():
+    # prefix caching: two sequences whose block tables point at the same physical pages for their common prefix
+    torch = torch_()
+    ps, h_kv, h_q, n_q, d = 64, 2, 8, 16, 128
+    rng = np.random.default_rng(13)
+    from workloads import f32_to_bf16_bits
+    shared = f32_to_bf16_bits(rng.standard_normal((1, 4 * ps, h_kv, d)).astype(np.float32))      # 4 pages both sequences use
+    tails = [f32_to_bf16_bits(rng.standard_normal((1, n, h_kv, d)).astype(np.float32)) for n in (100, 200)]
+    vsh = f32_to_bf16_bits(rng.standard_normal((1, 4 * ps, h_kv, d)).astype(np.float32))
+    vtails = [f32_to_bf16_bits(rng.standard_normal((1, n, h_kv, d)).astype(np.float32)) for n in (100, 200)]
+    seq_lens = [4 * ps + 100, 4 * ps + 200]
+    K = np.concatenate([shared, tails[0], shared, tails[1]], axis=1)                            # the dense equivalent
+    V = np.concatenate([vsh, vtails[0], vsh, vtails[1]], axis=1)
+    Q = f32_to_bf16_bits(rng.standard_normal((1, 2, n_q, h_q, d)).astype(np.float32))
+    # pool: pages 0..3 shared, then 2 pages for the first tail, 4 for the second
+    n_pages = 4 + 2 + 4
+    Kp = np.zeros((1, n_pages, ps, h_kv, d), dtype=np.uint16); Vp = np.zeros_like(Kp)
+    Kp[:, :4] = shared.reshape(1, 4, ps, h_kv, d); Vp[:, :4] = vsh.reshape(1, 4, ps, h_kv, d)
+    def fill(first, k, v):
+        n = k.shape[1]
+        for i in range((n + ps - 1) // ps):
+            m = min(ps, n - i * ps)
+            Kp[:, first + i, :m] = k[:, i * ps:i * ps + m]; Vp[:, first + i, :m] = v[:, i * ps:i * ps + m]
+    fill(4, tails[0], vtails[0]); fill(6, tails[1], vtails[1])
+    table = np.array([[0, 1, 2, 3, 4, 5, -1, -1], [0, 1, 2, 3, 6, 7, 8, 9]], dtype=np.int32)
+    pages = jq.Pages(page_size=ps, n_pages=n_pages, block_table=torch.from_numpy(table).cuda())
+    sh = jq.Shape(n_layers=1, seq_lens=seq_lens, n_q=n_q, h_q=h_q, h_kv=h_kv, budgets=[40, 70])
+    Qd = to_dev_bf16(Q)
+    Ko, Vo, idx, pooled = jq.evict_paged(sh, pages, Qd, to_dev_bf16(Kp), to_dev_bf16(Vp))
+    Ko1, Vo1, idx1, pooled1 = jq.evict(sh, Qd, to_dev_bf16(K), to_dev_bf16(V))
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled1) and torch.equal(idx, idx1)
+    assert torch.equal(Ko.view(torch.int16), Ko1.view(torch.int16)) and torch.equal(Vo.view(torch.int16), Vo1.view(torch.int16))
