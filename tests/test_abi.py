@@ -54,6 +54,8 @@ def test_workspace_size_grows_with_problem():
     (dict(d=64), -4), (dict(seq_lens=[8] * 129, budgets=[1] * 129), -4), (dict(h_q=1028, h_kv=257), -4),
     (dict(budgets=[0]), -3), (dict(budgets=[65]), -3),
     (dict(seq_lens=[64, 0], budgets=[8, 1]), -2),
+    (dict(seq_lens=[2200000], h_q=8, h_kv=8, n_q=2), -4),      # one sequence's keys reach 4 GiB
+    (dict(seq_lens=[2097000], h_q=8, h_kv=8, n_q=2), 0),       # ... and just below
     (dict(keep_first=-1), -2), (dict(keep_last=-3), -2),
     (dict(keep_first=5, keep_last=4), -3),                       # more always-kept positions than the budget
     (dict(seq_lens=[64, 64], budgets=[40, 8], keep_last=9), -3), # ... in any sequence

@@ -183,3 +183,34 @@ def test_config5_ragged_batch():
         check_problem_against_oracle(w, q, k, v, pooled[0, :, cu[s]:cu[s + 1]].cpu().numpy(),
                                      idx[0, :, cb[s]:cb[s + 1]].cpu().numpy(), from_dev_bf16(Ko[0, cb[s]:cb[s + 1]]),
                                      from_dev_bf16(Vo[0, cb[s]:cb[s + 1]]), "config 5 seq %d" % s)
+
+
+def test_sequence_just_below_the_four_gib_limit():
+    # the longest sequence the score kernels address (its keys stay below 4 GiB): byte offsets beyond 2^31 and
+    # up to 2^32 - 2^18, heavy hitters planted where an overflowing offset would miss them; few query rows so
+    # that the oracle can do the whole sequence
+    torch = torch_()
+    L, h, n_q, B, d = 2097000, 8, 2, 2048, 128
+    assert L * h * d * 2 < 2 ** 32
+    torch.manual_seed(250999)
+    Kd = torch.randn((1, L, h, d), device="cuda", dtype=torch.bfloat16)
+    Vd = torch.randn((1, L, h, d), device="cuda", dtype=torch.bfloat16)
+    Qd = torch.randn((1, 1, n_q, h, d), device="cuda", dtype=torch.bfloat16)
+    planted = [5, 1048575, 1048576, 1572864, L - 40, L - 1]            # 1048576 rows = byte offset 2^31
+    for j in planted:
+        Kd[0, j] = (3.0 * Qd[0, 0].float().mean(dim=0)).to(torch.bfloat16)   # [h, d]: aligned with each head's queries
+    sh = jq.Shape(n_layers=1, seq_lens=[L], n_q=n_q, h_q=h, h_kv=h, pool_k=7, budgets=[B])
+    Ko, Vo, idx, pooled = jq.evict(sh, Qd, Kd, Vd)
+    torch.cuda.synchronize()
+    Q, K, V = from_dev_bf16(Qd), from_dev_bf16(Kd), from_dev_bf16(Vd)
+    print("oracle on %d keys" % L, flush=True)
+    ref_p = oracle.pool(oracle.score(Q[0, 0], K[0]), 7)
+    pooled_h, idx_h = pooled[0].cpu().numpy(), idx[0].cpu().numpy()
+    assert_scores_close(pooled_h, ref_p, n_q / L, "pooled, 2.1 M keys")
+    ref_idx = oracle.select_topk(ref_p, B)
+    for g in range(h):
+        assert_kept_set_ok(ref_p[g], ref_idx[g], idx_h[g], "head %d" % g)
+        assert set(planted) <= set(idx_h[g].tolist())
+    rk, rv = oracle.compact(K[0], V[0], np.ascontiguousarray(idx_h))
+    np.testing.assert_array_equal(from_dev_bf16(Ko)[0], rk)
+    np.testing.assert_array_equal(from_dev_bf16(Vo)[0], rv)
