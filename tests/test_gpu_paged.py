@@ -187,3 +187,38 @@ def test_sequences_that_share_prefix_pages():
     torch.cuda.synchronize()
     assert torch.equal(pooled, pooled1) and torch.equal(idx, idx1)
     assert torch.equal(Ko.view(torch.int16), Ko1.view(torch.int16)) and torch.equal(Vo.view(torch.int16), Vo1.view(torch.int16))
+
+
+def test_pages_at_the_top_of_a_pool_just_below_four_gib():
+    # the score kernels address a layer's pool through one 32-bit offset: a sequence that lives in the LAST pages of
+    # the largest pool allowed exercises offsets up to 2^32
+    torch = torch_()
+    ps, h_kv, h_q, n_q, d, L, B = 256, 8, 8, 4, 128, 40000, 512
+    n_pages = (2 ** 32 - 1) // (ps * h_kv * d * 2)                      # 8191 pages
+    assert n_pages * ps * h_kv * d * 2 < 2 ** 32
+    rng = np.random.default_rng(14)
+    from workloads import f32_to_bf16_bits
+    Q = f32_to_bf16_bits(rng.standard_normal((1, 1, n_q, h_q, d)).astype(np.float32))
+    K = f32_to_bf16_bits(rng.standard_normal((1, L, h_kv, d)).astype(np.float32))
+    V = f32_to_bf16_bits(rng.standard_normal((1, L, h_kv, d)).astype(np.float32))
+    n_used = (L + ps - 1) // ps
+    table = (n_pages - 1 - rng.permutation(n_used)).astype(np.int32)[None, :]      # the top pages, shuffled
+    Kp = torch.zeros((1, n_pages, ps, h_kv, d), dtype=torch.bfloat16, device="cuda")
+    Vp = torch.zeros_like(Kp)
+    Kd, Vd = to_dev_bf16(K), to_dev_bf16(V)
+    for i in range(n_used):
+        m = min(ps, L - i * ps)
+        Kp[0, int(table[0, i]), :m] = Kd[0, i * ps:i * ps + m]
+        Vp[0, int(table[0, i]), :m] = Vd[0, i * ps:i * ps + m]
+    pages = jq.Pages(page_size=ps, n_pages=n_pages, block_table=torch.from_numpy(table).cuda())
+    sh = jq.Shape(n_layers=1, seq_lens=[L], n_q=n_q, h_q=h_q, h_kv=h_kv, budgets=[B])
+    Qd = to_dev_bf16(Q)
+    Ko, Vo, idx, pooled = jq.evict_paged(sh, pages, Qd, Kp, Vp)
+    Ko1, Vo1, idx1, pooled1 = jq.evict(sh, Qd, Kd, Vd)
+    torch.cuda.synchronize()
+    assert torch.equal(pooled, pooled1) and torch.equal(idx, idx1)
+    assert torch.equal(Ko.view(torch.int16), Ko1.view(torch.int16)) and torch.equal(Vo.view(torch.int16), Vo1.view(torch.int16))
+    ref_p = oracle.pool(oracle.score(Q[0, 0], K[0]), 7)
+    assert_scores_close(pooled[0].cpu().numpy(), ref_p, n_q / L, "pooled")
+    rk, rv = oracle.compact(K[0], V[0], np.ascontiguousarray(idx[0].cpu().numpy()))
+    np.testing.assert_array_equal(from_dev_bf16(Ko)[0], rk)
