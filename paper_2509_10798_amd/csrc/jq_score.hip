@@ -1,13 +1,16 @@
 // Importance scores of the prompt keys under the soft-token queries
 // (paper Section 4.3, Eq. 3), as two K-streaming MFMA passes for gfx950.
 //
-//   pass 1 (stats):  per query row r, the running maximum m_r and Z_r = sum_j 2^(t_rj - m_r) of its
-//                    base-2 logits t_rj = c * q_r.k_j, c = scale * log2(e); one partial per wave.
-//   combine:         beta_r = m_r + log2 Z_r over a sequence's partials, stored as -beta_r / c split
-//                    into three bf16 terms.
+//   pass 1 (stats):  per query row r, an offset m_r and Z_r = sum_j 2^(t_rj - m_r) of its base-2 logits
+//                    t_rj = c * q_r.k_j, c = scale * log2(e); one (m, Z) partial per workgroup.
+//   merge:           beta_r = m_r + log2 Z_r over a sequence's partials, as -beta_r / c split into three
+//                    bf16 terms -- done by every pass-2 workgroup for its own head in its start-up (a
+//                    separate small kernel only when a sequence leaves more than 64 partials).
 //   pass 2 (score):  score_j = sum_r 2^(c * (q_r.k_j - beta_r / c)).  The -beta_r/c term enters
 //                    through one extra MFMA step whose key-side operand is 1.0, so the epilogue is one
 //                    multiply, one exp2 and one add per logit.
+// Variants of the same kernels: supplied normalisers (pass 2 alone), the soft tokens' own keys or the prompt's
+// own last tokens as causally masked tiles of pass 1, keys read out of a paged pool.
 //
 // One wave owns one (layer, sequence, KV head) and a strided set of that sequence's 32-key tiles, and
 // keeps the head's (up to) 128 query rows in registers as MFMA operands.  The four waves of a workgroup
