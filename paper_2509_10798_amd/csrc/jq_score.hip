@@ -99,7 +99,7 @@ __device__ __forceinline__ void wait_frags_read() {
 // the head's query rows; a sequence whose W is not a multiple of four leaves the last workgroup's
 // surplus waves without tiles (they only help with the query rows).
 struct WaveItem {
-    int layer, seq, g, chunk_global;  // chunk_global: the wave's slot in the per-wave statistics
+    int layer, seq, g;
     int wave, n_waves;                // w and W
     int L;                            // keys in the sequence
     int n_tiles;                      // tiles this wave owns (0: surplus wave)
@@ -119,7 +119,6 @@ __device__ __forceinline__ void wave_item(const ScoreArgs& a, bool reverse, Wave
     w.L = a.tab.cu_seq[w.seq + 1] - a.tab.cu_seq[w.seq];
     w.n_waves = a.tab.cu_chunk[w.seq + 1] - a.tab.cu_chunk[w.seq];
     w.wave = (cg - a.tab.cu_cgrp[w.seq]) * kScoreWaves + wv;
-    w.chunk_global = a.tab.cu_chunk[w.seq] + w.wave;
     const int seq_tiles = (w.L + kKeyTile - 1) / kKeyTile;  // >= n_waves, since a chunk is at least one tile
     w.n_tiles = w.wave < w.n_waves ? (seq_tiles - w.wave + w.n_waves - 1) / w.n_waves : 0;
     w.tok0 = a.tab.cu_seq[w.seq];
