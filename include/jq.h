@@ -104,6 +104,15 @@ typedef struct jq_shape {
                                /* positions 0 .. L_s - n_q + i only (causal), the window's own  */
                                /* positions score 0 and are always kept (keep_last counts as    */
                                /* at least n_q).  Not with jq_score_tail / jq_evict_tail.       */
+    const int32_t* layer_budgets; /* NULL, or DEVICE int32 [n_layers, n_seq]: budgets that differ from */
+                               /* layer to layer in one call (the depth-dependent allocation of the   */
+                               /* PyramidKV baseline, Section 5.1).  `budgets` then gives each          */
+                               /* sequence's LARGEST budget and with it the layout of idx / K_out /     */
+                               /* V_out; layer l keeps layer_budgets[l, s] positions of sequence s and  */
+                               /* writes only the first that many slots of the sequence's segment (the  */
+                               /* rest is left untouched).  Read on the device only: a value outside    */
+                               /* 1..budgets[s] is clamped into that range.  Used by jq_select_topk,    */
+                               /* jq_compact and jq_evict*.                                              */
 } jq_shape;
 
 /* Bytes of device workspace that jq_score, jq_select_topk and jq_evict need for

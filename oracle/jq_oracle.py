@@ -179,7 +179,7 @@ def evict(Q, K, V, B: int, pool_k: int, scale: float = 0.0, lse=None, K_tail=Non
 
 
 def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0, keep_first: int = 0, keep_last: int = 0,
-                window: bool = False):
+                window: bool = False, layer_budgets=None):
     """Layers x ragged sequences, one problem at a time.
 
     Q [nl,n_seq,n_q,h_q,d], K/V [nl,T,h_kv,d] uint16.  Returns pooled [nl,h_kv,T],
@@ -194,13 +194,16 @@ def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0, k
     Ko = np.empty((nl, TB, h_kv, d), dtype=np.uint16); Vo = np.empty_like(Ko)
     for l in range(nl):
         for s in range(len(cu) - 1):
-            r = evict(Q[l, s], K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], int(budgets[s]), pool_k, scale,
+            # budgets that differ from layer to layer (the depth-dependent allocation of the PyramidKV baseline,
+            # Section 5.1): layer l keeps layer_budgets[l][s] positions and fills only that many slots
+            b = int(budgets[s]) if layer_budgets is None else int(layer_budgets[l][s])
+            r = evict(Q[l, s], K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], b, pool_k, scale,
                       keep_first=keep_first, keep_last=keep_last, window=window)
             scores[l, :, cu[s]:cu[s + 1]] = r["scores"]
             pooled[l, :, cu[s]:cu[s + 1]] = r["pooled"]
-            idx[l, :, cb[s]:cb[s + 1]] = r["idx"]
-            Ko[l, cb[s]:cb[s + 1]] = r["K_out"]
-            Vo[l, cb[s]:cb[s + 1]] = r["V_out"]
+            idx[l, :, cb[s]:cb[s] + b] = r["idx"]
+            Ko[l, cb[s]:cb[s] + b] = r["K_out"]
+            Vo[l, cb[s]:cb[s] + b] = r["V_out"]
     return {"scores": scores, "pooled": pooled, "idx": idx, "K_out": Ko, "V_out": Vo}
 
 

@@ -38,7 +38,8 @@ class _CShape(ctypes.Structure):
                 ("h_q", ctypes.c_int32), ("h_kv", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("pool_k", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("cu_seqlens", ctypes.POINTER(ctypes.c_int32)), ("budgets", ctypes.POINTER(ctypes.c_int32)),
-                ("keep_first", ctypes.c_int32), ("keep_last", ctypes.c_int32), ("window", ctypes.c_int32)]
+                ("keep_first", ctypes.c_int32), ("keep_last", ctypes.c_int32), ("window", ctypes.c_int32),
+                ("layer_budgets", ctypes.c_void_p)]
 
 
 class _CPages(ctypes.Structure):
@@ -105,6 +106,7 @@ class Shape:
     keep_first: int = 0   # positions at the start / end of every sequence that the selection always keeps
     keep_last: int = 0
     window: bool = False  # the queries are the prompt's own last n_q tokens (causal inside them, always kept)
+    layer_budgets: object = None  # int32 DEVICE tensor [n_layers, n_seq]: per-layer budgets (`budgets` = the largest)
     _keep: list = field(default_factory=list, repr=False)
 
     @property
@@ -121,7 +123,8 @@ class Shape:
 
     def c_struct(self) -> _CShape:
         key = (self.n_layers, tuple(self.seq_lens), self.n_q, self.h_q, self.h_kv, self.d, self.pool_k,
-               None if self.budgets is None else tuple(self.budgets), float(self.scale), self.keep_first, self.keep_last, bool(self.window))
+               None if self.budgets is None else tuple(self.budgets), float(self.scale), self.keep_first, self.keep_last, bool(self.window),
+               None if self.layer_budgets is None else int(self.layer_budgets.data_ptr()))
         if self._keep and self._keep[0] == key:  # marshalled once per distinct description
             return self._keep[3]
         cu = np.concatenate([[0], np.cumsum(np.asarray(self.seq_lens, dtype=np.int64))]).astype(np.int32)
@@ -130,7 +133,8 @@ class Shape:
         cs = _CShape(self.n_layers, self.n_seq, self.n_q, self.h_q, self.h_kv, self.d, self.pool_k,
                      float(self.scale), cu.ctypes.data_as(i32p),
                      bud.ctypes.data_as(i32p) if bud is not None else ctypes.cast(None, i32p),
-                     int(self.keep_first), int(self.keep_last), int(bool(self.window)))
+                     int(self.keep_first), int(self.keep_last), int(bool(self.window)),
+                     None if self.layer_budgets is None else int(self.layer_budgets.data_ptr()))
         self._keep = [key, cu, bud, cs]  # the host arrays must outlive the struct
         return cs
 

@@ -41,6 +41,8 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     p.d = sh->d; p.group = sh->h_q / sh->h_kv; p.pool_k = sh->pool_k;
     p.keep_first = sh->keep_first; p.keep_last = sh->keep_last;
     p.window = sh->window;
+    p.layer_budgets = sh->layer_budgets;
+    if (p.layer_budgets && misaligned(p.layer_budgets, 4)) return JQ_ERR_UNSUPPORTED;
     if (p.window) {  // the window's own positions are always kept
         if (p.keep_last < sh->n_q) p.keep_last = sh->n_q;
         for (int s = 0; s < sh->n_seq; ++s)
@@ -174,6 +176,7 @@ size_t kv_bytes(const Plan& p) {  // bytes of K (or V) as the caller holds it: d
     const size_t rows = p.block_table ? ((size_t)p.n_pages << p.page_shift) : (size_t)p.T;
     return (size_t)p.n_layers * rows * p.h_kv * p.d * 2;
 }
+size_t lb_bytes(const Plan& p) { return p.layer_budgets ? (size_t)p.n_layers * p.n_seq * 4 : 0; }
 size_t table_bytes(const Plan& p) { return p.block_table ? (size_t)p.n_seq * p.max_pages * 4 : 0; }
 size_t kv_out_bytes(const Plan& p) {  // bytes of K_out (or V_out): dense kept rows, or the output pools of all layers
     const size_t rows = p.out_map.block_table ? ((size_t)p.out_map.n_pages << p.out_map.page_shift) : (size_t)p.TB;
@@ -268,7 +271,9 @@ int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx, voi
     if ((rc = check_ws(p, ws, ws_bytes)) != JQ_OK) return rc;
     if (misaligned(pooled, 4) || misaligned(idx, 4)) return JQ_ERR_UNSUPPORTED;
     if (overlaps(idx, idx_bytes(p), pooled, score_bytes(p)) || overlaps(idx, idx_bytes(p), ws, p.ws_bytes) ||
-        overlaps(pooled, score_bytes(p), ws, p.ws_bytes))
+        overlaps(pooled, score_bytes(p), ws, p.ws_bytes) ||
+        (p.layer_budgets && (overlaps(idx, idx_bytes(p), p.layer_budgets, lb_bytes(p)) ||
+                             overlaps(ws, p.ws_bytes, p.layer_budgets, lb_bytes(p)))))
         return JQ_ERR_ALIAS;
     hipStream_t st = (hipStream_t)stream;
     uint32_t* hist = (uint32_t*)((char*)ws + p.off_hist);
@@ -289,7 +294,8 @@ int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_
     const size_t nin = kv_bytes(p), nout = kv_out_bytes(p);
     if (overlaps(K_out, nout, K, nin) || overlaps(K_out, nout, V, nin) || overlaps(V_out, nout, K, nin) ||
         overlaps(V_out, nout, V, nin) || overlaps(K_out, nout, V_out, nout) || overlaps(K_out, nout, idx, idx_bytes(p)) ||
-        overlaps(V_out, nout, idx, idx_bytes(p)))
+        overlaps(V_out, nout, idx, idx_bytes(p)) ||
+        (p.layer_budgets && (overlaps(K_out, nout, p.layer_budgets, lb_bytes(p)) || overlaps(V_out, nout, p.layer_budgets, lb_bytes(p)))))
         return JQ_ERR_ALIAS;
     return launch_status(launch_compact(p, K, V, idx, K_out, V_out, (hipStream_t)stream));
 }
@@ -314,7 +320,9 @@ int jq_compact_inplace(const jq_shape* shape, void* K, void* V, const int32_t* i
     if (misaligned(ws, 16) || ws_bytes < need) return JQ_ERR_WORKSPACE;
     const size_t nin = kv_bytes(p);
     if (overlaps(K, nin, V, nin) || overlaps(ws, need, K, nin) || overlaps(ws, need, V, nin) ||
-        overlaps(idx, idx_bytes(p), K, nin) || overlaps(idx, idx_bytes(p), V, nin) || overlaps(idx, idx_bytes(p), ws, need))
+        overlaps(idx, idx_bytes(p), K, nin) || overlaps(idx, idx_bytes(p), V, nin) || overlaps(idx, idx_bytes(p), ws, need) ||
+        (p.layer_budgets && (overlaps(K, nin, p.layer_budgets, lb_bytes(p)) || overlaps(V, nin, p.layer_budgets, lb_bytes(p)) ||
+                             overlaps(ws, need, p.layer_budgets, lb_bytes(p)))))
         return JQ_ERR_ALIAS;
     return launch_status(launch_compact_inplace(p, K, V, idx, ws, (hipStream_t)stream));
 }
@@ -336,13 +344,14 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
         (k_tail && misaligned(k_tail, 16)))
         return JQ_ERR_UNSUPPORTED;
     const size_t nin = kv_bytes(p), nout = kv_out_bytes(p);
-    const void* ins[6] = {Q, K, V, lse ? (const void*)lse : k_tail, p.block_table, p.out_map.block_table};
-    const size_t in_bytes[6] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p), table_bytes(p), out_table_bytes(p)};
+    const void* ins[7] = {Q, K, V, lse ? (const void*)lse : k_tail, p.block_table, p.out_map.block_table, p.layer_budgets};
+    const size_t in_bytes[7] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p), table_bytes(p), out_table_bytes(p),
+                                lb_bytes(p)};
     const void* outs[5] = {K_out, V_out, idx_out, scores_out, ws};
     const size_t out_bytes[5] = {nout, nout, idx_bytes(p), score_bytes(p), p.ws_bytes};
     for (int o = 0; o < 5; ++o) {
         if (!outs[o]) continue;
-        for (int i = 0; i < 6; ++i)
+        for (int i = 0; i < 7; ++i)
             if (ins[i] && overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return JQ_ERR_ALIAS;
         for (int o2 = o + 1; o2 < 5; ++o2)
             if (outs[o2] && overlaps(outs[o], out_bytes[o], outs[o2], out_bytes[o2])) return JQ_ERR_ALIAS;

@@ -40,6 +40,7 @@ struct Plan {
     int32_t n_layers, n_seq, n_q, h_q, h_kv, d, group, pool_k;
     int32_t keep_first, keep_last;  // positions at either end of a sequence that the selection always keeps
     int32_t window;                 // 1: the queries are the last n_q tokens of every sequence (causal inside them)
+    const int32_t* layer_budgets;   // DEVICE [n_layers][n_seq] or null: per-layer budgets (tab.cu_bud then holds the largest)
     int32_t rows;         // n_q * group: query rows that share one KV head
     int32_t row_tiles;    // ceil(rows / 32)
     int32_t row_groups;   // ceil(row_tiles / 4): passes of the score kernels over K
@@ -85,6 +86,13 @@ __device__ inline int64_t kv_row(const PageMap& pm, const int32_t* cu, int64_t T
     const int32_t e = pm.block_table[(int64_t)s * pm.max_pages + (pos >> pm.page_shift)];
     const int64_t page = (int64_t)layer * pm.n_pages + min(max(e, 0), pm.n_pages - 1);
     return (page << pm.page_shift) + (pos & ((1 << pm.page_shift) - 1));
+}
+
+// Budget of (layer, sequence): the table's segment length, or the caller's per-layer value clamped into 1..that.
+__device__ inline uint32_t budget_of(const int32_t* layer_budgets, const SeqTab& tab, int layer, int s) {
+    const int32_t cap = tab.cu_bud[s + 1] - tab.cu_bud[s];
+    if (!layer_budgets) return (uint32_t)cap;
+    return (uint32_t)min(max(layer_budgets[(int64_t)layer * tab.n_seq + s], 1), cap);
 }
 
 // Key the top-B selection ranks position j of an L-token sequence by: always-kept positions outrank

@@ -15,6 +15,7 @@ struct CompactArgs {
     int64_t T, TB;
     PageMap pm;      // where the rows of K and V live (dense or paged)
     PageMap pm_out;  // where the kept rows go
+    const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null: slots beyond a layer's own budget are skipped
     SeqTab tab;
 };
 
@@ -33,6 +34,7 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_kernel(CompactArgs
     const int layer = (int)(rest / a.TB);
     const int s = find_seq(a.tab.cu_bud, a.tab.n_seq, tb);
     const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
+    if ((uint32_t)(tb - a.tab.cu_bud[s]) >= budget_of(a.layer_budgets, a.tab, layer, s)) return;
     int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
     j = min(max(j, 0), L - 1);  // never read outside the sequence
     const int64_t src = ((kv_row(a.pm, a.tab.cu_seq, a.T, layer, s, j) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
@@ -51,6 +53,7 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.pm = p.page_map();
     a.pm_out = p.out_map;
+    a.layer_budgets = p.layer_budgets;
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
     return launch_kernel(jq_compact_kernel, dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads)),
@@ -67,6 +70,7 @@ struct InplaceArgs {
     const int32_t* idx;  // [n_layers][h_kv][TB], sequence-local
     int32_t n_layers, h_kv;
     int64_t T, TB;
+    const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null
     SeqTab tab;
 };
 
@@ -82,6 +86,7 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_inplace_kernel(Inp
     const int layer = (int)(rest / a.TB);
     const int s = find_seq(a.tab.cu_bud, a.tab.n_seq, tb);
     const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
+    if ((uint32_t)(tb - a.tab.cu_bud[s]) >= budget_of(a.layer_budgets, a.tab, layer, s)) return;  // slot not used by this layer
     int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
     j = min(max(j, 0), L - 1);
     const int64_t src_row = (int64_t)a.tab.cu_seq[s] + j;  // within the layer
@@ -106,6 +111,7 @@ hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t
     InplaceArgs a;
     a.K = (char*)K; a.V = (char*)V; a.stage = (char*)stage; a.idx = idx;
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
+    a.layer_budgets = p.layer_budgets;
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
     const dim3 grid((unsigned)((threads + kCompactThreads - 1) / kCompactThreads));

@@ -37,6 +37,7 @@ struct SelectArgs {
     char* K_out; char* V_out;
     PageMap pm;      // where the rows of K and V live (dense or paged)
     PageMap pm_out;  // where the kept rows go
+    const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null
     SeqTab tab;
 };
 
@@ -112,7 +113,7 @@ __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
     p.s = (prob / a.h_kv) % a.tab.n_seq;
     p.layer = prob / (a.h_kv * a.tab.n_seq);
     p.L = a.tab.cu_seq[p.s + 1] - a.tab.cu_seq[p.s];
-    p.B = (uint32_t)(a.tab.cu_bud[p.s + 1] - a.tab.cu_bud[p.s]);
+    p.B = budget_of(a.layer_budgets, a.tab, p.layer, p.s);
     p.x = a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s];
     p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
     p.hist = a.hist + (((int64_t)p.layer * a.tab.n_seq + p.s) * a.h_kv + p.g) * kHistStride;
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(Sele
 
     for (int s = s_first; s <= s_last; ++s) {  // almost always a single sequence
         uint32_t* hist = a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride;
-        const uint32_t B = (uint32_t)(a.tab.cu_bud[s + 1] - a.tab.cu_bud[s]);
+        const uint32_t B = budget_of(a.layer_budgets, a.tab, layer, s);
         const int Ls = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
         pick_bin<kScatterThreads, kHistBins / kScatterThreads>(hist, kHistBins, B, tmp, res);
         const uint32_t b1 = res[0];
@@ -450,6 +451,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     a.keep_first = p.keep_first; a.keep_last = p.keep_last;
     a.pm = p.page_map();
     a.pm_out = p.out_map;
+    a.layer_budgets = p.layer_budgets;
     a.tab = p.tab;
     const unsigned n_prob = (unsigned)((int64_t)p.n_layers * p.n_seq * p.h_kv);
 

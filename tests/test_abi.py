@@ -121,6 +121,14 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_compact_inplace(ctypes.byref(cs), K, K + 256, Ko, ws, n_in.value, None) == -6      # V inside K
     assert L.jq_compact_inplace(ctypes.byref(cs), K, V, K + 512, ws, n_in.value, None) == -6       # idx inside K
     assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, V + 1024, n_in.value, None) == -6      # staging inside V
+    class _T:                                   # stands in for a device tensor: only its address is marshalled
+        def __init__(self, addr): self.addr = addr
+        def data_ptr(self): return self.addr
+    cs_lb = shape(layer_budgets=_T(big + (10 << 30) + 2)).c_struct()
+    assert L.jq_evict(ctypes.byref(cs_lb), Q, K, V, Ko, Vo, None, None, ws, need, None) == -4      # misaligned per-layer budgets
+    cs_lb = shape(layer_budgets=_T(Ko + 64)).c_struct()
+    assert L.jq_evict(ctypes.byref(cs_lb), Q, K, V, Ko, Vo, None, None, ws, need, None) == -6      # ... inside an output
+    assert L.jq_compact(ctypes.byref(cs_lb), K, V, ws, Ko, Vo, None) == -6
     cs2 = shape(budgets=None).c_struct()
     assert L.jq_compact(ctypes.byref(cs2), K, V, ws, Ko, Vo, None) == -1                           # budgets required
     bad = _CShape(1, 1, 4, 4, 2, 128, 7, 0.0, ctypes.cast(None, ctypes.POINTER(ctypes.c_int32)),

@@ -354,6 +354,57 @@ def test_evict_with_always_kept_ends():
     assert not torch.equal(idx0, idx)
 
 
+def test_layer_dependent_budgets_in_one_call():
+    # the same schedule as one fused call: `budgets` gives every sequence's largest budget (and the output layout),
+    # a device array the budget of every (layer, sequence); slots beyond a layer's own budget stay untouched
+    torch = torch_()
+    seq_lens, cap, lb = [1200, 500], [300, 100], [[300, 100], [180, 64], [60, 7]]
+    w = make_workload(1, seq_lens=seq_lens, budget=cap, n_layers=3)
+    Q, K, V = w.assemble()
+    Qd, Kd, Vd = to_dev_bf16(Q), to_dev_bf16(K), to_dev_bf16(V)
+    lb_d = torch.tensor(lb, dtype=torch.int32, device="cuda")
+    sh = jq.Shape(n_layers=3, seq_lens=seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=cap,
+                  layer_budgets=lb_d)
+    TB = sum(cap)
+    idx = torch.full((3, w.h_kv, TB), -7, dtype=torch.int32, device="cuda")
+    Ko = torch.full((3, TB, w.h_kv, w.d), 1.5, dtype=torch.bfloat16, device="cuda"); Vo = Ko.clone()
+    jq.evict(sh, Qd, Kd, Vd, K_out=Ko, V_out=Vo, idx_out=idx)
+    # stage by stage as well
+    pooled = jq.pool(sh, jq.score(sh, Qd, Kd))
+    idx2 = torch.full_like(idx, -7)
+    jq.select_topk(sh, pooled, idx=idx2)
+    Ko2 = torch.full_like(Ko, 1.5); Vo2 = Ko2.clone()
+    jq.compact(sh, Kd, Vd, idx2, K_out=Ko2, V_out=Vo2)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(Ko.view(torch.int16), Ko2.view(torch.int16))
+    assert torch.equal(Vo.view(torch.int16), Vo2.view(torch.int16))
+    ref = oracle.evict_batch(Q, K, V, w.cu_seqlens, cap, w.pool_k, layer_budgets=lb)
+    idx_h, Ko_h, Vo_h = idx.cpu().numpy(), from_dev_bf16(Ko), from_dev_bf16(Vo)
+    cu, cb = w.cu_seqlens, w.cu_budgets
+    filler = from_dev_bf16(torch.full((1,), 1.5, dtype=torch.bfloat16, device="cuda"))[0]
+    for l in range(3):
+        for s in range(2):
+            b = lb[l][s]
+            for g in range(w.h_kv):
+                assert_kept_set_ok(ref["pooled"][l, g, cu[s]:cu[s + 1]], ref["idx"][l, g, cb[s]:cb[s] + b],
+                                   idx_h[l, g, cb[s]:cb[s] + b], "l%d s%d g%d" % (l, s, g))
+            rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], np.ascontiguousarray(idx_h[l, :, cb[s]:cb[s] + b]))
+            np.testing.assert_array_equal(Ko_h[l, cb[s]:cb[s] + b], rk)
+            np.testing.assert_array_equal(Vo_h[l, cb[s]:cb[s] + b], rv)
+            assert (idx_h[l, :, cb[s] + b:cb[s + 1]] == -7).all()                  # unused slots are not written
+            assert (Ko_h[l, cb[s] + b:cb[s + 1]] == filler).all() and (Vo_h[l, cb[s] + b:cb[s + 1]] == filler).all()
+    # values outside 1..cap are clamped on the device
+    lb_bad = torch.tensor([[0, 10 ** 6], [300, 100], [300, 100]], dtype=torch.int32, device="cuda")
+    sh_bad = jq.Shape(n_layers=3, seq_lens=seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=cap,
+                      layer_budgets=lb_bad)
+    idx3 = torch.full_like(idx, -7)
+    jq.select_topk(sh_bad, pooled, idx=idx3)
+    torch.cuda.synchronize()
+    i3 = idx3.cpu().numpy()
+    assert (i3[0, :, 0] >= 0).all() and (i3[0, :, 1:cb[1]] == -7).all()            # 0 -> one kept position
+    assert (i3[0, :, cb[1]:cb[2]] >= 0).all()                                      # 10^6 -> the sequence's cap
+
+
 def test_evict_equals_stage_composition_and_oracle():
     torch = torch_()
     w = make_workload(1, seq_lens=[1500, 700], budget=[200, 64], n_layers=2)
