@@ -275,6 +275,35 @@ def test_compact_inplace_matches_out_of_place_gather(seq_lens, budgets, mode):
     np.testing.assert_array_equal(Vh[:, TB:], V[:, TB:])
 
 
+def test_compact_inplace_with_layer_dependent_budgets():
+    torch = torch_()
+    rng = np.random.default_rng(44)
+    nl, h_kv, d, seq_lens, cap, lb = 2, 2, 128, [400, 300], [100, 50], [[100, 50], [30, 1]]
+    T, TB = sum(seq_lens), sum(cap)
+    K = rng.integers(0, 65536, (nl, T, h_kv, d)).astype(np.uint16)
+    V = rng.integers(0, 65536, (nl, T, h_kv, d)).astype(np.uint16)
+    idx = np.zeros((nl, h_kv, TB), dtype=np.int32)
+    cb = np.concatenate([[0], np.cumsum(cap)]); cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    for l in range(nl):
+        for g in range(h_kv):
+            for s in range(2):
+                idx[l, g, cb[s]:cb[s] + lb[l][s]] = np.sort(rng.choice(seq_lens[s], size=lb[l][s], replace=False))
+    sh = jq.Shape(n_layers=nl, seq_lens=seq_lens, n_q=1, h_q=h_kv, h_kv=h_kv, budgets=cap,
+                  layer_budgets=torch.tensor(lb, dtype=torch.int32, device="cuda"))
+    Kd, Vd = to_dev_bf16(K), to_dev_bf16(V)
+    jq.compact_inplace(sh, Kd, Vd, torch.from_numpy(idx).cuda())
+    torch.cuda.synchronize()
+    Kh, Vh = from_dev_bf16(Kd), from_dev_bf16(Vd)
+    for l in range(nl):
+        for s in range(2):
+            b = lb[l][s]
+            rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], np.ascontiguousarray(idx[l, :, cb[s]:cb[s] + b]))
+            np.testing.assert_array_equal(Kh[l, cb[s]:cb[s] + b], rk)
+            np.testing.assert_array_equal(Vh[l, cb[s]:cb[s] + b], rv)
+            np.testing.assert_array_equal(Kh[l, cb[s] + b:cb[s + 1]], K[l, cb[s] + b:cb[s + 1]])   # unused slots keep their rows
+    np.testing.assert_array_equal(Kh[:, TB:], K[:, TB:])
+
+
 def test_sink_and_recent_window_retention_through_compact():
     # position-based retention (attention sinks + recent window, the StreamingLLM baseline of Section 5.1)
     # needs no scores: the caller writes the positions and jq_compact prunes the cache
