@@ -19,14 +19,15 @@
 // loads that touch 32 cache lines each.  Key tiles of 32 keys x 128 channels are
 // fetched asynchronously, straight from global memory into a private, XOR-swizzled 8 KiB LDS slot
 // (buffer loads with the LDS modifier, 16 B per lane, 16 lanes per 256-byte key row, so every 128-byte
-// line is requested whole), double buffered, and read back in MFMA operand order without bank
-// conflicts.  After the start-up waves never share LDS, so the streaming loop has no workgroup barrier;
+// line is requested whole), two slots per wave used alternately, and read back in MFMA operand order without
+// bank conflicts.  After the start-up waves never share LDS, so the streaming loop has no workgroup barrier;
 // its only synchronisation is the wave's own s_waitcnt on its outstanding loads.
 //
 // MFMA 32x32x16 bf16 operand layout used here: lane l supplies row/column (l & 31) and the 8
 // contraction elements selected by (l >> 5); both operands use the same element order, so any
 // fixed channel permutation cancels.  Result: lane l holds column (l & 31), register v holds row
 // 8*(v/4) + 4*(l>>5) + (v&3).
+#include <cstdlib>
 #include <type_traits>
 
 #include "jq_common.h"
@@ -54,6 +55,7 @@ struct ScoreArgs {
     int32_t cu_part[JQ_MAX_SEQ + 1];
     int32_t group_shift;  // log2(group) when group is a power of two, else -1
     int32_t window;       // 1: the queries are the sequence's own last n_q tokens; query i sees keys 0 .. L - n_q + i
+    int32_t depth;        // key tiles a wave keeps in flight: 1 (the default) or 2
     int32_t row_tile0;   // first query-row tile of this launch
     int32_t accumulate;  // pass 2: add to `scores` instead of overwriting
     float c;             // scale * log2(e)
@@ -367,8 +369,9 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         }
     };
     // The first key tile goes to slot 0 at once; the second slots first serve as the staging area that turns
-    // the workgroup's query rows into operand order, then take the second tile.  From then on two tiles are
-    // always in flight: a slot is refilled as soon as its fragments are in registers.
+    // the workgroup's query rows into operand order.  From then on the wave's tiles alternate between its two
+    // slots, and the next tile is requested as soon as the current one's fragments are in registers (with
+    // a.depth == 2 the tile after that one is in flight as well).
     first_page();
     if (n_all > 0) fetch(0);
     bf16x8 qf[NQT][8];
@@ -378,7 +381,8 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
     if (n_all > 0) {  // not a surplus wave of the sequence's last workgroup
-    if (n_all > 1) fetch(1);
+    const int D = a.depth;  // uniform
+    if (D == 2 && n_all > 1) fetch(1);
 
     // Every load older than the second tile's eight (first tile, query rows) is covered
     // by the first wait of the sweep.  Tiles that lie entirely inside the keys every query row sees (all L
@@ -395,12 +399,12 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     // One sweep over the wave's tiles (the first two are already requested).  FAST: the first tile sets each
     // lane's offset m to the maximum of its logits there, later tiles keep it -- no maximum to track.
     auto full_tile = [&](int k, auto fixed) __attribute__((always_inline)) {
-        wait_tile_landed(k + 1 < n_all);
+        wait_tile_landed(D == 2 && k + 1 < n_all);
         bf16x8 kf[8];
         lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
-        if (k + 2 < n_all) {
+        if (k + D < n_all) {
             wait_frags_read();
-            fetch(k + 2);
+            fetch(k + D);
         }
         int valid[NQT];
 #pragma unroll
@@ -408,12 +412,12 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         stats_tile<NQT, false, decltype(fixed)::value>(kf, qf, m, z, c, valid, half);
     };
     auto masked_tile = [&](int k, const int (&valid)[NQT], bool fixed) __attribute__((always_inline)) {
-        wait_tile_landed(k + 1 < n_all);
+        wait_tile_landed(D == 2 && k + 1 < n_all);
         bf16x8 kf[8];
         lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
-        if (k + 2 < n_all) {
+        if (k + D < n_all) {
             wait_frags_read();
-            fetch(k + 2);
+            fetch(k + D);
         }
         if (fixed) stats_tile<NQT, true, true>(kf, qf, m, z, c, valid, half);
         else stats_tile<NQT, true, false>(kf, qf, m, z, c, valid, half);
@@ -447,7 +451,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         wait_frags_read();
         first_page();
         fetch(0);
-        if (n_all > 1) fetch(1);
+        if (D == 2 && n_all > 1) fetch(1);
         sweep(std::false_type{});
     }
 
@@ -633,7 +637,8 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         __syncthreads();  // the slot is refilled with a key tile next
     }
     if (w.n_tiles == 0) return;  // surplus wave of the sequence's last workgroup
-    if (w.n_tiles > 1) fetch(1);
+    const int D = a.depth;  // uniform
+    if (D == 2 && w.n_tiles > 1) fetch(1);
     if (!fused) {
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
@@ -669,15 +674,15 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     };
 
     // everything older than the second tile's eight loads (first tile, Q, the -beta/c terms) is in after this
-    wait_tile_landed(w.n_tiles > 1);
+    wait_tile_landed(D == 2 && w.n_tiles > 1);
     for (int k = 0; k < w.n_tiles; ++k) {
-        if (k > 0) wait_tile_landed(k + 1 < w.n_tiles);
+        if (k > 0) wait_tile_landed(D == 2 && k + 1 < w.n_tiles);
         bf16x8 kf[8];
         lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
         if (k > 0) store_tile(k - 1, pending);
-        if (k + 2 < w.n_tiles) {  // issued after the store: only these 8 loads are newer than tile k+1
+        if (k + D < w.n_tiles) {  // issued after the store: only these 8 loads are newer than tile k+1
             wait_frags_read();
-            fetch(k + 2);
+            fetch(k + D);
         }
         // Software pipeline over the query-row tiles: the MFMA chain of tile qt+1 is issued between the
         // exp2/add instructions of tile qt (a wave issues in order, so without interleaving its VALU work
@@ -750,6 +755,16 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.n_layers = p.n_layers; a.n_seq = p.n_seq; a.n_q = p.n_q; a.h_q = p.h_q; a.h_kv = p.h_kv;
     a.group = p.group; a.rows = p.rows; a.RP = p.row_tiles * kRowTile;
     a.window = p.window;
+    // Key tiles a wave keeps in flight: one.  The next tile is requested as soon as the current one's fragments are
+    // in registers and arrives while the wave computes; a second tile in flight only queues in the memory system
+    // (both passes already move data at the rate a plain read of K reaches) and costs the second pass 2.5 us on
+    // the 128K layer (46.7 -> 44.2 us; first pass 47.3 -> 46.8).
+    auto depth_knob = [](const char* name, int dflt) {  // ablation knobs
+        const char* env = std::getenv(name);
+        return env && (env[0] == '1' || env[0] == '2') && env[1] == 0 ? env[0] - '0' : dflt;
+    };
+    const int depth_cold = depth_knob("JQ_DEPTH_1", 1), depth_second = depth_knob("JQ_DEPTH_2", 1);
+    a.depth = depth_cold;
     a.group_shift = -1;
     for (int sh = 0; sh < 16; ++sh)
         if (p.group == (1 << sh)) a.group_shift = sh;
@@ -795,6 +810,7 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         for (int s = 0; s <= p.n_seq; ++s) { a.tab.cu_chunk[s] = p.cu_chunk2[s]; a.tab.cu_cgrp[s] = p.cu_cgrp2[s]; }
         a.n_cgrp = p.cu_cgrp2[p.n_seq];
         grid = dim3((unsigned)((int64_t)p.n_layers * a.n_cgrp * p.h_kv));
+        a.depth = depth_second;
     }
     for (int rg = 0; rg < p.row_groups; ++rg) {
         a.row_tile0 = rg * kMaxRowTiles;
