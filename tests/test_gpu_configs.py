@@ -1,8 +1,9 @@
 """GPU parity of the fused jq_evict on the five named workloads at their full sizes, in the
-launch configuration bench.py times (one call per workload).  Where the oracle would take minutes
-(32 layers, 16 ragged sequences) it checks sampled layers / sequences element by element, and every
-other output through properties that hold at any size: kept positions ascending and in range, the
-pruned cache bit-identical to a gather of the library's own positions, pooled mass conserved."""
+launch configuration bench.py times (one call per workload).  Every layer of the 32-layer workload
+and every sequence of the ragged batch is compared with the oracle element by element (unpooled
+scores from jq_score, pooled scores, kept sets, pruned cache); properties that hold at any size --
+kept positions ascending and in range, the pruned cache bit-identical to a gather of the library's
+own positions, pooled mass conserved -- are checked on the device on top of that."""
 import numpy as np
 import pytest
 
@@ -25,10 +26,13 @@ def shape_of(w):
                     budgets=w.budgets)
 
 
-def check_problem_against_oracle(w, Q, K, V, pooled_h, idx_h, Ko_h, Vo_h, what):
-    """One (layer, sequence): Q [n_q,h_q,d], K/V [L,h_kv,d] host bits; GPU outputs for that problem."""
+def check_problem_against_oracle(w, Q, K, V, pooled_h, idx_h, Ko_h, Vo_h, what, raw_h=None):
+    """One (layer, sequence): Q [n_q,h_q,d], K/V [L,h_kv,d] host bits; GPU outputs for that problem
+    (`raw_h`: the unpooled scores of jq_score for the same problem, compared as well when given)."""
     L, B = K.shape[0], idx_h.shape[1]
     ref_s = oracle.score(Q, K)
+    if raw_h is not None:
+        assert_scores_close(raw_h, ref_s, w.n_q * w.group / L, what + " unpooled")
     ref_p = oracle.pool(ref_s, w.pool_k)
     assert_scores_close(pooled_h, ref_p, w.n_q * w.group / L, what + " pooled")
     ref_idx = oracle.select_topk(ref_p, B)
@@ -99,11 +103,13 @@ def test_config3_mistral_layer_128k():
     w = make_workload(3)
     Q, K, V = w.assemble()
     Kd, Vd = to_dev_bf16(K), to_dev_bf16(V)
-    Ko, Vo, idx, pooled = jq.evict(shape_of(w), to_dev_bf16(Q), Kd, Vd)
+    Qd = to_dev_bf16(Q)
+    Ko, Vo, idx, pooled = jq.evict(shape_of(w), Qd, Kd, Vd)
+    raw = jq.score(shape_of(w), Qd, Kd)
     torch.cuda.synchronize()
     check_properties_on_device(torch, w, Kd, Vd, Ko, Vo, idx, pooled)
     check_problem_against_oracle(w, Q[0, 0], K[0], V[0], pooled[0].cpu().numpy(), idx[0].cpu().numpy(),
-                                 from_dev_bf16(Ko)[0], from_dev_bf16(Vo)[0], "config 3")
+                                 from_dev_bf16(Ko)[0], from_dev_bf16(Vo)[0], "config 3", raw_h=raw[0].cpu().numpy())
 
 
 def test_config3_paged_cache_with_sinks_and_window():
@@ -134,55 +140,70 @@ def test_config3_paged_cache_with_sinks_and_window():
         assert_kept_set_ok_keep(ref_p[g], ref_idx[g], idx_h[g], kf, kl, "config 3 forced head %d" % g)
 
 
-def test_config4_thirty_two_layers():
+@pytest.fixture(scope="module")
+def config4_call():
+    """The 32-layer workload through ONE jq_evict call (and one jq_score call); host copies of the inputs are kept for the
+    oracle (8 GiB), device tensors are dropped when the module's tests are done."""
     torch = torch_()
     w = make_workload(4)
     nl, L = w.n_layers, w.seq_lens[0]
-    sampled = {0: None, 13: None, 31: None}
     Qd = torch.empty((nl, 1, w.n_q, w.h_q, w.d), dtype=torch.bfloat16, device="cuda")
     Kd = torch.empty((nl, L, w.h_kv, w.d), dtype=torch.bfloat16, device="cuda")
     Vd = torch.empty_like(Kd)
+    host = []
     for l in range(nl):                                  # 8 GiB of inputs: generated and uploaded layer by layer
         q, k, v = w.tensors(l, 0)
         Qd[l, 0].copy_(to_dev_bf16(q)); Kd[l].copy_(to_dev_bf16(k)); Vd[l].copy_(to_dev_bf16(v))
-        if l in sampled:
-            sampled[l] = (q, k, v)
+        host.append((q, k, v))
         if l % 8 == 7:
             print("config 4: layer", l, "generated", flush=True)
     Ko, Vo, idx, pooled = jq.evict(shape_of(w), Qd, Kd, Vd)
+    raw = jq.score(shape_of(w), Qd, Kd)
     torch.cuda.synchronize()
     assert tuple(Ko.shape) == (32, 1024, 8, 128) and Ko.is_contiguous() and tuple(Vo.shape) == (32, 1024, 8, 128)
     check_properties_on_device(torch, w, Kd, Vd, Ko, Vo, idx, pooled)
-    for l, (q, k, v) in sampled.items():
-        print("config 4: oracle on layer", l, flush=True)
+    yield w, host, Ko, Vo, idx, pooled, raw
+    del Qd, Kd, Vd, Ko, Vo, idx, pooled, raw, host
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("first", [0, 8, 16, 24])
+def test_config4_thirty_two_layers(config4_call, first):
+    # every layer of the one 32-layer call against the oracle, eight layers per test
+    w, host, Ko, Vo, idx, pooled, raw = config4_call
+    for l in range(first, first + 8):
+        q, k, v = host[l]
         check_problem_against_oracle(w, q, k, v, pooled[l].cpu().numpy(), idx[l].cpu().numpy(),
-                                     from_dev_bf16(Ko[l]), from_dev_bf16(Vo[l]), "config 4 layer %d" % l)
+                                     from_dev_bf16(Ko[l]), from_dev_bf16(Vo[l]), "config 4 layer %d" % l,
+                                     raw_h=raw[l].cpu().numpy())
+        print("config 4: layer", l, "matches the oracle", flush=True)
 
 
+@pytest.mark.timeout(600)
 def test_config5_ragged_batch():
     torch = torch_()
     w = make_workload(5)
     T = w.total_tokens
     cu, cb = w.cu_seqlens, w.cu_budgets
-    order = np.argsort(w.seq_lens)
-    sampled = {int(order[0]): None, int(order[len(order) // 2]): None, int(order[-1]): None}
     Qd = torch.empty((1, w.n_seq, w.n_q, w.h_q, w.d), dtype=torch.bfloat16, device="cuda")
     Kd = torch.empty((1, T, w.h_kv, w.d), dtype=torch.bfloat16, device="cuda")
     Vd = torch.empty_like(Kd)
     for s in range(w.n_seq):
         q, k, v = w.tensors(0, s)
         Qd[0, s].copy_(to_dev_bf16(q)); Kd[0, cu[s]:cu[s + 1]].copy_(to_dev_bf16(k)); Vd[0, cu[s]:cu[s + 1]].copy_(to_dev_bf16(v))
-        if s in sampled:
-            sampled[s] = (q, k, v)
     print("config 5: %d tokens generated" % T, flush=True)
     Ko, Vo, idx, pooled = jq.evict(shape_of(w), Qd, Kd, Vd)        # a single fused call for all 16 sequences
+    raw = jq.score(shape_of(w), Qd, Kd)
     torch.cuda.synchronize()
     check_properties_on_device(torch, w, Kd, Vd, Ko, Vo, idx, pooled)
-    for s, (q, k, v) in sampled.items():
-        print("config 5: oracle on sequence", s, "L =", w.seq_lens[s], flush=True)
+    for s in range(w.n_seq):                                       # every sequence against the oracle
+        q, k, v = w.tensors(0, s)
         check_problem_against_oracle(w, q, k, v, pooled[0, :, cu[s]:cu[s + 1]].cpu().numpy(),
                                      idx[0, :, cb[s]:cb[s + 1]].cpu().numpy(), from_dev_bf16(Ko[0, cb[s]:cb[s + 1]]),
-                                     from_dev_bf16(Vo[0, cb[s]:cb[s + 1]]), "config 5 seq %d" % s)
+                                     from_dev_bf16(Vo[0, cb[s]:cb[s + 1]]), "config 5 seq %d" % s,
+                                     raw_h=raw[0, :, cu[s]:cu[s + 1]].cpu().numpy())
+        print("config 5: sequence", s, "L =", w.seq_lens[s], "matches the oracle", flush=True)
 
 
 def test_sequence_just_below_the_four_gib_limit():
