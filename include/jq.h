@@ -1,15 +1,15 @@
 /*
  * jq.h -- C ABI of the Judge Q KV-cache eviction hot path for AMD MI355X (gfx950).
  *
- * At the end of prefill the method (paper Section 4.3, "Optimizing KV Cache
- * Eviction via Soft Tokens during Inference") scores every prompt key by the
- * attention it receives from the appended soft-token queries (Eq. 3), keeps the
- * key-value pairs with the top-k scores and decodes on the pruned cache.  This
- * library is that path, per layer and per KV head, as HIP kernels:
+ * At the end of prefill the method (paper Section 4.3, the inference-time use of
+ * the trained soft tokens) scores every prompt key by the attention it receives
+ * from the appended soft-token queries (Eq. 3), keeps the key-value pairs with
+ * the top-k scores and decodes on the pruned cache.  This library is that path,
+ * per layer and per KV head, as HIP kernels:
  *
  *   jq_score        attention map of the soft tokens over the prompt (Eq. 3)
- *   jq_pool         1-D average pooling of the map ("pooling configurations",
- *                   Section 5.1, Baselines)
+ *   jq_pool         1-D average pooling of the map (the pooling settings that
+ *                   Section 5.1, Baselines, shares with the compared methods)
  *   jq_select_topk  top-B retention per KV head (Section 4.3)
  *   jq_compact      gather of the kept K/V rows into a dense pruned cache
  *   jq_compact_inplace  the same, written over the front of K and V themselves
@@ -43,8 +43,9 @@
  *   averaged) over the n_q soft tokens and the h_q/h_kv heads of the group, so
  *   the unpooled scores of a (layer, sequence, KV head) sum to n_q * h_q / h_kv.
  * - The caller owns every buffer.  The library allocates nothing, keeps no
- *   state between calls, never synchronises the stream and may be called from
- *   several host threads at once.  `stream` is a hipStream_t passed as void*
+ *   state between calls (apart from the knobs below, read once, and a one-time
+ *   per-device raise of one kernel's LDS limit), never synchronises the stream
+ *   and may be called from several host threads at once.  `stream` is a hipStream_t passed as void*
  *   (NULL = the default stream).  Work is only enqueued; results are ready when
  *   the stream reaches the end of the enqueued work.
  * - Every entry point returns a jq_status.  All argument errors are detected
@@ -67,8 +68,11 @@ typedef enum jq_status {
     JQ_ERR_NULL = -1,        /* a required pointer is NULL                               */
     JQ_ERR_SHAPE = -2,       /* a dimension, pool_k, scale or cu_seqlens is malformed    */
     JQ_ERR_BUDGET = -3,      /* some budget is outside 1..L_s, or below keep_first+keep_last */
-    JQ_ERR_UNSUPPORTED = -4, /* valid but not implemented (d != 128, too many sequences, */
-                             /* a sequence of 4 GiB or more of keys, a misaligned tensor) */
+    JQ_ERR_UNSUPPORTED = -4, /* valid but not implemented: d != 128, more than JQ_MAX_SEQ  */
+                             /* sequences, more than 65535 layers or 256 KV heads, more    */
+                             /* than 2^20 query rows per KV head, a sequence (or a layer's */
+                             /* page pool) with 4 GiB or more of keys, 2^31 or more kept   */
+                             /* rows or workgroups in one call, a misaligned tensor        */
     JQ_ERR_WORKSPACE = -5,   /* workspace missing, misaligned (16 B) or too small        */
     JQ_ERR_ALIAS = -6,       /* an output overlaps an input or another output            */
     JQ_ERR_LAUNCH = -7       /* the HIP runtime refused a launch                         */
@@ -110,9 +114,11 @@ typedef struct jq_shape {
                                /* sequence's LARGEST budget and with it the layout of idx / K_out /     */
                                /* V_out; layer l keeps layer_budgets[l, s] positions of sequence s and  */
                                /* writes only the first that many slots of the sequence's segment (the  */
-                               /* rest is left untouched).  Read on the device only: a value outside    */
-                               /* 1..budgets[s] is clamped into that range.  Used by jq_select_topk,    */
-                               /* jq_compact and jq_evict*.                                              */
+                               /* rest is left untouched).  Read on the device only, so it cannot be    */
+                               /* validated: a value outside max(1, keep_first + keep_last) ..           */
+                               /* budgets[s] is clamped into that range (the always-kept positions are   */
+                               /* kept in every layer; keep_last counts as at least n_q in window mode). */
+                               /* Used by jq_select_topk, jq_compact, jq_compact_inplace and jq_evict*.  */
 } jq_shape;
 
 /* Bytes of device workspace that jq_score, jq_select_topk and jq_evict need for
@@ -152,12 +158,16 @@ int jq_score_lse(const jq_shape* shape, const void* Q, const void* K, const floa
 int jq_score_tail(const jq_shape* shape, const void* Q, const void* K, const void* K_tail, float* scores,
                   void* ws, size_t ws_bytes, void* stream);
 
-/* pooled[l,g,t] = (1/pool_k) * sum_{|u| <= (pool_k-1)/2} scores[l,g,t+u], taking
+/* Pooling of the attention map before the selection (Section 5.1, Baselines: the method runs with the
+ * local-window and pooling settings of the compared methods; the paper gives no operator, this library reads
+ * it as a 1-D average with zero padding):
+ * pooled[l,g,t] = (1/pool_k) * sum_{|u| <= (pool_k-1)/2} scores[l,g,t+u], taking
  * zero for positions outside t's own sequence (divisor is always pool_k).
  * `pooled` must not overlap `scores`. */
 int jq_pool(const jq_shape* shape, const float* scores, float* pooled, void* stream);
 
-/* For every (layer, sequence, KV head): the budgets[s] positions with the largest
+/* Top-k retention (Section 4.3: the key-value pairs with the highest scores stay, the rest is discarded).
+ * For every (layer, sequence, KV head): the budgets[s] positions with the largest
  * pooled value; equal values are resolved towards the lower position; positions
  * are written in ascending order.  Exact for any finite fp32 input (-0 == +0).
  * The first keep_first and last keep_last positions of a sequence are always among
@@ -166,7 +176,8 @@ int jq_pool(const jq_shape* shape, const float* scores, float* pooled, void* str
 int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx,
                    void* ws, size_t ws_bytes, void* stream);
 
-/* K_out[l, cu_budgets[s]+b, g, :] = K[l, cu_seqlens[s] + idx[l,g,cu_budgets[s]+b], g, :]
+/* The pruned cache that decoding continues on (Section 4.3), as a gather of the kept rows:
+ * K_out[l, cu_budgets[s]+b, g, :] = K[l, cu_seqlens[s] + idx[l,g,cu_budgets[s]+b], g, :]
  * and the same for V, as 16-bit patterns.  An index outside 0..L_s-1 is clamped
  * into that range (never dereferenced out of bounds). */
 int jq_compact(const jq_shape* shape, const void* K, const void* V, const int32_t* idx,
@@ -204,7 +215,8 @@ int jq_hit_rate(const jq_shape* shape, const int32_t* idx_cur, const int32_t* id
 int jq_map_mse(const jq_shape* shape, const float* scores_a, float rows_a, const float* scores_b, float rows_b,
                float* mse, void* stream);
 
-/* score -> pool -> select -> compact in one call.  `idx_out` (kept positions) and
+/* The whole eviction step of Section 4.3 at the end of prefill (Eq. 3 scores -> pooling -> top-k retention ->
+ * pruned cache) for n_layers x n_seq problems: score -> pool -> select -> compact in one call.  `idx_out` (kept positions) and
  * `scores_out` (POOLED scores) may each be NULL when the caller does not want
  * them; the workspace then holds them. */
 int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V,
@@ -278,6 +290,14 @@ int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const v
  * `bytes` bytes (a multiple of 16; 16-byte aligned, non-overlapping DEVICE buffers).
  * Profilers read its known traffic to calibrate their HBM byte counters. */
 int jq_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
+
+/* Ablation and diagnosis knobs.  The library reads a few environment variables ONCE per process, at its first
+ * call (never on the path of a later call): JQ_CHUNK_KEYS / JQ_CHUNK_KEYS_2 (keys per wave in the first / second
+ * pass over K, multiples of 32 up to 8192), JQ_DEPTH_1 / JQ_DEPTH_2 (key tiles a wave keeps in flight, 1 or 2),
+ * JQ_LOG (print the HIP error string when a launch is refused).  Results do not depend on them beyond rounding
+ * order.  jq_reload_knobs reads the environment again; it must not run concurrently with other calls (tests use
+ * it to force rarely taken code paths at small sizes).  Always returns JQ_OK. */
+int jq_reload_knobs(void);
 
 /* Static, never-NULL description of a status code. */
 const char* jq_status_string(int status);

@@ -2,8 +2,8 @@
  * CPU oracle for the Judge Q eviction hot path -- TEST INFRASTRUCTURE ONLY.
  *
  * A plain, slow fp64 implementation of what the method computes at the end of
- * prefill (paper Section 4.3 "Optimizing KV Cache Eviction via Soft Tokens
- * during Inference", Eq. 3): the attention map of the soft-token queries over
+ * prefill (paper Section 4.3, the inference-time use of the soft tokens,
+ * Eq. 3): the attention map of the soft-token queries over
  * the prompt keys, top-k retention on that map, and the pruned cache.  It is
  * used by the tests, the smoke check and the benchmark's CPU baseline leg to
  * judge the HIP kernels; it shares no code with them and the product path must
@@ -267,7 +267,7 @@ int jqo_score_window(int n_q, int h_q, int h_kv, int d, long L, double scale, co
 }
 
 /*
- * 1-D average pooling of one head's scores ("pooling configurations",
+ * 1-D average pooling of one head's scores (the pooling settings of the
  * Section 5.1 baselines paragraph).  Reading: stride 1, same-length output,
  * zeros outside [0, L), divisor always pool_k (so the first and last
  * (pool_k-1)/2 outputs are damped).  pool_k must be odd and >= 1.

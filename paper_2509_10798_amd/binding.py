@@ -22,7 +22,7 @@ JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
 EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
-           "jq_copy_probe", "jq_status_string")
+           "jq_copy_probe", "jq_reload_knobs", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel", "jq_select_finalize_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
 
@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
         L.jq_evict_paged.argtypes = [shp, pgp, pgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_traced.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp), ctypes.c_int]
         L.jq_copy_probe.argtypes = [vp, vp, sz, vp]
+        L.jq_reload_knobs.argtypes = []
         L.jq_status_string.argtypes = [ctypes.c_int]
         L.jq_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -350,6 +351,11 @@ def map_mse(shape: Shape, scores_a, rows_a: float, scores_b, rows_b: float, mse=
     _check(lib().jq_map_mse(ctypes.byref(cs), _ptr(scores_a), float(rows_a), _ptr(scores_b), float(rows_b), _ptr(mse),
                             _stream(stream)), "jq_map_mse")
     return mse
+
+
+def reload_knobs() -> None:
+    """Make the library read its ablation knobs (JQ_CHUNK_KEYS, JQ_DEPTH_1, ...) from the environment again."""
+    _check(lib().jq_reload_knobs(), "jq_reload_knobs")
 
 
 def copy_probe(src, dst, stream=None):

@@ -1,5 +1,6 @@
 // C ABI of libjq: argument validation, planning (wave counts, workspace layout) and the launch
 // sequences.  Everything here runs on the host; no HIP call is made before validation succeeds.
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -7,6 +8,32 @@
 #include "jq_common.h"
 
 namespace jq {
+
+static Knobs read_knobs() {
+    Knobs k{};
+    auto chunk = [](const char* name) {
+        const char* env = std::getenv(name);
+        const long v = env ? std::atol(env) : 0;
+        return (int32_t)((v >= kKeyTile && v <= 8192 && v % kKeyTile == 0) ? v : 0);
+    };
+    auto depth = [](const char* name) {
+        const char* env = std::getenv(name);
+        return (int32_t)(env && (env[0] == '1' || env[0] == '2') && env[1] == 0 ? env[0] - '0' : 1);
+    };
+    k.chunk_keys = chunk("JQ_CHUNK_KEYS");
+    k.chunk_keys2 = chunk("JQ_CHUNK_KEYS_2");
+    if (!std::getenv("JQ_CHUNK_KEYS_2")) k.chunk_keys2 = k.chunk_keys;
+    k.depth1 = depth("JQ_DEPTH_1");
+    k.depth2 = depth("JQ_DEPTH_2");
+    k.log = std::getenv("JQ_LOG") != nullptr;
+    return k;
+}
+static Knobs& knobs_storage() {
+    static Knobs k = read_knobs();  // first use, thread-safe
+    return k;
+}
+const Knobs& knobs() { return knobs_storage(); }
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -82,16 +109,13 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     // Infinity Cache and has more arithmetic per tile; it does better with two waves per SIMD.  The cap makes
     // big calls run in several rounds.
     const int64_t keys = (int64_t)p.n_layers * p.h_kv * p.T;
-    auto plan_waves = [&](int64_t target_waves, const char* knob, int32_t* cu_chunk, int32_t* cu_cgrp, int32_t* chunk_keys,
+    auto plan_waves = [&](int64_t target_waves, int32_t knob, int32_t* cu_chunk, int32_t* cu_cgrp, int32_t* chunk_keys,
                           int32_t* n_chunks) {
         int64_t chunk = (keys + target_waves - 1) / target_waves;
         chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
         if (chunk < 64) chunk = 64;
         if (chunk > 1024) chunk = 1024;
-        if (const char* env = std::getenv(knob)) {  // ablation knob
-            const long v = std::atol(env);
-            if (v >= kKeyTile && v <= 8192 && v % kKeyTile == 0) chunk = v;
-        }
+        if (knob) chunk = knob;  // ablation knob
         int64_t nc = 0, ng = 0;
         cu_chunk[0] = 0;
         cu_cgrp[0] = 0;
@@ -107,9 +131,8 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
         *n_chunks = (int32_t)nc;
         return ng;
     };
-    const int64_t ng = plan_waves(1024, "JQ_CHUNK_KEYS", p.tab.cu_chunk, p.tab.cu_cgrp, &p.chunk_keys, &p.n_chunks);
-    const int64_t ng2 = plan_waves(2048, std::getenv("JQ_CHUNK_KEYS_2") ? "JQ_CHUNK_KEYS_2" : "JQ_CHUNK_KEYS", p.cu_chunk2,
-                                   p.cu_cgrp2, &p.chunk_keys2, &p.n_chunks2);
+    const int64_t ng = plan_waves(1024, knobs().chunk_keys, p.tab.cu_chunk, p.tab.cu_cgrp, &p.chunk_keys, &p.n_chunks);
+    const int64_t ng2 = plan_waves(2048, knobs().chunk_keys2, p.cu_chunk2, p.cu_cgrp2, &p.chunk_keys2, &p.n_chunks2);
     if ((int64_t)p.n_layers * (ng > ng2 ? ng : ng2) * p.h_kv >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
     if ((int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
 
@@ -191,7 +214,7 @@ size_t tail_bytes(const Plan& p) { return (size_t)p.n_layers * p.n_seq * p.n_q *
 
 inline int launch_status(hipError_t e) {
     if (e == hipSuccess) return JQ_OK;
-    if (std::getenv("JQ_LOG")) std::fprintf(stderr, "libjq: launch failed: %s\n", hipGetErrorString(e));
+    if (knobs().log) std::fprintf(stderr, "libjq: launch failed: %s\n", hipGetErrorString(e));
     return JQ_ERR_LAUNCH;
 }
 
@@ -458,13 +481,21 @@ int jq_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
     return launch_status(launch_copy_probe(src, dst, bytes, (hipStream_t)stream));
 }
 
+int jq_reload_knobs(void) {
+    knobs_storage() = read_knobs();
+    return JQ_OK;
+}
+
 const char* jq_status_string(int status) {
     switch (status) {
         case JQ_OK: return "ok";
         case JQ_ERR_NULL: return "a required pointer is NULL";
         case JQ_ERR_SHAPE: return "malformed shape (dimension, pool_k, scale or cu_seqlens)";
         case JQ_ERR_BUDGET: return "a budget is outside 1..L or below keep_first + keep_last";
-        case JQ_ERR_UNSUPPORTED: return "valid but unsupported (d != 128, too many sequences, or misaligned tensor)";
+        case JQ_ERR_UNSUPPORTED:
+            return "valid but unsupported (d != 128, more than JQ_MAX_SEQ sequences, more than 65535 layers or 256 KV heads, "
+                   "a sequence or a layer's page pool with 4 GiB or more of keys, more than 2^31 - 1 kept rows or "
+                   "workgroups in one call, or a misaligned tensor)";
         case JQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case JQ_ERR_ALIAS: return "an output overlaps an input or another output";
         case JQ_ERR_LAUNCH: return "the HIP runtime refused a launch";

@@ -78,21 +78,28 @@ __device__ inline uint32_t sortable_key(float x) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+// A block-table entry as every kernel uses it: entries outside the pool (a corrupt table, the -1 of an unused slot)
+// are clamped into it, so that the scored keys and the gathered rows always come from the same page.
+__host__ __device__ inline int32_t clamp_page(int32_t entry, int32_t n_pages) {
+    return entry < 0 ? 0 : (entry > n_pages - 1 ? n_pages - 1 : entry);
+}
+
 // Row (in units of token rows, over all layers) of token `pos` of sequence `s`; `cu` holds the sequences' dense
-// offsets (token offsets for the cache, kept-row offsets for the pruned cache) and T their total.  A table entry
-// outside the pool is clamped into it.
+// offsets (token offsets for the cache, kept-row offsets for the pruned cache) and T their total.
 __device__ inline int64_t kv_row(const PageMap& pm, const int32_t* cu, int64_t T, int layer, int s, int pos) {
     if (!pm.block_table) return (int64_t)layer * T + cu[s] + pos;
     const int32_t e = pm.block_table[(int64_t)s * pm.max_pages + (pos >> pm.page_shift)];
-    const int64_t page = (int64_t)layer * pm.n_pages + min(max(e, 0), pm.n_pages - 1);
+    const int64_t page = (int64_t)layer * pm.n_pages + clamp_page(e, pm.n_pages);
     return (page << pm.page_shift) + (pos & ((1 << pm.page_shift) - 1));
 }
 
-// Budget of (layer, sequence): the table's segment length, or the caller's per-layer value clamped into 1..that.
-__device__ inline uint32_t budget_of(const int32_t* layer_budgets, const SeqTab& tab, int layer, int s) {
+// Budget of (layer, sequence): the table's segment length, or the caller's per-layer value clamped into
+// max(1, forced) .. that, where `forced` = keep_first + keep_last is the number of positions that are kept whatever
+// they score (the host has checked forced <= segment length; it cannot see the per-layer values).
+__device__ inline uint32_t budget_of(const int32_t* layer_budgets, const SeqTab& tab, int layer, int s, int forced) {
     const int32_t cap = tab.cu_bud[s + 1] - tab.cu_bud[s];
     if (!layer_budgets) return (uint32_t)cap;
-    return (uint32_t)min(max(layer_budgets[(int64_t)layer * tab.n_seq + s], 1), cap);
+    return (uint32_t)min(max(layer_budgets[(int64_t)layer * tab.n_seq + s], max(forced, 1)), cap);
 }
 
 // Key the top-B selection ranks position j of an L-token sequence by: always-kept positions outrank
@@ -100,6 +107,16 @@ __device__ inline uint32_t budget_of(const int32_t* layer_budgets, const SeqTab&
 __device__ inline uint32_t select_key(float x, int j, int L, int keep_first, int keep_last) {
     return (j < keep_first || j >= L - keep_last) ? 0xFFFFFFFFu : sortable_key(x);
 }
+
+// Ablation and diagnosis knobs, read from the environment ONCE per process (first use) -- no entry point touches the
+// environment on its hot path.  jq_reload_knobs() reads them again (tests use it to force rarely taken paths).
+struct Knobs {
+    int32_t chunk_keys;   // JQ_CHUNK_KEYS: keys per wave in the pass that reads K cold (0: planned from the call's size)
+    int32_t chunk_keys2;  // JQ_CHUNK_KEYS_2: the same for the second pass (0: JQ_CHUNK_KEYS if set, else planned)
+    int32_t depth1, depth2;  // JQ_DEPTH_1 / JQ_DEPTH_2: key tiles a wave keeps in flight (1 or 2)
+    int32_t log;          // JQ_LOG: print the HIP error string when a launch is refused
+};
+const Knobs& knobs();
 
 // Kernels whose start/stop timestamps jq_evict_traced reports, in launch order.
 enum TraceKernel { kTrStats = 0, kTrScore, kTrPool, kTrScatter, kTrFinalize, kTraceKernels };

@@ -16,6 +16,7 @@ struct CompactArgs {
     PageMap pm;      // where the rows of K and V live (dense or paged)
     PageMap pm_out;  // where the kept rows go
     const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null: slots beyond a layer's own budget are skipped
+    int32_t forced;                // keep_first + keep_last: the least a per-layer budget can be
     SeqTab tab;
 };
 
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_kernel(CompactArgs
     const int layer = (int)(rest / a.TB);
     const int s = find_seq(a.tab.cu_bud, a.tab.n_seq, tb);
     const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
-    if ((uint32_t)(tb - a.tab.cu_bud[s]) >= budget_of(a.layer_budgets, a.tab, layer, s)) return;
+    if ((uint32_t)(tb - a.tab.cu_bud[s]) >= budget_of(a.layer_budgets, a.tab, layer, s, a.forced)) return;
     int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
     j = min(max(j, 0), L - 1);  // never read outside the sequence
     const int64_t src = ((kv_row(a.pm, a.tab.cu_seq, a.T, layer, s, j) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
@@ -54,6 +55,7 @@ hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int
     a.pm = p.page_map();
     a.pm_out = p.out_map;
     a.layer_budgets = p.layer_budgets;
+    a.forced = p.keep_first + p.keep_last;
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
     return launch_kernel(jq_compact_kernel, dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads)),
@@ -71,6 +73,7 @@ struct InplaceArgs {
     int32_t n_layers, h_kv;
     int64_t T, TB;
     const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null
+    int32_t forced;                // keep_first + keep_last: the least a per-layer budget can be
     SeqTab tab;
 };
 
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_inplace_kernel(Inp
     const int layer = (int)(rest / a.TB);
     const int s = find_seq(a.tab.cu_bud, a.tab.n_seq, tb);
     const int L = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
-    if ((uint32_t)(tb - a.tab.cu_bud[s]) >= budget_of(a.layer_budgets, a.tab, layer, s)) return;  // slot not used by this layer
+    if ((uint32_t)(tb - a.tab.cu_bud[s]) >= budget_of(a.layer_budgets, a.tab, layer, s, a.forced)) return;  // slot not used by this layer
     int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
     j = min(max(j, 0), L - 1);
     const int64_t src_row = (int64_t)a.tab.cu_seq[s] + j;  // within the layer
@@ -112,6 +115,7 @@ hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t
     a.K = (char*)K; a.V = (char*)V; a.stage = (char*)stage; a.idx = idx;
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.layer_budgets = p.layer_budgets;
+    a.forced = p.keep_first + p.keep_last;
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
     const dim3 grid((unsigned)((threads + kCompactThreads - 1) / kCompactThreads));

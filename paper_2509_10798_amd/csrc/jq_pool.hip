@@ -1,4 +1,4 @@
-// 1-D average pooling of the importance scores (the "pooling configurations" the paper's
+// 1-D average pooling of the importance scores (the pooling settings the paper's
 // Section 5.1 shares with its baselines), fused with the first radix histogram that the top-B
 // selection needs, plus two small helpers (fill, standalone histogram).
 //

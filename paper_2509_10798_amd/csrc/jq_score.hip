@@ -27,7 +27,6 @@
 // contraction elements selected by (l >> 5); both operands use the same element order, so any
 // fixed channel permutation cancels.  Result: lane l holds column (l & 31), register v holds row
 // 8*(v/4) + 4*(l>>5) + (v&3).
-#include <cstdlib>
 #include <type_traits>
 
 #include "jq_common.h"
@@ -249,7 +248,7 @@ template <bool PAGED>
 __device__ __forceinline__ uint32_t tile_offset(const KeyStream& ks, int t, int page) {
     const uint32_t tok = (uint32_t)t * kKeyTile;
     if (!PAGED) return tok * ks.row_bytes;
-    const uint32_t p = min((uint32_t)page, ks.last_page);
+    const uint32_t p = (uint32_t)clamp_page(page, (int32_t)ks.last_page + 1);  // the same clamp as the gather's
     return ((p << ks.page_shift) + (tok & ks.page_mask)) * ks.row_bytes;
 }
 // One table word per tile, at a wave-uniform address.  The table is read-only for the whole launch, so it is
@@ -759,11 +758,7 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     // in registers and arrives while the wave computes; a second tile in flight only queues in the memory system
     // (both passes already move data at the rate a plain read of K reaches) and costs the second pass 2.5 us on
     // the 128K layer (46.7 -> 44.2 us; first pass 47.3 -> 46.8).
-    auto depth_knob = [](const char* name, int dflt) {  // ablation knobs
-        const char* env = std::getenv(name);
-        return env && (env[0] == '1' || env[0] == '2') && env[1] == 0 ? env[0] - '0' : dflt;
-    };
-    const int depth_cold = depth_knob("JQ_DEPTH_1", 1), depth_second = depth_knob("JQ_DEPTH_2", 1);
+    const int depth_cold = knobs().depth1, depth_second = knobs().depth2;  // ablation knobs (default 1)
     a.depth = depth_cold;
     a.group_shift = -1;
     for (int sh = 0; sh < 16; ++sh)

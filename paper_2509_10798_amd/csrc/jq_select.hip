@@ -1,6 +1,6 @@
-// Top-B retention per (layer, sequence, KV head) -- "retain the key-value pairs corresponding to
-// the top-k highest scores" (paper Section 4.3) -- as an exact radix select on the order-preserving
-// 32-bit key of the pooled fp32 score.  Ties go to the lower position; output is ascending.
+// Top-B retention per (layer, sequence, KV head): the B best-scored key-value pairs stay, the rest is
+// dropped (paper Section 4.3) -- as an exact radix select on the order-preserving 32-bit key of the
+// pooled fp32 score.  Ties go to the lower position; output is ascending.
 //
 //   level 1: bits 31..21, histogram supplied by the pooling kernel                    -> bin b1
 //   level 2: bits 20..10 of the elements in b1                                         -> bin b2
@@ -18,6 +18,8 @@
 //               its own range of output slots; in the fused eviction call it also gathers the K/V
 //               rows of those slots, so the pruned cache needs no further kernel.
 // General path (very long sequences): one workgroup per problem streams the row three times.
+#include <atomic>
+
 #include "jq_common.h"
 
 namespace jq {
@@ -113,7 +115,7 @@ __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
     p.s = (prob / a.h_kv) % a.tab.n_seq;
     p.layer = prob / (a.h_kv * a.tab.n_seq);
     p.L = a.tab.cu_seq[p.s + 1] - a.tab.cu_seq[p.s];
-    p.B = budget_of(a.layer_budgets, a.tab, p.layer, p.s);
+    p.B = budget_of(a.layer_budgets, a.tab, p.layer, p.s, a.keep_first + a.keep_last);
     p.x = a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s];
     p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
     p.hist = a.hist + (((int64_t)p.layer * a.tab.n_seq + p.s) * a.h_kv + p.g) * kHistStride;
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(Sele
 
     for (int s = s_first; s <= s_last; ++s) {  // almost always a single sequence
         uint32_t* hist = a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride;
-        const uint32_t B = budget_of(a.layer_budgets, a.tab, layer, s);
+        const uint32_t B = budget_of(a.layer_budgets, a.tab, layer, s, a.keep_first + a.keep_last);
         const int Ls = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
         pick_bin<kScatterThreads, kHistBins / kScatterThreads>(hist, kHistBins, B, tmp, res);
         const uint32_t b1 = res[0];
@@ -439,6 +441,22 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
 constexpr int kFinalizeFixedWords = 2048 + 1024 + 32 + 32;
 constexpr size_t kMaxLds = 160 * 1024;
 
+// Launches of the finalize kernel with more than 64 KiB of dynamic LDS need the function's limit raised.  That
+// is done once per device, to the fixed maximum any call can ask for (never to a call's own size: the attribute is
+// process-wide, and two host threads with different sequence lengths must not undo each other's setting).
+static hipError_t allow_large_lds() {
+    static std::atomic<uint64_t> done{0};  // bit d: device d has the limit raised
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute((const void*)jq_select_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)(kMaxLds - 1024));
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
                          const void* K, const void* V, void* K_out, void* V_out, bool* gathered) {
     SelectArgs a;
@@ -466,8 +484,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     hipError_t e = launch_kernel(jq_select_scatter_kernel, grid, dim3(kScatterThreads), 0, st, p.marks, kTrScatter, a);
     if (e != hipSuccess) return e;
     if (lds_bytes > 64 * 1024) {
-        e = hipFuncSetAttribute((const void*)jq_select_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds_bytes);
+        e = allow_large_lds();
         if (e != hipSuccess) return e;
     }
     // Slices per problem: enough workgroups to spread the emission (and the gather) over the chip, each with

@@ -15,3 +15,18 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def knobs(monkeypatch):
+    """Set ablation knobs of libjq (environment variables it reads once per process) for one test: knobs(JQ_CHUNK_KEYS="64")
+    sets them and makes the library read them again; they are restored afterwards."""
+    import paper_2509_10798_amd as jq
+
+    def set_knobs(**kw):
+        for k, v in kw.items():
+            monkeypatch.setenv(k, str(v))
+        jq.reload_knobs()
+    yield set_knobs
+    monkeypatch.undo()
+    jq.reload_knobs()

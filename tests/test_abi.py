@@ -181,3 +181,21 @@ def test_paged_descriptor_errors_come_before_any_launch():
     assert evict((64, 16, 5), out=(4, 4, 2, otab + 2)) == -4            # misaligned output table
     assert evict((64, 16, 5), out=(4, 4, 2, Ko + 64)) == -6             # output table inside the output pool
     assert evict((64, 16, 5), out=(4, 1 << 20, 2, otab), ko=K - (1 << 29)) == -6   # a large output pool reaches into K
+
+
+def test_knobs_are_read_once_and_again_on_request(monkeypatch):
+    # the environment is not consulted by ordinary calls: a knob set after the first call has no effect until
+    # jq_reload_knobs; the per-workgroup statistics area of the workspace shows which wave split is planned
+    sh = shape(seq_lens=[8192], budgets=[8])
+    jq.reload_knobs()
+    base = jq.workspace_bytes(sh)
+    monkeypatch.setenv("JQ_CHUNK_KEYS", "32")
+    assert jq.workspace_bytes(sh) == base
+    jq.reload_knobs()
+    assert jq.workspace_bytes(sh) > base          # one wave per 32 keys: more workgroups, more partial statistics
+    monkeypatch.setenv("JQ_CHUNK_KEYS", "33")     # not a multiple of the tile: ignored
+    jq.reload_knobs()
+    assert jq.workspace_bytes(sh) == base
+    monkeypatch.undo()
+    jq.reload_knobs()
+    assert jq.workspace_bytes(sh) == base

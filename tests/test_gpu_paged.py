@@ -99,6 +99,36 @@ def test_evict_paged_matches_oracle_and_dense(page_size):
                                 w.n_q * w.group / w.seq_lens[s])
 
 
+def test_block_table_entries_outside_the_pool_are_clamped_the_same_way_everywhere():
+    # a -1 (and a too large) entry INSIDE a sequence's range: the keys that are scored and the rows that are gathered
+    # must come from the same page, i.e. the call equals the call on the correspondingly clamped table
+    torch = torch_()
+    w = make_workload(1, seq_lens=[1500, 700], budget=[400, 200], n_layers=2)
+    Q, K, V, Kp, Vp, pages = paged_inputs(w, 64, seed=77)
+    sh = jq.Shape(n_layers=2, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    bad = pages.block_table.clone()
+    bad[0, 3] = -1; bad[0, 7] = pages.n_pages + 5; bad[1, 2] = -(2 ** 31)
+    good = bad.clone()
+    good[0, 3] = 0; good[0, 7] = pages.n_pages - 1; good[1, 2] = 0
+    Qd = to_dev_bf16(Q)
+    a = jq.evict_paged(sh, jq.Pages(page_size=64, n_pages=pages.n_pages, block_table=bad), Qd, Kp, Vp)
+    b = jq.evict_paged(sh, jq.Pages(page_size=64, n_pages=pages.n_pages, block_table=good), Qd, Kp, Vp)
+    torch.cuda.synchronize()
+    assert torch.equal(a[3], b[3]) and torch.equal(a[2], b[2])
+    assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16)) and torch.equal(a[1].view(torch.int16), b[1].view(torch.int16))
+    # and the clamped call is the dense call on the keys those pages hold
+    Kp_h, Vp_h, tab = from_dev_bf16(Kp), from_dev_bf16(Vp), good.cpu().numpy()
+    cu = w.cu_seqlens
+    Kd = np.empty_like(K); Vd = np.empty_like(V)
+    for s_, L in enumerate(w.seq_lens):
+        for t in range(L):
+            Kd[:, cu[s_] + t] = Kp_h[:, tab[s_, t // 64], t % 64]
+            Vd[:, cu[s_] + t] = Vp_h[:, tab[s_, t // 64], t % 64]
+    c = jq.evict(sh, Qd, to_dev_bf16(Kd), to_dev_bf16(Vd))
+    torch.cuda.synchronize()
+    assert torch.equal(a[3], c[3]) and torch.equal(a[2], c[2]) and torch.equal(a[0].view(torch.int16), c[0].view(torch.int16))
+
+
 def test_evict_paged_very_long_sequence_takes_the_separate_gather():
     # beyond the selection's LDS bitmaps the kept rows are gathered by the stand-alone copy kernel, which
     # has to follow the block table as well

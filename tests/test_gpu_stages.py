@@ -62,15 +62,19 @@ def test_score_with_peaked_softmax_and_custom_scale():
     run_score_case(1, [1500], 16, 8, 2, seed=12, scale=0.35, spread=1.5)
 
 
-@pytest.mark.parametrize("alpha,where", [(9.0, 3500), (9.0, 3), (7.0, 4999), (30.0, 2048), (9.0, 31)])
-def test_score_with_one_dominant_key(monkeypatch, alpha, where):
+@pytest.mark.parametrize("alpha,where,chunk", [(9.0, 3500, 1024), (9.0, 3, 1024), (7.0, 4999, 1024), (30.0, 2048, 1024), (9.0, 31, 1024),
+                                               (9.0, 3500, None), (30.0, 4100, None)])
+def test_score_with_one_dominant_key(knobs, alpha, where, chunk):
     # The statistics pass keeps the first tile's maximum as the softmax offset of a query row.  A key that
     # aligns with a query row, planted late, exceeds that offset by more than fp32 exp2 can hold
     # (alpha >= 9: the wave must fall back to the running maximum), by a large but representable factor
-    # (alpha = 7), or sits in the first tile itself, so that every later term underflows.
-    print("score dominant key", alpha, where, flush=True)
+    # (alpha = 7), or sits in the first tile itself, so that every later term underflows.  chunk None: no knob at
+    # all -- at the default work split this sequence gets 79 waves of two tiles each, and the planted key sits in
+    # the second tile of its wave, so the fallback is reached the way a caller would reach it.
+    print("score dominant key", alpha, where, chunk, flush=True)
     torch = torch_()
-    monkeypatch.setenv("JQ_CHUNK_KEYS", "1024")            # long waves: many tiles after the first
+    if chunk:
+        knobs(JQ_CHUNK_KEYS=str(chunk))                    # long waves: many tiles after the first
     rng = np.random.default_rng(15)
     L, n_q, h_q, h_kv, d = 5000, 16, 8, 2, 128
     Qf = rng.standard_normal((1, 1, n_q, h_q, d)).astype(np.float32)
@@ -89,18 +93,18 @@ def test_score_with_one_dominant_key(monkeypatch, alpha, where):
     assert ref[0, where] > 0.99 and got[0, where] > 0.99   # that query row's whole mass sits on the planted key
 
 
-def test_score_several_chunks_per_sequence(monkeypatch):
+def test_score_several_chunks_per_sequence(knobs):
     # force 64-key chunks so that one sequence is split over many waves and partial statistics merge
     print("score chunked", flush=True)
-    monkeypatch.setenv("JQ_CHUNK_KEYS", "64")
+    knobs(JQ_CHUNK_KEYS="64")
     run_score_case(1, [1111, 95], 16, 8, 2, seed=13)
 
 
-def test_score_with_hundreds_of_partial_statistics(monkeypatch):
+def test_score_with_hundreds_of_partial_statistics(knobs):
     # a sequence cut into more than 256 waves leaves more partials than the second pass merges by itself: the
     # separate merge launch runs (here forced by 64-key chunks)
     print("score with a merge launch", flush=True)
-    monkeypatch.setenv("JQ_CHUNK_KEYS", "64")
+    knobs(JQ_CHUNK_KEYS="64")
     run_score_case(1, [20000, 300], 16, 8, 2, seed=14)
 
 
@@ -148,8 +152,10 @@ def run_select_case(x, seq_lens, budgets, keep_first=0, keep_last=0):
 
 @pytest.mark.parametrize("seq_lens,budgets", [([1], [1]), ([7], [7]), ([100], [1]), ([5000], [256]),
                                                ([4097, 33, 9000], [512, 33, 1]), ([70000], [2048]),
+                                               ([300000], [2048]),    # bitmaps beyond 64 KiB of LDS: the raised limit
                                                ([700000], [3000])])   # too long for the LDS bitmaps: streaming path
 def test_select_is_exact_on_random_scores(seq_lens, budgets):
+    print("select case", seq_lens, budgets, flush=True)
     rng = np.random.default_rng(31)
     x = rng.random((2, 3, sum(seq_lens))).astype(np.float32)
     run_select_case(x, seq_lens, budgets)
@@ -432,6 +438,42 @@ def test_layer_dependent_budgets_in_one_call():
     i3 = idx3.cpu().numpy()
     assert (i3[0, :, 0] >= 0).all() and (i3[0, :, 1:cb[1]] == -7).all()            # 0 -> one kept position
     assert (i3[0, :, cb[1]:cb[2]] >= 0).all()                                      # 10^6 -> the sequence's cap
+
+
+def test_layer_budget_below_the_always_kept_positions_is_raised_to_them():
+    # a per-layer budget smaller than keep_first + keep_last cannot drop always-kept positions: it is raised to their
+    # number, in the selection, the gather and the in-place gather alike
+    torch = torch_()
+    L, h_kv, kf, kl, cap = 3000, 2, 4, 32, 200
+    rng = np.random.default_rng(38)
+    x = rng.random((3, h_kv, L)).astype(np.float32)
+    x[:, :, :kf] = 0.0; x[:, :, L - kl:] = -1.0                        # the forced positions score worst
+    lb = [[10], [kf + kl], [120]]                                      # below, at, above the forced count
+    lb_d = torch.tensor(lb, dtype=torch.int32, device="cuda")
+    sh = jq.Shape(n_layers=3, seq_lens=[L], n_q=1, h_q=h_kv, h_kv=h_kv, budgets=[cap], keep_first=kf, keep_last=kl,
+                  layer_budgets=lb_d)
+    idx = torch.full((3, h_kv, cap), -7, dtype=torch.int32, device="cuda")
+    jq.select_topk(sh, torch.from_numpy(x).cuda(), idx=idx)
+    K = rng.integers(0, 65536, (3, L, h_kv, 128)).astype(np.uint16)
+    V = rng.integers(0, 65536, (3, L, h_kv, 128)).astype(np.uint16)
+    Kd, Vd = to_dev_bf16(K), to_dev_bf16(V)
+    Ko = torch.full((3, cap, h_kv, 128), 1.5, dtype=torch.bfloat16, device="cuda"); Vo = Ko.clone()
+    jq.compact(sh, Kd, Vd, idx, K_out=Ko, V_out=Vo)
+    Ki, Vi = Kd.clone(), Vd.clone()
+    jq.compact_inplace(sh, Ki, Vi, idx)
+    torch.cuda.synchronize()
+    idx_h, Ko_h, Vo_h, Ki_h = idx.cpu().numpy(), from_dev_bf16(Ko), from_dev_bf16(Vo), from_dev_bf16(Ki)
+    filler = from_dev_bf16(torch.full((1,), 1.5, dtype=torch.bfloat16, device="cuda"))[0]
+    for l, b in enumerate([kf + kl, kf + kl, 120]):                   # the budgets actually used
+        ref = oracle.select_topk(x[l].astype(np.float64), b, kf, kl)
+        np.testing.assert_array_equal(idx_h[l, :, :b], ref)
+        assert (idx_h[l, :, b:] == -7).all()
+        rk, rv = oracle.compact(K[l], V[l], np.ascontiguousarray(idx_h[l, :, :b]))
+        np.testing.assert_array_equal(Ko_h[l, :b], rk)
+        np.testing.assert_array_equal(Vo_h[l, :b], rv)
+        assert (Ko_h[l, b:] == filler).all()
+        np.testing.assert_array_equal(Ki_h[l, :b], rk)
+        np.testing.assert_array_equal(Ki_h[l, b:], K[l, b:])           # rows beyond the layer's own budget stay
 
 
 def test_evict_equals_stage_composition_and_oracle():

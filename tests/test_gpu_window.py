@@ -58,9 +58,9 @@ def test_window_scores_match_oracle(n_layers, seq_lens, n_q, h_q, h_kv):
     check_window_scores(n_layers, seq_lens, n_q, h_q, h_kv)
 
 
-def test_window_scores_with_many_small_waves(monkeypatch):
+def test_window_scores_with_many_small_waves(knobs):
     # 64-key chunks: waves whose only tiles lie inside the window (some query rows then see none of their keys)
-    monkeypatch.setenv("JQ_CHUNK_KEYS", "64")
+    knobs(JQ_CHUNK_KEYS="64")
     check_window_scores(1, [1000, 130], 48, 8, 2, seed=72)
     check_window_scores(1, [200], 32, 8, 2, seed=73, q_spread=3.0)
 
