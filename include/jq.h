@@ -223,6 +223,18 @@ int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V,
              void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
              void* ws, size_t ws_bytes, void* stream);
 
+/* jq_evict for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same inputs, outputs and results as jq_evict, but no workspace argument: the
+ * kernels' scratch memory is a fixed array of JQ_STATIC_WS_BYTES inside the library's device image (every GPU the
+ * library runs on holds its own copy until the process ends).  The call allocates and frees nothing.  A shape
+ * whose jq_workspace_bytes exceeds JQ_STATIC_WS_BYTES is rejected with JQ_ERR_WORKSPACE before any launch (the
+ * 128K-token layer with 8 KV heads needs 16.6 MiB).  All calls on one GPU share that GPU's array, which keeps
+ * the previous call's contents (the kernels clear what they need cleared): calls that overlap in time on one GPU
+ * -- two streams, two host threads -- race on it and must be serialised by the caller. */
+#define JQ_STATIC_WS_BYTES (32u << 20)
+int jq_evict_static(const jq_shape* shape, const void* Q, const void* K, const void* V,
+                    void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* stream);
+
 /* jq_evict with caller-supplied normalisers (see jq_score_lse): one pass over K. */
 int jq_evict_lse(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,
                  void* K_out, void* V_out, int32_t* idx_out, float* scores_out,

@@ -413,6 +413,46 @@ int jq_evict_tail(const jq_shape* shape, const void* Q, const void* K, const voi
     return evict_impl(shape, Q, K, V, nullptr, K_tail, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
 }
 
+// ---- jq_evict without a caller workspace ----------------------------------------------------------------
+// The scratch memory of the eviction kernels (softmax partials, histograms, raw scores, candidate lists) in a
+// file-scope device array instead of a caller buffer.  `scratch` names the array for the device compiler only; on
+// the host it is a stand-in, so the array's device address is looked up once per device and only that address is
+// ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[JQ_STATIC_WS_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_ptr[kMaxDevices];  // per device: the address of that device's copy of `scratch`
+
+int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return JQ_ERR_LAUNCH;
+    void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {  // first call on this device (which is current): every thread that races here finds the same address
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return JQ_ERR_LAUNCH;
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return JQ_OK;
+}
+}  // namespace
+
+int jq_evict_static(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
+                    int32_t* idx_out, float* scores_out, void* stream) {
+    Plan p;
+    const int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if (p.ws_bytes > (size_t)JQ_STATIC_WS_BYTES) return JQ_ERR_WORKSPACE;  // the problem needs more scratch than the array holds
+    if (!Q || !K || !V || !K_out || !V_out) return JQ_ERR_NULL;
+    void* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != JQ_OK) return rs;
+    // Nothing in the scratch area has to survive from, or be cleared before, a call: the first kernels write the
+    // partial statistics and clear the histograms and list counters before anything reads them.
+    return evict_impl(shape, Q, K, V, nullptr, nullptr, K_out, V_out, idx_out, scores_out, ws, JQ_STATIC_WS_BYTES, stream,
+                      nullptr);
+}
+
 int jq_score_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, const void* K_pool, const float* lse,
                    float* scores, void* ws, size_t ws_bytes, void* stream) {
     return score_impl(shape, Q, K_pool, lse, nullptr, false, scores, ws, ws_bytes, stream, pages, true);
