@@ -287,13 +287,13 @@ int jq_evict_paged(const jq_shape* shape, const jq_pages* pages, const jq_pages*
  * start / stop events, so that hipEventElapsedTime(marks[2i], marks[2i+1]) is the
  * duration of that dispatch alone:
  *   0 statistics pass over K   1 score pass over K (merges the statistics first)
- *   2 pooling (+ histogram)    3 selection: scatter      4 selection: finalize + gather
+ *   2 pooling (+ histogram and sorted segments)    3 selection + gather
  * (when a stage needs several launches the last one is reported; sequences too long
- * for the selection's fast path take a streaming selection, reported in slot 4, and an
+ * for the selection's fast path take a streaming selection, reported in slot 3, and an
  * untimed separate gather; sequences long enough to leave hundreds of partial
  * statistics get an untimed merge launch between slots 0 and 1).  Results are those of
  * jq_evict. */
-#define JQ_TRACE_MARKS 10
+#define JQ_TRACE_MARKS 8
 int jq_evict_traced(const jq_shape* shape, const void* Q, const void* K, const void* V,
                     void* K_out, void* V_out, int32_t* idx_out, float* scores_out,
                     void* ws, size_t ws_bytes, void* stream, void* const* marks, int n_marks);

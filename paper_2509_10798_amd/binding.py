@@ -23,7 +23,7 @@ STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET"
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
 EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
            "jq_copy_probe", "jq_reload_knobs", "jq_status_string")
-TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_scatter_kernel", "jq_select_finalize_kernel")
+TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_finalize_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
 
 

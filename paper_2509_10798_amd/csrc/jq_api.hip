@@ -136,6 +136,28 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     if ((int64_t)p.n_layers * (ng > ng2 ? ng : ng2) * p.h_kv >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
     if ((int64_t)p.n_layers * p.n_seq * p.h_kv * p.row_tiles >= INT32_MAX) return JQ_ERR_UNSUPPORTED;
 
+    // pooling workgroups (= segments of the selection's lists): whole sequences in pieces of kSegLen positions
+    p.cu_seg[0] = 0;
+    for (int s = 0; s < sh->n_seq; ++s) {
+        const int64_t L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
+        p.cu_seg[s + 1] = p.cu_seg[s] + (int32_t)((L + kSegLen - 1) / kSegLen);
+    }
+    p.n_seg = p.cu_seg[sh->n_seq];
+    // Entries a segment keeps: eight times what a block of kSegLen scores contributes to the kept set on average
+    // (densest sequence of the call), as a power of two in 128..kSegLen; blocks that hold more are re-read from
+    // the scores by the selection.
+    {
+        double dens = 0.0;  // kept positions per score
+        for (int s = 0; s < sh->n_seq; ++s) {
+            const double L = sh->cu_seqlens[s + 1] - sh->cu_seqlens[s];
+            const double B = p.tab.cu_bud[s + 1] - p.tab.cu_bud[s];
+            if (B / L > dens) dens = B / L;
+        }
+        int head = 128;
+        while (head < kSegLen && head < 8.0 * dens * kSegLen) head *= 2;
+        p.seg_head = head;
+    }
+
     const size_t RP = (size_t)p.row_tiles * kRowTile;
     size_t off = 0;
     p.off_stats = off;  off += align_up((size_t)p.n_layers * ng * p.h_kv * RP * sizeof(float2));  // one per pass-1 workgroup
@@ -144,8 +166,8 @@ int make_plan(const jq_shape* sh, bool need_budgets, Plan* out) {
     p.off_scores = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));
     p.off_pooled = off; off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(float));
     p.off_idx = off;    off += align_up((size_t)p.n_layers * p.h_kv * p.TB * sizeof(int32_t));
-    p.off_sure = off;   off += align_up((size_t)p.n_layers * p.h_kv * p.TB * sizeof(int32_t));
-    p.off_cand = off;   off += align_up((size_t)p.n_layers * p.h_kv * p.T * sizeof(uint2));
+    p.off_seg = off;    off += align_up((size_t)p.n_layers * p.h_kv * p.n_seg * p.seg_head * sizeof(uint2));
+    p.off_seghdr = off; off += align_up((size_t)p.n_layers * p.h_kv * p.n_seg * sizeof(uint4));
     p.ws_bytes = off;
     *out = p;
     return JQ_OK;
@@ -282,7 +304,7 @@ int jq_pool(const jq_shape* shape, const float* scores, float* pooled, void* str
     if (!scores || !pooled) return JQ_ERR_NULL;
     if (misaligned(scores, 4) || misaligned(pooled, 4)) return JQ_ERR_UNSUPPORTED;
     if (overlaps(scores, score_bytes(p), pooled, score_bytes(p))) return JQ_ERR_ALIAS;
-    return launch_status(launch_pool(p, scores, pooled, nullptr, (hipStream_t)stream));
+    return launch_status(launch_pool(p, scores, pooled, nullptr, nullptr, (hipStream_t)stream));
 }
 
 int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx, void* ws, size_t ws_bytes,
@@ -301,7 +323,7 @@ int jq_select_topk(const jq_shape* shape, const float* pooled, int32_t* idx, voi
     hipStream_t st = (hipStream_t)stream;
     uint32_t* hist = (uint32_t*)((char*)ws + p.off_hist);
     hipError_t e = launch_fill_u32(hist, (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride, 0u, st);
-    if (e == hipSuccess) e = launch_hist(p, pooled, hist, st);
+    if (e == hipSuccess) e = launch_hist(p, pooled, hist, (char*)ws, st);
     if (e == hipSuccess) e = launch_select(p, pooled, hist, (char*)ws, idx, st);
     return launch_status(e);
 }
@@ -389,7 +411,7 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
     p.marks = marks;
     const size_t zero_words = (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride;
     hipError_t e = launch_score(p, Q, K, raw, w, st, hist, zero_words, lse, k_tail);  // also clears the selection histograms
-    if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, st);
+    if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, w, st);
     bool gathered = false;  // the selection's last kernel gathers the kept rows itself unless it had to stream
     if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st, K, V, K_out, V_out, &gathered);
     if (e == hipSuccess && !gathered) e = launch_compact(p, K, V, idx, K_out, V_out, st);

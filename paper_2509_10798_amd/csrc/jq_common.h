@@ -18,6 +18,7 @@ constexpr int kScoreWaves = 4;      // waves per workgroup in the score kernels
 constexpr int kHistBins = 2048;     // level-1 radix bins (top 11 bits of the sortable key)
 constexpr int kHistStride = kHistBins + 16;  // per problem: the bins, then [0] #sure and [1] #candidate counters
 constexpr int kSelectThreads = 1024;
+constexpr int kSegLen = 1024;       // positions per pooling workgroup = entries per segment of the selection's sorted lists
 
 // Per-call sequence table, passed to kernels by value (about 2 KiB of kernarg).
 struct SeqTab {
@@ -55,11 +56,15 @@ struct Plan {
     int32_t page_shift, n_pages, max_pages;
     int64_t T, TB;
     SeqTab tab;
+    // pooling workgroups ("segments") per layer and head: ceil(L_s / kSegLen) per sequence, never across sequences
+    int32_t n_seg;
+    int32_t cu_seg[JQ_MAX_SEQ + 1];
+    int32_t seg_head;  // entries kept per segment: several times the average kept positions per kSegLen scores
     PageMap page_map() const { return PageMap{block_table, page_shift, n_pages, max_pages}; }
     PageMap out_map;      // where the pruned cache goes (block_table null: dense [n_layers][TB] rows)
     void* const* marks;   // host only: nullptr, or 2 * kTraceKernels events (start, stop) for jq_evict_traced
     // workspace layout (byte offsets, 256-aligned)
-    size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, off_sure, off_cand, ws_bytes;
+    size_t off_stats, off_aug, off_hist, off_scores, off_pooled, off_idx, off_seg, off_seghdr, ws_bytes;
 };
 
 // Largest s with cu[s] <= v (cu[0] = 0, strictly increasing, v < cu[n]).
@@ -118,8 +123,47 @@ struct Knobs {
 };
 const Knobs& knobs();
 
+// Workgroup barrier that orders LDS traffic only: global loads and stores that are still outstanding stay in
+// flight across it (a plain __syncthreads() waits for all of them first).  For workgroups that communicate
+// through LDS alone.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Inclusive prefix sum over a block of THREADS threads (thread order); `tmp` (LDS) holds THREADS/64 + 1 words.
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* tmp, uint32_t* total) {
+    constexpr int kW = THREADS / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d);
+        if (lane >= d) x += y;
+    }
+    lds_barrier();  // tmp may still be read from a previous call
+    if (lane == 63) tmp[wave] = x;
+    lds_barrier();
+    if (wave == 0) {
+        const uint32_t w = lane < kW ? tmp[lane] : 0u;
+        uint32_t wi = w;
+#pragma unroll
+        for (int d = 1; d < kW; d <<= 1) {
+            const uint32_t y = __shfl_up(wi, d);
+            if (lane >= d) wi += y;
+        }
+        if (lane < kW) tmp[lane] = wi - w;  // exclusive wave offsets
+        if (lane == kW - 1) tmp[kW] = wi;
+    }
+    lds_barrier();
+    *total = tmp[kW];
+    return x + tmp[wave];
+}
+
 // Kernels whose start/stop timestamps jq_evict_traced reports, in launch order.
-enum TraceKernel { kTrStats = 0, kTrScore, kTrPool, kTrScatter, kTrFinalize, kTraceKernels };
+enum TraceKernel { kTrStats = 0, kTrScore, kTrPool, kTrFinalize, kTraceKernels };
 
 // Launch through hipLaunchKernel so that the status belongs to this launch alone (the sticky
 // "last error" of the runtime may hold an unrelated, earlier code from the host application).
@@ -142,11 +186,16 @@ inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, size_t lds
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
                         uint32_t* zero = nullptr, size_t zero_words = 0, const float* lse = nullptr,
                         const void* k_tail = nullptr);
-hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, hipStream_t st);
+// With `hist` the pooling kernel also builds the selection's level-1 histograms, and with `ws` on top of that
+// the per-workgroup sorted lists (segments) that the selection's fast path reads.
+hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, char* ws_or_null,
+                       hipStream_t st);
 hipError_t launch_map_mse(const Plan& p, const float* scores_a, float rows_a, const float* scores_b, float rows_b,
                           float* mse, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t st);
-hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, hipStream_t st);
+hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, char* ws_or_null, hipStream_t st);
+// Whether every sequence of the plan fits the selection's fast path (LDS bitmaps); otherwise it streams.
+bool select_fast_path(const Plan& p);
 // With K, V, K_out, V_out (all or none) the selection also gathers the kept rows when its fast path runs;
 // `*gathered` tells whether it did (otherwise launch_compact is still due).
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,

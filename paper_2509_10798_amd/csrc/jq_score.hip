@@ -43,6 +43,9 @@ struct ScoreArgs {
     const uint16_t* K_tail;  // [n_layers][n_seq][n_q][h_kv][d] keys of the soft tokens themselves, or null
     const float* lse;        // [n_layers][n_seq][n_q][h_q] caller-supplied natural-log normalisers, or null
     float inv_scale;         // 1 / scale
+    int32_t one_L, one_waves;  // single-sequence calls: the sequence's length and its number of waves per head (0
+                               // otherwise), next to the pointers, so that a wave's first kernel-argument reads
+                               // do not chain through the per-sequence tables further down
     float2* stats;    // [n_layers][n_cgrp of pass 1][h_kv][RP]: (m, Z) per pass-1 workgroup
     uint2* aug;       // [n_layers][n_seq][h_kv][RP]: bf16 triple of -beta/c
     float* scores;    // [n_layers][h_kv][T]
@@ -51,7 +54,6 @@ struct ScoreArgs {
     // pass 2 only: where pass 1 left its per-workgroup statistics (its own n_cgrp and per-sequence offsets),
     // and whether this launch merges them itself (otherwise jq_combine_kernel has filled `aug`)
     int32_t n_part, fuse_combine;
-    int32_t cu_part[JQ_MAX_SEQ + 1];
     int32_t group_shift;  // log2(group) when group is a power of two, else -1
     int32_t window;       // 1: the queries are the sequence's own last n_q tokens; query i sees keys 0 .. L - n_q + i
     int32_t depth;        // key tiles a wave keeps in flight: 1 (the default) or 2
@@ -65,6 +67,9 @@ struct ScoreArgs {
     // page block_table[s * max_pages + (t >> page_shift)]
     const int32_t* block_table;
     int32_t page_shift, n_pages, max_pages;
+    // the per-sequence tables come last: every scalar above sits in the first few hundred bytes of the kernel
+    // arguments, which a wave fetches in one go
+    int32_t cu_part[JQ_MAX_SEQ + 1];
     SeqTab tab;
 };
 
@@ -116,13 +121,21 @@ __device__ __forceinline__ void wave_item(const ScoreArgs& a, bool reverse, Wave
     const uint32_t rest = b / (uint32_t)a.h_kv;
     const int cg = (int)(rest % (uint32_t)a.n_cgrp);
     w.layer = (int)(rest / (uint32_t)a.n_cgrp);
-    w.seq = find_seq(a.tab.cu_cgrp, a.tab.n_seq, cg);
-    w.L = a.tab.cu_seq[w.seq + 1] - a.tab.cu_seq[w.seq];
-    w.n_waves = a.tab.cu_chunk[w.seq + 1] - a.tab.cu_chunk[w.seq];
-    w.wave = (cg - a.tab.cu_cgrp[w.seq]) * kScoreWaves + wv;
+    if (a.one_L) {  // one sequence: nothing to look up
+        w.seq = 0;
+        w.L = a.one_L;
+        w.n_waves = a.one_waves;
+        w.wave = cg * kScoreWaves + wv;
+        w.tok0 = 0;
+    } else {
+        w.seq = find_seq(a.tab.cu_cgrp, a.tab.n_seq, cg);
+        w.L = a.tab.cu_seq[w.seq + 1] - a.tab.cu_seq[w.seq];
+        w.n_waves = a.tab.cu_chunk[w.seq + 1] - a.tab.cu_chunk[w.seq];
+        w.wave = (cg - a.tab.cu_cgrp[w.seq]) * kScoreWaves + wv;
+        w.tok0 = a.tab.cu_seq[w.seq];
+    }
     const int seq_tiles = (w.L + kKeyTile - 1) / kKeyTile;  // >= n_waves, since a chunk is at least one tile
     w.n_tiles = w.wave < w.n_waves ? (seq_tiles - w.wave + w.n_waves - 1) / w.n_waves : 0;
-    w.tok0 = a.tab.cu_seq[w.seq];
 }
 
 // ---- key tiles: global -> LDS -------------------------------------------------------------------
@@ -477,7 +490,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
             Z = Z * __builtin_amdgcn_exp2f(M - mm) + mz.y * __builtin_amdgcn_exp2f(mz.x - mm);
             M = mm;
         }
-        const int cg = a.tab.cu_cgrp[w.seq] + w.wave / kScoreWaves;  // this workgroup among the layer's, per head
+        const int cg = (a.one_L ? 0 : a.tab.cu_cgrp[w.seq]) + w.wave / kScoreWaves;  // this workgroup among the layer's, per head
         a.stats[(((int64_t)w.layer * a.n_cgrp + cg) * a.h_kv + w.g) * a.RP + a.row_tile0 * kRowTile + threadIdx.x] = make_float2(M, Z);
     }
 }
@@ -597,7 +610,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     float cM = -1.0e30f, cZ = 0.f;
     if (fused && (threadIdx.x >> 1) < NQT * kRowTile) {
         const int crow = a.row_tile0 * kRowTile + (int)(threadIdx.x >> 1);
-        const int c0 = a.cu_part[w.seq], n_p = a.cu_part[w.seq + 1] - c0;
+        const int c0 = a.one_L ? 0 : a.cu_part[w.seq], n_p = a.one_L ? a.n_part : a.cu_part[w.seq + 1] - c0;
         const float2* pp = a.stats + (((int64_t)w.layer * a.n_part + c0) * a.h_kv + w.g) * a.RP + crow;
         const int64_t pstep = (int64_t)a.h_kv * a.RP;
         for (int k0 = (int)(threadIdx.x & 1); k0 < n_p; k0 += 16) {  // 8 independent loads in flight
@@ -772,6 +785,8 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     const bool paged = p.block_table != nullptr;
     a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
     a.n_cgrp = p.tab.cu_cgrp[p.n_seq];
+    a.one_L = p.n_seq == 1 ? p.tab.cu_seq[1] : 0;
+    a.one_waves = p.n_seq == 1 ? p.tab.cu_chunk[1] : 0;
 
     dim3 grid((unsigned)((int64_t)p.n_layers * a.n_cgrp * p.h_kv));
     hipError_t e;
@@ -804,6 +819,7 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         a.chunk_keys = p.chunk_keys2; a.n_chunks = p.n_chunks2;
         for (int s = 0; s <= p.n_seq; ++s) { a.tab.cu_chunk[s] = p.cu_chunk2[s]; a.tab.cu_cgrp[s] = p.cu_cgrp2[s]; }
         a.n_cgrp = p.cu_cgrp2[p.n_seq];
+        a.one_waves = p.n_seq == 1 ? p.cu_chunk2[1] : 0;
         grid = dim3((unsigned)((int64_t)p.n_layers * a.n_cgrp * p.h_kv));
         a.depth = depth_second;
     }

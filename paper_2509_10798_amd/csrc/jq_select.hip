@@ -7,16 +7,16 @@
 //   level 3: bits  9..0  of the elements in (b1, b2)                                   -> threshold key tau
 //   result : every key > tau, plus the first (B - #greater) positions with key == tau
 //
-// Fast path (every sequence of the call fits the LDS bitmaps):
-//   scatter  -- the whole GPU streams the scores once; positions above bin b1 go to a "sure"
-//               list, (key, position) pairs inside b1 to a candidate list (block-aggregated
-//               appends; the order between blocks is arbitrary);
-//   finalize -- a workgroup resolves levels 2 and 3 on a problem's candidates in LDS, marks sure /
-//               chosen positions in an L-bit LDS bitmap, trims the tie group to its lowest
-//               positions and emits set bits in ascending order.  Several workgroups ("slices")
-//               work on one problem: each repeats the (cheap, L2-resident) resolution and emits
-//               its own range of output slots; in the fused eviction call it also gathers the K/V
-//               rows of those slots, so the pruned cache needs no further kernel.
+// Fast path (every sequence of the call fits the LDS bitmaps): ONE kernel after the pooling kernel, which
+// has left the best elements of every 1024-position block of the scores as a "segment" of (key, position)
+// pairs ordered by level-1 bin, highest first.  A workgroup picks b1 from the histogram, reads each segment
+// of its problem until the bins fall below b1 (a few dozen entries per segment; a block with more qualifying
+// elements than its segment holds is classified from its pooled scores instead), marks positions above b1 in
+// an L-bit LDS bitmap and resolves levels 2 and 3 on the pairs inside b1 (all of them sit in one LDS list),
+// marks the chosen positions, trims the tie group to its lowest positions and emits set bits in ascending
+// order.  Several workgroups ("slices") work on one problem: each repeats the (cheap, cache-resident)
+// resolution and emits its own range of output slots; in the fused eviction call it also gathers the K/V
+// rows of those slots, so the pruned cache needs no further kernel.
 // General path (very long sequences): one workgroup per problem streams the row three times.
 #include <atomic>
 
@@ -26,12 +26,16 @@ namespace jq {
 
 struct SelectArgs {
     const float* pooled;  // [n_layers][h_kv][T]
-    uint32_t* hist;       // [n_layers][n_seq][h_kv][kHistStride]: level-1 bins, then the two list counters
-    int32_t* sure;        // [n_layers][h_kv][TB]   positions above bin b1 (unordered)
-    uint2* cand;          // [n_layers][h_kv][T]    (key, position) inside bin b1 (unordered)
+    uint32_t* hist;       // [n_layers][n_seq][h_kv][kHistStride]: level-1 bins
+    const uint2* seg;     // [n_layers][h_kv][n_seg][head]  (key, position) by level-1 bin, highest first
+    const uint4* seg_hdr; // [n_layers][h_kv][n_seg]  (lowest bin of the block's window, elements inside it, last slot's key, -)
+    int32_t head;         // entries kept per segment (a multiple of 64)
     int32_t* idx;         // [n_layers][h_kv][TB]
     int32_t n_layers, h_kv;
     int32_t keep_first, keep_last;  // always-kept positions at either end of every sequence
+    int32_t one_L, one_B;           // single-sequence calls: the sequence's length and budget (0 otherwise), next to
+                                    // the other scalars, so that a workgroup's first kernel-argument reads do not
+                                    // chain through the per-sequence tables further down
     int64_t T, TB;
     // fused gather (all four null when the kept rows are not wanted): K,V [n_layers][T][h_kv][d] bf16,
     // K_out,V_out [n_layers][TB][h_kv][d]
@@ -40,42 +44,36 @@ struct SelectArgs {
     PageMap pm;      // where the rows of K and V live (dense or paged)
     PageMap pm_out;  // where the kept rows go
     const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null
+    int32_t n_seg;                   // segments per layer and head
+    int32_t cu_seg[JQ_MAX_SEQ + 1];  // ... per sequence
     SeqTab tab;
 };
-
-// Inclusive prefix sum over a block of THREADS threads (thread order); `tmp` holds THREADS/64 + 1 words.
-template <int THREADS>
-__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t* tmp, uint32_t* total) {
-    constexpr int kW = THREADS / 64;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t x = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t y = __shfl_up(x, d);
-        if (lane >= d) x += y;
-    }
-    __syncthreads();  // tmp may still be read from a previous call
-    if (lane == 63) tmp[wave] = x;
-    __syncthreads();
-    if (wave == 0) {
-        const uint32_t w = lane < kW ? tmp[lane] : 0u;
-        uint32_t wi = w;
-#pragma unroll
-        for (int d = 1; d < kW; d <<= 1) {
-            const uint32_t y = __shfl_up(wi, d);
-            if (lane >= d) wi += y;
-        }
-        if (lane < kW) tmp[lane] = wi - w;  // exclusive wave offsets
-        if (lane == kW - 1) tmp[kW] = wi;
-    }
-    __syncthreads();
-    *total = tmp[kW];
-    return x + tmp[wave];
-}
 
 // bins[0..n_bins): find the bin b with (#elements in bins > b) < need <= (#elements in bins >= b).
 // Thread t owns PER consecutive bins, highest bins first.  result[0] = b, result[1] = #elements above,
 // result[2] = #elements inside b.
+// pick_bin_counts takes the thread's PER counts already loaded (c[e] = count of bin n_bins - 1 - (PER * thread + e)).
+template <int THREADS, int PER>
+__device__ __forceinline__ void pick_bin_counts(const uint32_t (&c)[PER], int n_bins, uint32_t need, uint32_t* tmp,
+                                                uint32_t* result) {
+    uint32_t sum = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) sum += c[e];
+    uint32_t total;
+    const uint32_t incl = block_scan_incl<THREADS>(sum, tmp, &total);
+    uint32_t before = incl - sum;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        if (before < need && need <= before + c[e]) {
+            result[0] = (uint32_t)(n_bins - 1 - (PER * (int)threadIdx.x + e));
+            result[1] = before;
+            result[2] = c[e];
+        }
+        before += c[e];
+    }
+    lds_barrier();
+}
+
 template <int THREADS, int PER, typename BinPtr>
 __device__ __forceinline__ void pick_bin(BinPtr bins, int n_bins, uint32_t need, uint32_t* tmp, uint32_t* result) {
     uint32_t c[PER];
@@ -98,7 +96,7 @@ __device__ __forceinline__ void pick_bin(BinPtr bins, int n_bins, uint32_t need,
         }
         before += c[e];
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 struct Problem {
@@ -111,12 +109,23 @@ struct Problem {
 
 __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
     Problem p;
+    if (a.one_L) {  // one sequence: nothing to look up
+        p.g = prob % a.h_kv;
+        p.s = 0;
+        p.layer = prob / a.h_kv;
+        p.L = a.one_L;
+        p.B = a.layer_budgets ? budget_of(a.layer_budgets, a.tab, p.layer, 0, a.keep_first + a.keep_last) : (uint32_t)a.one_B;
+        p.x = a.pooled ? a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T : nullptr;
+        p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB;
+        p.hist = a.hist + ((int64_t)p.layer * a.h_kv + p.g) * kHistStride;
+        return p;
+    }
     p.g = prob % a.h_kv;
     p.s = (prob / a.h_kv) % a.tab.n_seq;
     p.layer = prob / (a.h_kv * a.tab.n_seq);
     p.L = a.tab.cu_seq[p.s + 1] - a.tab.cu_seq[p.s];
     p.B = budget_of(a.layer_budgets, a.tab, p.layer, p.s, a.keep_first + a.keep_last);
-    p.x = a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s];
+    p.x = a.pooled ? a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s] : nullptr;
     p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
     p.hist = a.hist + (((int64_t)p.layer * a.tab.n_seq + p.s) * a.h_kv + p.g) * kHistStride;
     return p;
@@ -198,167 +207,168 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_stream_kernel(Select
 }
 
 // ------------------------------------------------------------------------------------------------
-// fast path, step 1: scatter positions above / inside the level-1 threshold bin
-// ------------------------------------------------------------------------------------------------
-constexpr int kScatterThreads = 256;
-constexpr int kScatterPerThread = 8;  // 2048 positions per block (4096: +1.5 us, 1024: +1.5 us on the 128K layer)
-constexpr int kScatterBlockPos = kScatterThreads * kScatterPerThread;
-
-__global__ __launch_bounds__(kScatterThreads) void jq_select_scatter_kernel(SelectArgs a) {
-    __shared__ uint32_t tmp[kScatterThreads / 64 + 1];
-    __shared__ uint32_t res[4];
-    __shared__ uint32_t base[2];
-    const int g = blockIdx.y, layer = blockIdx.z;
-    const int64_t p0 = (int64_t)blockIdx.x * kScatterBlockPos;
-    const int64_t p1 = min(a.T, p0 + kScatterBlockPos);
-    const int s_first = find_seq(a.tab.cu_seq, a.tab.n_seq, p0);
-    const int s_last = find_seq(a.tab.cu_seq, a.tab.n_seq, p1 - 1);
-    const float* row = a.pooled + ((int64_t)layer * a.h_kv + g) * a.T;
-    // thread t takes positions p0 + t, p0 + t + 256, ...: neighbouring lanes read neighbouring words, and
-    // the lists are unordered, so which thread appends which position does not matter
-    const int64_t t0 = p0 + threadIdx.x;
-    uint32_t key[kScatterPerThread];
-#pragma unroll
-    for (int e = 0; e < kScatterPerThread; ++e) {
-        const int64_t t = t0 + (int64_t)e * kScatterThreads;
-        key[e] = (t < p1) ? sortable_key(row[t]) : 0u;
-    }
-
-    for (int s = s_first; s <= s_last; ++s) {  // almost always a single sequence
-        uint32_t* hist = a.hist + (((int64_t)layer * a.tab.n_seq + s) * a.h_kv + g) * kHistStride;
-        const uint32_t B = budget_of(a.layer_budgets, a.tab, layer, s, a.keep_first + a.keep_last);
-        const int Ls = a.tab.cu_seq[s + 1] - a.tab.cu_seq[s];
-        pick_bin<kScatterThreads, kHistBins / kScatterThreads>(hist, kHistBins, B, tmp, res);
-        const uint32_t b1 = res[0];
-        const int64_t q0 = max(p0, (int64_t)a.tab.cu_seq[s]), q1 = min(p1, (int64_t)a.tab.cu_seq[s + 1]);
-        uint32_t n_s = 0, n_c = 0;
-#pragma unroll
-        for (int e = 0; e < kScatterPerThread; ++e) {
-            const int64_t t = t0 + (int64_t)e * kScatterThreads;
-            const bool in = t >= q0 && t < q1;
-            const int j = (int)(t - a.tab.cu_seq[s]);
-            if (in && (j < a.keep_first || j >= Ls - a.keep_last)) key[e] = 0xFFFFFFFFu;  // always kept
-            n_s += in && (key[e] >> 21) > b1;
-            n_c += in && (key[e] >> 21) == b1;
-        }
-        // one pair of global atomics per block: prefix sums inside the block, then a block base
-        uint32_t total;
-        const uint32_t packed = n_s | (n_c << 16);  // at most kScatterBlockPos per field
-        const uint32_t excl = block_scan_incl<kScatterThreads>(packed, tmp, &total) - packed;
-        if (threadIdx.x == 0) {
-            base[0] = (total & 0xFFFFu) ? atomicAdd(hist + kHistBins, total & 0xFFFFu) : 0u;
-            base[1] = (total >> 16) ? atomicAdd(hist + kHistBins + 1, total >> 16) : 0u;
-        }
-        __syncthreads();
-        uint32_t slot_s = base[0] + (excl & 0xFFFFu), slot_c = base[1] + (excl >> 16);
-        int32_t* sure = a.sure + ((int64_t)layer * a.h_kv + g) * a.TB + a.tab.cu_bud[s];
-        uint2* cand = a.cand + ((int64_t)layer * a.h_kv + g) * a.T + a.tab.cu_seq[s];
-#pragma unroll
-        for (int e = 0; e < kScatterPerThread; ++e) {
-            const int64_t t = t0 + (int64_t)e * kScatterThreads;
-            const bool in = t >= q0 && t < q1;
-            const uint32_t bin = key[e] >> 21;
-            const uint32_t j = (uint32_t)(t - a.tab.cu_seq[s]);
-            if (in && bin > b1) { if (slot_s < B) sure[slot_s] = (int32_t)j; ++slot_s; }
-            if (in && bin == b1) { if (slot_c < (uint32_t)Ls) cand[slot_c] = make_uint2(key[e], j); ++slot_c; }
-        }
-        __syncthreads();
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
-// fast path, step 2: resolve the candidates and emit ascending positions
+// fast path: resolve the threshold from the sorted segments and emit ascending positions
 // ------------------------------------------------------------------------------------------------
 constexpr int kFinThreads = 512;
-constexpr int kFinCache = 16;  // candidates a thread keeps in registers (8192 per block)
+constexpr int kFinWaves = kFinThreads / 64;
+constexpr int kSegBatch = 16;  // segments whose first 64 entries a wave requests before it knows the threshold bin
 
-__global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectArgs a, int words_cap) {
+__global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectArgs a, int words_cap, int qual_cap) {
     extern __shared__ uint32_t lds[];
     uint32_t* bins2 = lds;                        // 2048: level-2 histogram
     uint32_t* bins3 = bins2 + 2048;               // 1024: level-3 histogram
     uint32_t* tmp = bins3 + 1024;                 // scan scratch (padded to 32)
     uint32_t* res = tmp + 32;                     // pick results (padded to 32)
-    uint32_t* keep = res + 32;                    // words_cap: bitmap of kept positions
+    uint32_t* cnt = res + 32;                     // [0] elements with bin >= b1 (padded to 32)
+    uint32_t* keep = cnt + 32;                    // words_cap: bitmap of kept positions
     uint32_t* ties = keep + words_cap;            // words_cap: bitmap of positions with key == tau
+    uint2* qual = (uint2*)(ties + words_cap);     // qual_cap: (key, position) of the elements with bin >= b1
+    int32_t* seg_n = (int32_t*)(qual + qual_cap); // segs_cap: usable entries of each segment of the problem (-1: none)
 
     const Problem p = problem_of(a, blockIdx.x);  // blockIdx.y: which slice of the problem's output slots
     const int words = (p.L + 31) >> 5;
-    const uint32_t n_sure = min(p.hist[kHistBins], p.B);
-    const uint32_t n_cand = min(p.hist[kHistBins + 1], (uint32_t)p.L);
-    const int32_t* sure = a.sure + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
-    const uint2* cand = a.cand + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n_seg = a.one_L ? a.n_seg : a.cu_seg[p.s + 1] - a.cu_seg[p.s];
+    const int64_t seg0 = ((int64_t)p.layer * a.h_kv + p.g) * a.n_seg + (a.one_L ? 0 : a.cu_seg[p.s]);
+    const int head = a.head;
+    const uint2* segs = a.seg + seg0 * head;
+    const uint4* seg_hdr = a.seg_hdr + seg0;
 
-    // The candidate list is read from global memory once: each thread keeps up to kFinCache entries in
-    // registers; anything beyond (huge tie groups) is re-read in every pass.
-    uint2 cc[kFinCache];
+    // Requested first: this thread's four level-1 bins, the header of "its" segment (thread t looks after segment
+    // t), and the first entries of the wave's first segments; all of that arrives while the
+    // threshold bin is being picked (128 entries of each, two per lane).  The entry loads are unconditional, from clamped and therefore always valid
+    // addresses -- a segment's storage holds `head` entries whatever its element count -- so that all of them are in
+    // flight together; what lies outside is masked afterwards.
+    uint32_t c1[kHistBins / kFinThreads];
 #pragma unroll
-    for (int e = 0; e < kFinCache; ++e) {
-        // loaded before the counter is known (the list's storage spans L entries, so this stays in bounds)
-        const uint32_t i = threadIdx.x + e * kFinThreads;
-        cc[e] = i < (uint32_t)p.L ? cand[i] : make_uint2(0u, 0xFFFFFFFFu);
-    }
+    for (int e = 0; e < kHistBins / kFinThreads; ++e) c1[e] = p.hist[kHistBins - 1 - ((kHistBins / kFinThreads) * (int)threadIdx.x + e)];
+    const uint4 my_hdr = seg_hdr[min((int)threadIdx.x, n_seg - 1)];
+    uint4 first[kSegBatch];  // entries 2 * lane and 2 * lane + 1 of the wave's i-th segment
 #pragma unroll
-    for (int e = 0; e < kFinCache; ++e)
-        if (threadIdx.x + e * kFinThreads >= n_cand) cc[e].y = 0xFFFFFFFFu;  // position 0xFFFFFFFF marks "none"
-    const uint32_t spill0 = kFinCache * kFinThreads;
-    // the same for the head of the "sure" list (its storage spans B entries)
-    constexpr int kSureCache = 4;
-    int32_t sc[kSureCache];
-#pragma unroll
-    for (int e = 0; e < kSureCache; ++e) {
-        const uint32_t i = threadIdx.x + e * kFinThreads;
-        sc[e] = i < p.B ? sure[i] : 0;
-    }
-
+    for (int i = 0; i < kSegBatch; ++i)
+        first[i] = *(const uint4*)(segs + (int64_t)min(wave + i * kFinWaves, n_seg - 1) * head + 2 * lane);
     for (int w = threadIdx.x; w < words; w += kFinThreads) { keep[w] = 0; ties[w] = 0; }
-    for (int b = threadIdx.x; b < 3072; b += kFinThreads) bins2[b] = 0;  // both histograms
-    __syncthreads();
+    for (int b = threadIdx.x; b < 3072 + 96; b += kFinThreads) bins2[b] = 0;  // both histograms, tmp, res, cnt
+    lds_barrier();
+    pick_bin_counts<kFinThreads, kHistBins / kFinThreads>(c1, kHistBins, p.B, tmp, res);
+    const uint32_t b1 = res[0];
+    const uint32_t n_above = res[1];  // positions above bin b1 (all of them are kept); < B
 
-#pragma unroll
-    for (int e = 0; e < kSureCache; ++e) {
-        const uint32_t j = (uint32_t)sc[e];
-        if (threadIdx.x + e * kFinThreads < n_sure && j < (uint32_t)p.L) atomicOr(&keep[j >> 5], 1u << (j & 31));
-    }
-    for (uint32_t i = kSureCache * kFinThreads + threadIdx.x; i < n_sure; i += kFinThreads) {
-        const uint32_t j = (uint32_t)sure[i];
-        if (j < (uint32_t)p.L) atomicOr(&keep[j >> 5], 1u << (j & 31));
-    }
-    uint32_t need = p.B - n_sure;  // >= 1: the threshold bin always contributes
+    // header = (lowest bin of the block's window, elements inside the window, key of the segment's last slot);
+    // usable entries of a segment, or -1 when the segment cannot answer -- more qualifying elements than it holds,
+    // or a window that ends above b1 -- and the block is classified from its pooled scores instead
+    auto usable = [&](uint4 hdr) {
+        const bool answers = b1 >= hdr.x && !((int)hdr.y > head && (hdr.z >> 21) >= b1);
+        return answers ? min(head, (int)hdr.y) : -1;
+    };
+    for (int t = threadIdx.x; t < n_seg; t += kFinThreads) seg_n[t] = usable(t == (int)threadIdx.x ? my_hdr : seg_hdr[t]);
+    lds_barrier();
 
-    // level 2 on the candidates
+    // Every entry with bin >= b1 goes into one flat LDS list `qual` (as far as it reaches; cnt[0] counts them all),
+    // which the passes below work through evenly, a few entries per thread.  The entries of a wave's first segments
+    // are counted with ballots first, so that the whole batch needs ONE reservation: atomics of many lanes on one
+    // LDS word are served one at a time.
+    auto put = [&](uint32_t key, uint32_t pos) __attribute__((always_inline)) {  // rare paths: one reservation per entry
+        const uint32_t to = atomicAdd(&cnt[0], 1u);
+        if (to < (uint32_t)qual_cap) qual[to] = make_uint2(key, pos);
+    };
+    auto scan_block = [&](int sg, auto f) __attribute__((always_inline)) {
+        const int j0 = sg * kSegLen, j1 = min(p.L, j0 + kSegLen);
+        for (int j = j0 + lane; j < j1; j += 64) {
+            const uint32_t key = select_key(p.x[j], j, p.L, a.keep_first, a.keep_last);
+            if ((key >> 21) >= b1) f(key, (uint32_t)j);
+        }
+    };
+    const int my_n = seg_n[min(wave + (lane & (kSegBatch - 1)) * kFinWaves, n_seg - 1)];  // lane i < 16: the wave's i-th segment
+    uint64_t ge_even[kSegBatch], ge_odd[kSegBatch];  // wave-uniform: lanes whose even / odd entry of the i-th segment qualifies
+    uint32_t n_mine = 0, more = 0;  // more, bit i: the 128th entry of the i-th segment still qualified
 #pragma unroll
-    for (int e = 0; e < kFinCache; ++e)
-        if (cc[e].y != 0xFFFFFFFFu) atomicAdd(&bins2[(cc[e].x >> 10) & 2047u], 1u);
-    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kFinThreads) atomicAdd(&bins2[(cand[i].x >> 10) & 2047u], 1u);
-    __syncthreads();
+    for (int i = 0; i < kSegBatch; ++i) {
+        const int n = wave + i * kFinWaves < n_seg ? __builtin_amdgcn_readlane(my_n, i) : 0;  // -1: not from its entries
+        ge_even[i] = __ballot(2 * lane < n && (first[i].x >> 21) >= b1);
+        ge_odd[i] = __ballot(2 * lane + 1 < n && (first[i].z >> 21) >= b1);
+        n_mine += (uint32_t)(__popcll(ge_even[i]) + __popcll(ge_odd[i]));
+        more |= (uint32_t)(ge_odd[i] >> 63) << i;
+    }
+    if (n_mine) {  // wave-uniform
+        uint32_t to = 0;
+        if (lane == 0) to = atomicAdd(&cnt[0], n_mine);
+        to = __builtin_amdgcn_readfirstlane(to);
+#pragma unroll
+        for (int i = 0; i < kSegBatch; ++i) {
+            uint64_t m = ge_even[i];
+            uint32_t slot = to + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if (((m >> lane) & 1) && slot < (uint32_t)qual_cap) qual[slot] = make_uint2(first[i].x, first[i].y);
+            to += (uint32_t)__popcll(m);
+            m = ge_odd[i];
+            slot = to + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if (((m >> lane) & 1) && slot < (uint32_t)qual_cap) qual[slot] = make_uint2(first[i].z, first[i].w);
+            to += (uint32_t)__popcll(m);
+        }
+    }
+    // Second visits (a segment whose 128th entry still qualified, a block that is classified from its scores), and
+    // the segments beyond the first batch: rare, so the common case only tests one mask.
+    auto visit = [&](int sg, int n, int off) __attribute__((always_inline)) {
+        if (n < 0) {
+            scan_block(sg, put);
+            return;
+        }
+        // chunks of 64 entries while the previous chunk's last entry still qualified
+        bool last_in = true;
+        for (; off < n && last_in; off += 64) {
+            const uint2 e = segs[(int64_t)sg * head + min(off + lane, head - 1)];
+            const bool ge = off + lane < n && (e.x >> 21) >= b1;
+            if (ge) put(e.x, e.y);
+            last_in = (__ballot(ge) >> 63) != 0;
+        }
+    };
+    uint32_t again = more | (uint32_t)__ballot(lane < kSegBatch && wave + lane * kFinWaves < n_seg && my_n < 0);
+    while (again) {  // wave-uniform
+        const int i = __builtin_ctz(again);
+        again &= again - 1;
+        const int sg = wave + i * kFinWaves;
+        visit(sg, seg_n[sg], 128);
+    }
+    for (int sg = wave + kSegBatch * kFinWaves; sg < n_seg; sg += kFinWaves) visit(sg, seg_n[sg], 0);
+    lds_barrier();
+    const uint32_t n_qual = cnt[0];
+    const bool listed = n_qual <= (uint32_t)qual_cap;  // uniform; otherwise every pass re-reads the scores
+    uint32_t need = p.B - min(n_above, p.B - 1);       // >= 1: the threshold bin always contributes
+
+    // f(key, position) for every element with bin >= b1
+    auto for_each_qual = [&](auto f) __attribute__((always_inline)) {
+        if (listed) {
+            for (uint32_t i = threadIdx.x; i < n_qual; i += kFinThreads) f(qual[i].x, qual[i].y);
+        } else {
+            for (int sg = wave; sg < n_seg; sg += kFinWaves) scan_block(sg, f);
+        }
+    };
+    // positions above b1 are kept; level 2 on the pairs inside b1
+    for_each_qual([&](uint32_t key, uint32_t pos) {
+        if (pos >= (uint32_t)p.L) return;
+        if ((key >> 21) > b1) atomicOr(&keep[pos >> 5], 1u << (pos & 31));
+        else atomicAdd(&bins2[(key >> 10) & 2047u], 1u);
+    });
+    lds_barrier();
     pick_bin<kFinThreads, 2048 / kFinThreads>(bins2, 2048, need, tmp, res);
     const uint32_t b2 = res[0];
     need -= res[1];
     // level 3
-#pragma unroll
-    for (int e = 0; e < kFinCache; ++e)
-        if (cc[e].y != 0xFFFFFFFFu && ((cc[e].x >> 10) & 2047u) == b2) atomicAdd(&bins3[cc[e].x & 1023u], 1u);
-    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kFinThreads) {
-        const uint32_t k = cand[i].x;
-        if (((k >> 10) & 2047u) == b2) atomicAdd(&bins3[k & 1023u], 1u);
-    }
-    __syncthreads();
+    for_each_qual([&](uint32_t key, uint32_t pos) {
+        if (pos < (uint32_t)p.L && (key >> 10) == ((b1 << 11) | b2)) atomicAdd(&bins3[key & 1023u], 1u);
+    });
+    lds_barrier();
     pick_bin<kFinThreads, 1024 / kFinThreads>(bins3, 1024, need, tmp, res + 4);
-    const uint32_t low21 = (b2 << 10) | res[4];
+    const uint32_t tau = (((b1 << 11) | b2) << 10) | res[4];
     need -= res[5];                                   // how many positions with key == tau are kept
     const bool all_ties = (need == res[6]);           // uniform: the whole tie group is kept (the usual case)
-
-    auto classify = [&](uint2 c) {
-        const uint32_t k21 = c.x & 0x1FFFFFu;
-        if (c.y < (uint32_t)p.L) {
-            if (k21 > low21 || (all_ties && k21 == low21)) atomicOr(&keep[c.y >> 5], 1u << (c.y & 31));
-            else if (k21 == low21) atomicOr(&ties[c.y >> 5], 1u << (c.y & 31));
-        }
-    };
-#pragma unroll
-    for (int e = 0; e < kFinCache; ++e) classify(cc[e]);
-    for (uint32_t i = spill0 + threadIdx.x; i < n_cand; i += kFinThreads) classify(cand[i]);
-    __syncthreads();
+    for_each_qual([&](uint32_t key, uint32_t pos) {
+        if (pos >= (uint32_t)p.L || (key >> 21) != b1) return;
+        if (key > tau || (all_ties && key == tau)) atomicOr(&keep[pos >> 5], 1u << (pos & 31));
+        else if (key == tau) atomicOr(&ties[pos >> 5], 1u << (pos & 31));
+    });
+    lds_barrier();
 
     // thread t owns a contiguous run of words, so thread order is position order
     const int wpt = (words + kFinThreads - 1) / kFinThreads;
@@ -370,18 +380,16 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         uint32_t before = block_scan_incl<kFinThreads>(n_t, tmp, &total) - n_t;
         for (int w = w0; w < w1 && before < need; ++w) {
             uint32_t t = ties[w];
-            const uint32_t cnt = __popc(t);
-            uint32_t take = min(cnt, need - before);
-            before += cnt;
+            const uint32_t cnt_w = __popc(t);
+            uint32_t take = min(cnt_w, need - before);
+            before += cnt_w;
             uint32_t add = 0;
             while (take--) { const uint32_t low = t & (0u - t); add |= low; t ^= low; }
             keep[w] |= add;  // only this thread touches word w here
         }
-        __syncthreads();
+        lds_barrier();
     }
-    // Exclusive prefix of the kept count per 32-position word (thread t scans its run of words), then the
-    // words are dealt round-robin for emission: kept positions cluster (contiguous heavy-hitter spans), and a
-    // thread that owned a whole cluster would emit hundreds of positions alone.
+    // Exclusive prefix of the kept count per 32-position word (thread t scans its run of words).
     uint32_t n_k = 0;
     for (int w = w0; w < w1; ++w) n_k += __popc(keep[w]);
     uint32_t run = block_scan_incl<kFinThreads>(n_k, tmp, &total) - n_k;
@@ -391,7 +399,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         wpre[w] = run;
         run += c;
     }
-    __syncthreads();
+    lds_barrier();
     // Emission is parallel over OUTPUT slots, not over words: kept positions cluster (contiguous heavy-hitter
     // spans), so per-word loops leave most lanes idle.  Slot o lives in the last word w with wpre[w] <= o
     // (binary search in LDS, same trip count for every thread); inside the word, the (o - wpre[w])-th set bit
@@ -423,7 +431,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         }
         if (a.K_out == nullptr) continue;  // uniform
         // Pruned cache (paper Section 4.3): the kept rows of this batch, 16 lanes x 16 B per 256-byte head row.
-        __syncthreads();
+        lds_barrier();
         const uint32_t n_rows = min((uint32_t)kFinThreads, o_end - o0);
         const int part = threadIdx.x & 15;
         for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
@@ -434,12 +442,33 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
             *(uint4*)(a.K_out + dst) = kv;
             *(uint4*)(a.V_out + dst) = vv;
         }
-        __syncthreads();  // slot_pos is rewritten by the next batch
+        lds_barrier();  // slot_pos is rewritten by the next batch
     }
 }
 
-constexpr int kFinalizeFixedWords = 2048 + 1024 + 32 + 32;
+constexpr int kFinalizeFixedWords = 2048 + 1024 + 32 + 32 + 32;
 constexpr size_t kMaxLds = 160 * 1024;
+constexpr int kQualCap = 8192;     // elements at or above the threshold bin that the LDS list holds when there is room
+constexpr int kQualCapMin = 1024;
+
+// LDS of the finalize kernel for the plan's longest sequence: the two bitmaps, one word per segment, then as much
+// list as fits.
+static size_t finalize_lds(const Plan& p, int* words_cap, int* qual_cap) {
+    int max_len = 0;
+    for (int s = 0; s < p.n_seq; ++s) max_len = max(max_len, p.tab.cu_seq[s + 1] - p.tab.cu_seq[s]);
+    *words_cap = (max_len + 31) / 32;
+    const size_t segs_cap = ((size_t)max_len + kSegLen - 1) / kSegLen;
+    const size_t fixed = ((size_t)kFinalizeFixedWords + 2 * (size_t)*words_cap + segs_cap) * sizeof(uint32_t);
+    const size_t room = kMaxLds - 1024 > fixed ? (kMaxLds - 1024 - fixed) / sizeof(uint2) : 0;
+    *qual_cap = (int)(room < (size_t)kQualCap ? room : (size_t)kQualCap);
+    return fixed + (size_t)*qual_cap * sizeof(uint2);
+}
+
+bool select_fast_path(const Plan& p) {
+    int words_cap, qual_cap;
+    finalize_lds(p, &words_cap, &qual_cap);
+    return qual_cap >= kQualCapMin;  // otherwise the bitmaps (nearly) fill LDS: stream instead
+}
 
 // Launches of the finalize kernel with more than 64 KiB of dynamic LDS need the function's limit raised.  That
 // is done once per device, to the fixed maximum any call can ask for (never to a call's own size: the attribute is
@@ -463,28 +492,28 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     a.pooled = pooled; a.hist = hist; a.idx = idx;
     a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
     if (gathered) *gathered = false;
-    a.sure = (int32_t*)(ws + p.off_sure);
-    a.cand = (uint2*)(ws + p.off_cand);
+    a.seg = (const uint2*)(ws + p.off_seg);
+    a.seg_hdr = (const uint4*)(ws + p.off_seghdr);
+    a.head = p.seg_head;
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.keep_first = p.keep_first; a.keep_last = p.keep_last;
+    a.one_L = p.n_seq == 1 ? p.tab.cu_seq[1] : 0;
+    a.one_B = p.n_seq == 1 ? p.tab.cu_bud[1] : 0;
     a.pm = p.page_map();
     a.pm_out = p.out_map;
     a.layer_budgets = p.layer_budgets;
+    a.n_seg = p.n_seg;
+    for (int s = 0; s <= p.n_seq; ++s) a.cu_seg[s] = p.cu_seg[s];
     a.tab = p.tab;
     const unsigned n_prob = (unsigned)((int64_t)p.n_layers * p.n_seq * p.h_kv);
 
-    int max_len = 0;
-    for (int s = 0; s < p.n_seq; ++s) max_len = max(max_len, p.tab.cu_seq[s + 1] - p.tab.cu_seq[s]);
-    int words_cap = (max_len + 31) / 32;
-    const size_t lds_bytes = ((size_t)kFinalizeFixedWords + 2 * (size_t)words_cap) * sizeof(uint32_t);
-    if (lds_bytes > kMaxLds - 1024)  // bitmaps do not fit: stream instead
+    if (!select_fast_path(p))  // bitmaps do not fit: stream instead
         return launch_kernel(jq_select_stream_kernel, dim3(n_prob), dim3(kSelectThreads), 0, st, p.marks, kTrFinalize, a);
 
-    dim3 grid((unsigned)((p.T + kScatterBlockPos - 1) / kScatterBlockPos), p.h_kv, p.n_layers);
-    hipError_t e = launch_kernel(jq_select_scatter_kernel, grid, dim3(kScatterThreads), 0, st, p.marks, kTrScatter, a);
-    if (e != hipSuccess) return e;
+    int words_cap, qual_cap;
+    const size_t lds_bytes = finalize_lds(p, &words_cap, &qual_cap);
     if (lds_bytes > 64 * 1024) {
-        e = allow_large_lds();
+        const hipError_t e = allow_large_lds();
         if (e != hipSuccess) return e;
     }
     // Slices per problem: enough workgroups to spread the emission (and the gather) over the chip, each with
@@ -500,7 +529,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     if (slices < 1) slices = 1;
     if (gathered) *gathered = K_out != nullptr;
     return launch_kernel(jq_select_finalize_kernel, dim3(n_prob, (unsigned)slices), dim3(kFinThreads), lds_bytes, st, p.marks,
-                         kTrFinalize, a, words_cap);
+                         kTrFinalize, a, words_cap, qual_cap);
 }
 
 }  // namespace jq
