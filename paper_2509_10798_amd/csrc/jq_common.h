@@ -98,6 +98,14 @@ __device__ inline int64_t kv_row(const PageMap& pm, const int32_t* cu, int64_t T
     return (page << pm.page_shift) + (pos & ((1 << pm.page_shift) - 1));
 }
 
+// The same with the sequence's first dense row (`cu[s]` of kv_row) already looked up.
+__device__ inline int64_t kv_row_from(const PageMap& pm, int64_t seq_row0, int64_t T, int layer, int s, int pos) {
+    if (!pm.block_table) return (int64_t)layer * T + seq_row0 + pos;
+    const int32_t e = pm.block_table[(int64_t)s * pm.max_pages + (pos >> pm.page_shift)];
+    const int64_t page = (int64_t)layer * pm.n_pages + clamp_page(e, pm.n_pages);
+    return (page << pm.page_shift) + (pos & ((1 << pm.page_shift) - 1));
+}
+
 // Budget of (layer, sequence): the table's segment length, or the caller's per-layer value clamped into
 // max(1, forced) .. that, where `forced` = keep_first + keep_last is the number of positions that are kept whatever
 // they score (the host has checked forced <= segment length; it cannot see the per-layer values).

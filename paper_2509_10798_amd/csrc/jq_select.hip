@@ -101,6 +101,7 @@ __device__ __forceinline__ void pick_bin(BinPtr bins, int n_bins, uint32_t need,
 
 struct Problem {
     int layer, s, g, L;
+    int tok0, bud0;  // first token row / first kept row of the sequence (dense layouts)
     uint32_t B;
     const float* x;
     int32_t* out;
@@ -114,6 +115,7 @@ __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
         p.s = 0;
         p.layer = prob / a.h_kv;
         p.L = a.one_L;
+        p.tok0 = 0; p.bud0 = 0;
         p.B = a.layer_budgets ? budget_of(a.layer_budgets, a.tab, p.layer, 0, a.keep_first + a.keep_last) : (uint32_t)a.one_B;
         p.x = a.pooled ? a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T : nullptr;
         p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB;
@@ -124,6 +126,7 @@ __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
     p.s = (prob / a.h_kv) % a.tab.n_seq;
     p.layer = prob / (a.h_kv * a.tab.n_seq);
     p.L = a.tab.cu_seq[p.s + 1] - a.tab.cu_seq[p.s];
+    p.tok0 = a.tab.cu_seq[p.s]; p.bud0 = a.tab.cu_bud[p.s];
     p.B = budget_of(a.layer_budgets, a.tab, p.layer, p.s, a.keep_first + a.keep_last);
     p.x = a.pooled ? a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s] : nullptr;
     p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
@@ -214,7 +217,7 @@ constexpr int kFinWaves = kFinThreads / 64;
 constexpr int kSegBatch = 16;  // segments whose first 64 entries a wave requests before it knows the threshold bin
 
 __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectArgs a, int words_cap, int qual_cap) {
-    extern __shared__ uint32_t lds[];
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
     uint32_t* bins2 = lds;                        // 2048: level-2 histogram
     uint32_t* bins3 = bins2 + 2048;               // 1024: level-3 histogram
     uint32_t* tmp = bins3 + 1024;                 // scan scratch (padded to 32)
@@ -244,12 +247,15 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
 #pragma unroll
     for (int e = 0; e < kHistBins / kFinThreads; ++e) c1[e] = p.hist[kHistBins - 1 - ((kHistBins / kFinThreads) * (int)threadIdx.x + e)];
     const uint4 my_hdr = seg_hdr[min((int)threadIdx.x, n_seg - 1)];
-    uint4 first[kSegBatch];  // entries 2 * lane and 2 * lane + 1 of the wave's i-th segment
+    uint2 first[kSegBatch], second[kSegBatch];  // entries lane and 64 + lane of the wave's i-th segment
 #pragma unroll
-    for (int i = 0; i < kSegBatch; ++i)
-        first[i] = *(const uint4*)(segs + (int64_t)min(wave + i * kFinWaves, n_seg - 1) * head + 2 * lane);
-    for (int w = threadIdx.x; w < words; w += kFinThreads) { keep[w] = 0; ties[w] = 0; }
-    for (int b = threadIdx.x; b < 3072 + 96; b += kFinThreads) bins2[b] = 0;  // both histograms, tmp, res, cnt
+    for (int i = 0; i < kSegBatch; ++i) {
+        const uint2* sp = segs + (int64_t)min(wave + i * kFinWaves, n_seg - 1) * head;
+        first[i] = sp[lane];
+        second[i] = sp[64 + lane];
+    }
+    for (int w = 4 * threadIdx.x; w < 2 * words_cap; w += 4 * kFinThreads) *(uint4*)&keep[w] = make_uint4(0u, 0u, 0u, 0u);  // keep, ties
+    for (int b = 4 * threadIdx.x; b < 3072 + 96; b += 4 * kFinThreads) *(uint4*)&bins2[b] = make_uint4(0u, 0u, 0u, 0u);  // histograms, tmp, res, cnt
     lds_barrier();
     pick_bin_counts<kFinThreads, kHistBins / kFinThreads>(c1, kHistBins, p.B, tmp, res);
     const uint32_t b1 = res[0];
@@ -281,15 +287,14 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         }
     };
     const int my_n = seg_n[min(wave + (lane & (kSegBatch - 1)) * kFinWaves, n_seg - 1)];  // lane i < 16: the wave's i-th segment
-    uint64_t ge_even[kSegBatch], ge_odd[kSegBatch];  // wave-uniform: lanes whose even / odd entry of the i-th segment qualifies
-    uint32_t n_mine = 0, more = 0;  // more, bit i: the 128th entry of the i-th segment still qualified
+    uint64_t ge_mask[kSegBatch];    // wave-uniform: lanes whose entry of the i-th segment qualifies (first 64 entries)
+    uint32_t n_mine = 0, more = 0;  // more, bit i: the 64th entry of the i-th segment still qualified
 #pragma unroll
     for (int i = 0; i < kSegBatch; ++i) {
         const int n = wave + i * kFinWaves < n_seg ? __builtin_amdgcn_readlane(my_n, i) : 0;  // -1: not from its entries
-        ge_even[i] = __ballot(2 * lane < n && (first[i].x >> 21) >= b1);
-        ge_odd[i] = __ballot(2 * lane + 1 < n && (first[i].z >> 21) >= b1);
-        n_mine += (uint32_t)(__popcll(ge_even[i]) + __popcll(ge_odd[i]));
-        more |= (uint32_t)(ge_odd[i] >> 63) << i;
+        ge_mask[i] = __ballot(lane < n && (first[i].x >> 21) >= b1);
+        n_mine += (uint32_t)__popcll(ge_mask[i]);
+        more |= (uint32_t)(ge_mask[i] >> 63) << i;
     }
     if (n_mine) {  // wave-uniform
         uint32_t to = 0;
@@ -297,14 +302,22 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         to = __builtin_amdgcn_readfirstlane(to);
 #pragma unroll
         for (int i = 0; i < kSegBatch; ++i) {
-            uint64_t m = ge_even[i];
-            uint32_t slot = to + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-            if (((m >> lane) & 1) && slot < (uint32_t)qual_cap) qual[slot] = make_uint2(first[i].x, first[i].y);
+            const uint64_t m = ge_mask[i];
+            const uint32_t slot = to + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if (((m >> lane) & 1) && slot < (uint32_t)qual_cap) qual[slot] = first[i];
             to += (uint32_t)__popcll(m);
-            m = ge_odd[i];
-            slot = to + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-            if (((m >> lane) & 1) && slot < (uint32_t)qual_cap) qual[slot] = make_uint2(first[i].z, first[i].w);
-            to += (uint32_t)__popcll(m);
+        }
+    }
+    // entries 64..127 of the few segments whose 64th entry still qualified (they are in registers already)
+    uint32_t again = 0;  // bit i: the 128th entry qualified as well
+    if (more) {  // wave-uniform
+#pragma unroll
+        for (int i = 0; i < kSegBatch; ++i) {
+            if (!(more & (1u << i))) continue;
+            const int n = __builtin_amdgcn_readlane(my_n, i);
+            const bool ge = 64 + lane < n && (second[i].x >> 21) >= b1;
+            if (ge) put(second[i].x, second[i].y);
+            again |= (uint32_t)(__ballot(ge) >> 63) << i;
         }
     }
     // Second visits (a segment whose 128th entry still qualified, a block that is classified from its scores), and
@@ -323,7 +336,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
             last_in = (__ballot(ge) >> 63) != 0;
         }
     };
-    uint32_t again = more | (uint32_t)__ballot(lane < kSegBatch && wave + lane * kFinWaves < n_seg && my_n < 0);
+    again |= (uint32_t)__ballot(lane < kSegBatch && wave + lane * kFinWaves < n_seg && my_n < 0);
     while (again) {  // wave-uniform
         const int i = __builtin_ctz(again);
         again &= again - 1;
@@ -370,15 +383,16 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
     });
     lds_barrier();
 
-    // thread t owns a contiguous run of words, so thread order is position order
-    const int wpt = (words + kFinThreads - 1) / kFinThreads;
-    const int w0 = threadIdx.x * wpt, w1 = min(words, w0 + wpt);
+    // Thread t owns a contiguous run of `wpt` words (a multiple of four, read as 16-byte vectors; the bitmaps are
+    // padded with zero words up to kFinThreads * wpt), so thread order is position order.
+    const int wpt = words_cap / kFinThreads;
+    const int w0 = threadIdx.x * wpt;
     uint32_t total;
     if (!all_ties) {  // the lowest `need` tie positions join the kept set
         uint32_t n_t = 0;
-        for (int w = w0; w < w1; ++w) n_t += __popc(ties[w]);
+        for (int w = w0; w < w0 + wpt; ++w) n_t += __popc(ties[w]);
         uint32_t before = block_scan_incl<kFinThreads>(n_t, tmp, &total) - n_t;
-        for (int w = w0; w < w1 && before < need; ++w) {
+        for (int w = w0; w < w0 + wpt && before < need; ++w) {
             uint32_t t = ties[w];
             const uint32_t cnt_w = __popc(t);
             uint32_t take = min(cnt_w, need - before);
@@ -389,24 +403,62 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         }
         lds_barrier();
     }
-    // Exclusive prefix of the kept count per 32-position word (thread t scans its run of words).
+    // Exclusive prefix of the kept count per 32-position word.
     uint32_t n_k = 0;
-    for (int w = w0; w < w1; ++w) n_k += __popc(keep[w]);
+    for (int w = w0; w < w0 + wpt; w += 4) {
+        const uint4 k4 = *(const uint4*)&keep[w];
+        n_k += __popc(k4.x) + __popc(k4.y) + __popc(k4.z) + __popc(k4.w);
+    }
     uint32_t run = block_scan_incl<kFinThreads>(n_k, tmp, &total) - n_k;
     uint32_t* wpre = ties;  // the tie bitmap is dead by now
-    for (int w = w0; w < w1; ++w) {
-        const uint32_t c = __popc(keep[w]);
-        wpre[w] = run;
-        run += c;
+    for (int w = w0; w < w0 + wpt; w += 4) {
+        const uint4 k4 = *(const uint4*)&keep[w];
+        uint4 pre;
+        pre.x = run; run += __popc(k4.x);
+        pre.y = run; run += __popc(k4.y);
+        pre.z = run; run += __popc(k4.z);
+        pre.w = run; run += __popc(k4.w);
+        *(uint4*)&wpre[w] = pre;
     }
     lds_barrier();
-    // Emission is parallel over OUTPUT slots, not over words: kept positions cluster (contiguous heavy-hitter
-    // spans), so per-word loops leave most lanes idle.  Slot o lives in the last word w with wpre[w] <= o
-    // (binary search in LDS, same trip count for every thread); inside the word, the (o - wpre[w])-th set bit
-    // is found by five popcount halvings.  Consecutive threads write consecutive slots.
     const uint32_t per_slice = (p.B + gridDim.y - 1) / gridDim.y;
     const uint32_t o_begin = min(p.B, blockIdx.y * per_slice), o_end = min(p.B, o_begin + per_slice);
-    uint32_t* slot_pos = bins2;  // the histograms are dead: positions of the current batch of kFinThreads slots
+    uint32_t* slot_pos = bins2;  // the histograms are dead: kept positions of (a batch of) the slice's output slots
+    // Pruned cache (paper Section 4.3): the kept rows of output slots o0 .. o0 + n_rows - 1, whose positions are in
+    // slot_pos; 16 lanes x 16 B per 256-byte head row.
+    auto gather_rows = [&](uint32_t o0, uint32_t n_rows) __attribute__((always_inline)) {
+        const int part = threadIdx.x & 15;
+        for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
+            const int64_t src = ((kv_row_from(a.pm, p.tok0, a.T, p.layer, p.s, (int)slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+            const int64_t dst = ((kv_row_from(a.pm_out, p.bud0, a.TB, p.layer, p.s, (int)(o0 + rr)) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+            const uint4 kv = *(const uint4*)(a.K + src);
+            const uint4 vv = *(const uint4*)(a.V + src);
+            *(uint4*)(a.K_out + dst) = kv;
+            *(uint4*)(a.V_out + dst) = vv;
+        }
+    };
+    if (listed && o_end - o_begin <= 3072u) {
+        // Every kept element sits in the flat list, and its output slot is its rank among the kept positions:
+        // the words before its own (prefix array) plus the set bits below it in its word.
+        for (uint32_t i = threadIdx.x; i < n_qual; i += kFinThreads) {
+            const uint32_t pos = qual[i].y;
+            if (pos >= (uint32_t)p.L) continue;
+            const uint32_t word = keep[pos >> 5], bit = pos & 31;
+            if (!((word >> bit) & 1u)) continue;
+            const uint32_t o = wpre[pos >> 5] + __popc(word & ((1u << bit) - 1u));
+            if (o >= o_begin && o < o_end) {
+                p.out[o] = (int)pos;
+                slot_pos[o - o_begin] = pos;
+            }
+        }
+        if (a.K_out == nullptr) return;  // uniform
+        lds_barrier();
+        gather_rows(o_begin, o_end - o_begin);
+        return;
+    }
+    // Otherwise emission is parallel over OUTPUT slots: slot o lives in the last word w with wpre[w] <= o (binary
+    // search in LDS, same trip count for every thread); inside the word, the (o - wpre[w])-th set bit is found by
+    // five popcount halvings.  Consecutive threads write consecutive slots.
     for (uint32_t o0 = o_begin; o0 < o_end; o0 += kFinThreads) {  // uniform trip count
         const uint32_t o = o0 + threadIdx.x;
         if (o < o_end) {
@@ -430,18 +482,8 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
             slot_pos[threadIdx.x] = at;
         }
         if (a.K_out == nullptr) continue;  // uniform
-        // Pruned cache (paper Section 4.3): the kept rows of this batch, 16 lanes x 16 B per 256-byte head row.
         lds_barrier();
-        const uint32_t n_rows = min((uint32_t)kFinThreads, o_end - o0);
-        const int part = threadIdx.x & 15;
-        for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
-            const int64_t src = ((kv_row(a.pm, a.tab.cu_seq, a.T, p.layer, p.s, (int)slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
-            const int64_t dst = ((kv_row(a.pm_out, a.tab.cu_bud, a.TB, p.layer, p.s, (int)(o0 + rr)) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
-            const uint4 kv = *(const uint4*)(a.K + src);
-            const uint4 vv = *(const uint4*)(a.V + src);
-            *(uint4*)(a.K_out + dst) = kv;
-            *(uint4*)(a.V_out + dst) = vv;
-        }
+        gather_rows(o0, min((uint32_t)kFinThreads, o_end - o0));
         lds_barrier();  // slot_pos is rewritten by the next batch
     }
 }
@@ -456,7 +498,7 @@ constexpr int kQualCapMin = 1024;
 static size_t finalize_lds(const Plan& p, int* words_cap, int* qual_cap) {
     int max_len = 0;
     for (int s = 0; s < p.n_seq; ++s) max_len = max(max_len, p.tab.cu_seq[s + 1] - p.tab.cu_seq[s]);
-    *words_cap = (max_len + 31) / 32;
+    *words_cap = ((max_len + 31) / 32 + 4 * kFinThreads - 1) / (4 * kFinThreads) * (4 * kFinThreads);  // whole 16-byte vectors per thread
     const size_t segs_cap = ((size_t)max_len + kSegLen - 1) / kSegLen;
     const size_t fixed = ((size_t)kFinalizeFixedWords + 2 * (size_t)*words_cap + segs_cap) * sizeof(uint32_t);
     const size_t room = kMaxLds - 1024 > fixed ? (kMaxLds - 1024 - fixed) / sizeof(uint2) : 0;
