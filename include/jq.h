@@ -14,6 +14,7 @@
  *   jq_compact      gather of the kept K/V rows into a dense pruned cache
  *   jq_compact_inplace  the same, written over the front of K and V themselves
  *   jq_evict        all of the above for n_layers x n_seq problems in one call
+ *   jq_evict_inplace  the same, the pruned cache written over the front of K and V themselves
  *   jq_score_lse, jq_evict_lse    the same with caller-supplied softmax normalisers
  *   jq_score_tail, jq_evict_tail  the same with the soft tokens' own keys in the softmax
  *   jq_score_paged, jq_evict_paged  the same on a paged cache (pools + block table)
@@ -234,6 +235,20 @@ int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V,
 #define JQ_STATIC_WS_BYTES (32u << 20)
 int jq_evict_static(const jq_shape* shape, const void* Q, const void* K, const void* V,
                     void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* stream);
+
+/* The eviction step of Section 4.3 when no second cache may exist (decoding continues on the pruned cache, so a
+ * server wants the rest of the memory back at once): after the call
+ *   K[l, cu_budgets[s]+b, g, :] = (old) K[l, cu_seqlens[s] + idx[l,g,cu_budgets[s]+b], g, :]
+ * for every kept row, likewise V -- the pruned cache lies at the front of every layer of K and V themselves,
+ * rows from sum(budgets) on are left as they were, and K and V keep their [n_layers, T, h_kv, d] strides.
+ * `lse` NULL: two passes over K as jq_evict; otherwise one pass with the supplied normalisers as jq_evict_lse.
+ * The kernel that selects the kept positions also copies the kept rows that are about to be overwritten to the
+ * workspace, and one more launch writes every kept row; no order between workgroups is assumed.  `ws` (DEVICE, 16-byte
+ * aligned) must hold jq_evict_inplace_workspace_bytes (the scratch of jq_evict plus room for the pruned cache).
+ * idx_out (kept positions) and scores_out (pooled scores) may be NULL; nothing may overlap K or V. */
+int jq_evict_inplace_workspace_bytes(const jq_shape* shape, size_t* bytes);
+int jq_evict_inplace(const jq_shape* shape, const void* Q, void* K, void* V, const float* lse,
+                     int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream);
 
 /* jq_evict with caller-supplied normalisers (see jq_score_lse): one pass over K. */
 int jq_evict_lse(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,

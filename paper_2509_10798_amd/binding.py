@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_inplace_workspace_bytes", "jq_evict_inplace", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
            "jq_copy_probe", "jq_reload_knobs", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_finalize_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.jq_compact_inplace.argtypes = [shp, vp, vp, vp, vp, sz, vp]
         L.jq_evict.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.jq_evict_inplace_workspace_bytes.argtypes = [shp, ctypes.POINTER(sz)]
+        L.jq_evict_inplace.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         pgp = ctypes.POINTER(_CPages)
         L.jq_score_paged.argtypes = [shp, pgp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_paged.argtypes = [shp, pgp, pgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -270,6 +272,26 @@ def evict(shape: Shape, Q, K, V, K_out=None, V_out=None, idx_out=None, scores_ou
     _check(lib().jq_evict(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(idx_out),
                           _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)), "jq_evict")
     return K_out, V_out, idx_out, scores_out
+
+
+def evict_inplace(shape: Shape, Q, K, V, lse=None, idx_out=None, scores_out=None, ws=None, stream=None, want_idx=True,
+                  want_scores=True):
+    """Fused eviction whose pruned cache is written over the front of K and V themselves (rows 0..TB-1 of every
+    layer).  Returns (K, V, idx_out, pooled scores)."""
+    import torch
+    dev = K.device
+    if idx_out is None and want_idx:
+        idx_out = torch.empty((shape.n_layers, shape.h_kv, shape.TB), dtype=torch.int32, device=dev)
+    if scores_out is None and want_scores:
+        scores_out = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=dev)
+    cs = shape.c_struct()
+    if ws is None:
+        n = ctypes.c_size_t(0)
+        _check(lib().jq_evict_inplace_workspace_bytes(ctypes.byref(cs), ctypes.byref(n)), "jq_evict_inplace_workspace_bytes")
+        ws = torch.empty(int(n.value), dtype=torch.uint8, device=dev)
+    _check(lib().jq_evict_inplace(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(lse), _ptr(idx_out), _ptr(scores_out),
+                                  _ptr(ws), ws.numel(), _stream(stream)), "jq_evict_inplace")
+    return K, V, idx_out, scores_out
 
 
 STATIC_WS_BYTES = 32 << 20

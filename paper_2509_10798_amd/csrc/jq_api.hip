@@ -418,6 +418,54 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
     return launch_status(e);
 }
 
+int jq_evict_inplace_workspace_bytes(const jq_shape* shape, size_t* bytes) {
+    if (!bytes) return JQ_ERR_NULL;
+    Plan p;
+    const int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    *bytes = p.ws_bytes + align_up(2 * kv_out_bytes(p));
+    return JQ_OK;
+}
+
+int jq_evict_inplace(const jq_shape* shape, const void* Q, void* K, void* V, const float* lse, int32_t* idx_out,
+                     float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+    Plan p;
+    int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if (!Q || !K || !V) return JQ_ERR_NULL;
+    if (!ws) return JQ_ERR_NULL;
+    const size_t stage_bytes = 2 * kv_out_bytes(p), need = p.ws_bytes + align_up(stage_bytes);
+    if (misaligned(ws, 16) || ws_bytes < need) return JQ_ERR_WORKSPACE;
+    if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || (idx_out && misaligned(idx_out, 4)) ||
+        (scores_out && misaligned(scores_out, 4)) || (lse && misaligned(lse, 4)))
+        return JQ_ERR_UNSUPPORTED;
+    const size_t nin = kv_bytes(p);
+    const void* bufs[8] = {Q, K, V, lse, p.layer_budgets, idx_out, scores_out, ws};
+    const size_t sizes[8] = {q_bytes(p), nin, nin, lse_bytes(p), lb_bytes(p), idx_bytes(p), score_bytes(p), need};
+    for (int i = 0; i < 8; ++i)  // K and V are written: nothing may overlap them; outputs and workspace overlap nothing
+        for (int j = i + 1; j < 8; ++j)
+            if (bufs[i] && bufs[j] && (i == 1 || i == 2 || j == 1 || j == 2 || j >= 5) && overlaps(bufs[i], sizes[i], bufs[j], sizes[j]))
+                return JQ_ERR_ALIAS;
+
+    hipStream_t st = (hipStream_t)stream;
+    char* w = (char*)ws;
+    char* stage = w + p.ws_bytes;
+    uint32_t* hist = (uint32_t*)(w + p.off_hist);
+    float* raw = (float*)(w + p.off_scores);
+    float* pooled = scores_out ? scores_out : (float*)(w + p.off_pooled);
+    int32_t* idx = idx_out ? idx_out : (int32_t*)(w + p.off_idx);
+    const size_t zero_words = (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride;
+    hipError_t e = launch_score(p, Q, K, raw, w, st, hist, zero_words, lse, nullptr);
+    if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, w, st);
+    // The selection kernel saves the kept rows that are about to be overwritten; one more launch then writes every
+    // kept row over the front of K and V.  (A streaming selection saves nothing: both launches of the stand-alone
+    // in-place gather run.)
+    bool staged = false;
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st, K, V, nullptr, nullptr, &staged, stage);
+    if (e == hipSuccess) e = staged ? launch_compact_inplace_write(p, K, V, idx, stage, st) : launch_compact_inplace(p, K, V, idx, stage, st);
+    return launch_status(e);
+}
+
 int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
              int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
     return evict_impl(shape, Q, K, V, nullptr, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);

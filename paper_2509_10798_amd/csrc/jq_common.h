@@ -205,14 +205,19 @@ hipError_t launch_hist(const Plan& p, const float* pooled, uint32_t* hist, char*
 // Whether every sequence of the plan fits the selection's fast path (LDS bitmaps); otherwise it streams.
 bool select_fast_path(const Plan& p);
 // With K, V, K_out, V_out (all or none) the selection also gathers the kept rows when its fast path runs;
-// `*gathered` tells whether it did (otherwise launch_compact is still due).
+// `*gathered` tells whether it did (otherwise launch_compact is still due).  With K, V and `stage` (in-place
+// eviction, dense layouts, no K_out / V_out) it copies the kept rows whose sources are about to be overwritten to
+// `stage` instead; launch_compact_inplace_write then finishes the job (`*gathered` false: the full
+// launch_compact_inplace is due).
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
                          const void* K = nullptr, const void* V = nullptr, void* K_out = nullptr, void* V_out = nullptr,
-                         bool* gathered = nullptr);
+                         bool* gathered = nullptr, void* stage = nullptr);
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
                           hipStream_t st);
 // In place: kept rows land at the front of K / V themselves; `stage` holds 2 * n_layers * TB * h_kv rows.
 hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st);
+// Only its second launch: every kept row written, from `stage` (rows staged earlier) or from its untouched source.
+hipError_t launch_compact_inplace_write(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st);
 
 // `cu_ref_budgets`: n_seq + 1 prefix sums of the reference list lengths, `tb_ref` their total.
 hipError_t launch_hit_rate(const Plan& p, const int32_t* cu_ref_budgets, int64_t tb_ref, const int32_t* cur,

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_inplace_kernel(Inp
     }
 }
 
-hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st) {
+static InplaceArgs inplace_args(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, dim3* grid) {
     InplaceArgs a;
     a.K = (char*)K; a.V = (char*)V; a.stage = (char*)stage; a.idx = idx;
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
@@ -118,9 +118,21 @@ hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t
     a.forced = p.keep_first + p.keep_last;
     a.tab = p.tab;
     const int64_t threads = (int64_t)p.n_layers * p.TB * p.h_kv * kLanesPerRow;
-    const dim3 grid((unsigned)((threads + kCompactThreads - 1) / kCompactThreads));
+    *grid = dim3((unsigned)((threads + kCompactThreads - 1) / kCompactThreads));
+    return a;
+}
+
+hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st) {
+    dim3 grid;
+    const InplaceArgs a = inplace_args(p, K, V, idx, stage, &grid);
     hipError_t e = launch_kernel(jq_compact_inplace_kernel<false>, grid, dim3(kCompactThreads), 0, st, nullptr, -1, a);
     if (e != hipSuccess) return e;
+    return launch_kernel(jq_compact_inplace_kernel<true>, grid, dim3(kCompactThreads), 0, st, nullptr, -1, a);
+}
+
+hipError_t launch_compact_inplace_write(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st) {
+    dim3 grid;
+    const InplaceArgs a = inplace_args(p, K, V, idx, stage, &grid);
     return launch_kernel(jq_compact_inplace_kernel<true>, grid, dim3(kCompactThreads), 0, st, nullptr, -1, a);
 }
 

@@ -41,6 +41,9 @@ struct SelectArgs {
     // K_out,V_out [n_layers][TB][h_kv][d]
     const char* K; const char* V;
     char* K_out; char* V_out;
+    // in-place eviction (dense layouts; K_out, V_out null): kept rows whose source lies inside the front that a later
+    // kernel overwrites are copied to `stage` [2][n_layers][TB][h_kv][d] here; that kernel then writes every kept row
+    char* stage;
     PageMap pm;      // where the rows of K and V live (dense or paged)
     PageMap pm_out;  // where the kept rows go
     const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null
@@ -428,6 +431,18 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
     // slot_pos; 16 lanes x 16 B per 256-byte head row.
     auto gather_rows = [&](uint32_t o0, uint32_t n_rows) __attribute__((always_inline)) {
         const int part = threadIdx.x & 15;
+        if (a.stage) {  // uniform
+            const int64_t v_stage = (int64_t)a.n_layers * a.TB * a.h_kv * (kHeadDim * 2);
+            for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
+                const int64_t src_row = (int64_t)p.tok0 + slot_pos[rr];  // within the layer
+                if (src_row >= a.TB) continue;                             // not overwritten: read in place later
+                const int64_t src = ((((int64_t)p.layer * a.T + src_row) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+                const int64_t stg = ((((int64_t)p.layer * a.TB + p.bud0 + o0 + rr) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+                *(uint4*)(a.stage + stg) = *(const uint4*)(a.K + src);
+                *(uint4*)(a.stage + v_stage + stg) = *(const uint4*)(a.V + src);
+            }
+            return;
+        }
         for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
             const int64_t src = ((kv_row_from(a.pm, p.tok0, a.T, p.layer, p.s, (int)slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
             const int64_t dst = ((kv_row_from(a.pm_out, p.bud0, a.TB, p.layer, p.s, (int)(o0 + rr)) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
@@ -437,6 +452,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
             *(uint4*)(a.V_out + dst) = vv;
         }
     };
+    const bool want_rows = a.K_out != nullptr || a.stage != nullptr;  // uniform
     if (listed && o_end - o_begin <= 3072u) {
         // Every kept element sits in the flat list, and its output slot is its rank among the kept positions:
         // the words before its own (prefix array) plus the set bits below it in its word.
@@ -451,7 +467,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
                 slot_pos[o - o_begin] = pos;
             }
         }
-        if (a.K_out == nullptr) return;  // uniform
+        if (!want_rows) return;  // uniform
         lds_barrier();
         gather_rows(o_begin, o_end - o_begin);
         return;
@@ -481,7 +497,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
             p.out[o] = (int)at;
             slot_pos[threadIdx.x] = at;
         }
-        if (a.K_out == nullptr) continue;  // uniform
+        if (!want_rows) continue;  // uniform
         lds_barrier();
         gather_rows(o0, min((uint32_t)kFinThreads, o_end - o0));
         lds_barrier();  // slot_pos is rewritten by the next batch
@@ -529,10 +545,11 @@ static hipError_t allow_large_lds() {
 }
 
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
-                         const void* K, const void* V, void* K_out, void* V_out, bool* gathered) {
+                         const void* K, const void* V, void* K_out, void* V_out, bool* gathered, void* stage) {
     SelectArgs a;
     a.pooled = pooled; a.hist = hist; a.idx = idx;
     a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
+    a.stage = (char*)stage;
     if (gathered) *gathered = false;
     a.seg = (const uint2*)(ws + p.off_seg);
     a.seg_hdr = (const uint4*)(ws + p.off_seghdr);
@@ -569,7 +586,7 @@ hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, cha
     if (slices > (min_budget + 63) / 64) slices = (min_budget + 63) / 64;
     if (slices > 64) slices = 64;
     if (slices < 1) slices = 1;
-    if (gathered) *gathered = K_out != nullptr;
+    if (gathered) *gathered = K_out != nullptr || stage != nullptr;
     return launch_kernel(jq_select_finalize_kernel, dim3(n_prob, (unsigned)slices), dim3(kFinThreads), lds_bytes, st, p.marks,
                          kTrFinalize, a, words_cap, qual_cap);
 }

@@ -118,6 +118,14 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_compact_inplace_workspace_bytes(ctypes.byref(cs), None) == -1
     assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, None, n_in.value, None) == -1
     assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, ws, n_in.value - 1, None) == -5
+    n_ev = ctypes.c_size_t()
+    assert L.jq_evict_inplace_workspace_bytes(ctypes.byref(cs), ctypes.byref(n_ev)) == 0 and n_ev.value >= need + n_in.value
+    assert L.jq_evict_inplace_workspace_bytes(ctypes.byref(cs), None) == -1
+    assert L.jq_evict_inplace(ctypes.byref(cs), Q, None, V, None, None, None, ws, n_ev.value, None) == -1
+    assert L.jq_evict_inplace(ctypes.byref(cs), Q, K, V, None, None, None, ws, need, None) == -5              # no room for the staged rows
+    assert L.jq_evict_inplace(ctypes.byref(cs), Q, K, K + 512, None, None, None, ws, n_ev.value, None) == -6  # V inside K
+    assert L.jq_evict_inplace(ctypes.byref(cs), K + 64, K, V, None, None, None, ws, n_ev.value, None) == -6   # Q inside K (which is written)
+    assert L.jq_evict_inplace(ctypes.byref(cs), Q, K, V, None, Ko, Ko + 16, ws, n_ev.value, None) == -6       # the two outputs overlap
     assert L.jq_compact_inplace(ctypes.byref(cs), K, K + 256, Ko, ws, n_in.value, None) == -6      # V inside K
     assert L.jq_compact_inplace(ctypes.byref(cs), K, V, K + 512, ws, n_in.value, None) == -6       # idx inside K
     assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, V + 1024, n_in.value, None) == -6      # staging inside V

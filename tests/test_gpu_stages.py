@@ -509,3 +509,55 @@ def test_evict_equals_stage_composition_and_oracle():
             rk, rv = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], idx_h[l, :, cb[s]:cb[s + 1]])
             np.testing.assert_array_equal(Ko_h[l, cb[s]:cb[s + 1]], rk)
             np.testing.assert_array_equal(Vo_h[l, cb[s]:cb[s + 1]], rv)
+
+
+@pytest.mark.parametrize("seq_lens,budgets,n_layers,with_lse", [
+    ([3000], [500], 2, False),                 # sources on both sides of the overwritten front
+    ([900, 40, 2000], [300, 40, 700], 2, False),   # a later sequence's rows land on an earlier sequence's sources; one kept whole
+    ([600], [600], 1, False),                  # everything kept: every source lies inside the front
+    ([2500, 1300], [256, 100], 1, True),       # one pass with supplied normalisers
+])
+def test_evict_inplace_leaves_the_pruned_cache_at_the_front_of_k_and_v(seq_lens, budgets, n_layers, with_lse):
+    # the fused call without a second cache equals jq_evict followed by a copy of its pruned cache over the front of K, V
+    torch = torch_()
+    print("evict in place", seq_lens, budgets, n_layers, with_lse, flush=True)
+    w = make_workload(1, seq_lens=seq_lens, budget=budgets, n_layers=n_layers)
+    Q, K, V = w.assemble()
+    sh = jq.Shape(n_layers=n_layers, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    Qd, Kd, Vd = to_dev_bf16(Q), to_dev_bf16(K), to_dev_bf16(V)
+    lse = None
+    if with_lse:
+        lse = torch.full((n_layers, len(seq_lens), w.n_q, w.h_q), 9.0, dtype=torch.float32, device="cuda")
+    Ko, Vo, idx, pooled = jq.evict(sh, Qd, Kd, Vd, lse=lse)
+    Ki, Vi = Kd.clone(), Vd.clone()
+    _, _, idx2, pooled2 = jq.evict_inplace(sh, Qd, Ki, Vi, lse=lse)
+    torch.cuda.synchronize()
+    TB = sum(budgets)
+    assert torch.equal(idx, idx2) and torch.equal(pooled, pooled2)
+    assert torch.equal(Ki[:, :TB].view(torch.int16), Ko.view(torch.int16)) and torch.equal(Vi[:, :TB].view(torch.int16), Vo.view(torch.int16))
+    assert torch.equal(Ki[:, TB:].view(torch.int16), Kd[:, TB:].view(torch.int16))       # the rest is untouched
+    assert torch.equal(Vi[:, TB:].view(torch.int16), Vd[:, TB:].view(torch.int16))
+    # and the pruned cache is the oracle's gather of those positions from the ORIGINAL cache
+    idx_h, Ki_h = idx.cpu().numpy(), from_dev_bf16(Ki)
+    cu, cb = w.cu_seqlens, w.cu_budgets
+    for l in range(n_layers):
+        for s in range(len(seq_lens)):
+            rk, _ = oracle.compact(K[l, cu[s]:cu[s + 1]], V[l, cu[s]:cu[s + 1]], np.ascontiguousarray(idx_h[l, :, cb[s]:cb[s + 1]]))
+            np.testing.assert_array_equal(Ki_h[l, cb[s]:cb[s + 1]], rk)
+
+
+def test_evict_inplace_on_a_long_sequence_takes_the_streaming_selection():
+    torch = torch_()
+    L, h, n_q, B = 700000, 2, 2, 300
+    torch.manual_seed(7)
+    Kd = torch.randn((1, L, h, 128), device="cuda", dtype=torch.bfloat16)
+    Vd = torch.randn((1, L, h, 128), device="cuda", dtype=torch.bfloat16)
+    Qd = torch.randn((1, 1, n_q, h, 128), device="cuda", dtype=torch.bfloat16)
+    sh = jq.Shape(n_layers=1, seq_lens=[L], n_q=n_q, h_q=h, h_kv=h, budgets=[B])
+    Ko, Vo, idx, _ = jq.evict(sh, Qd, Kd, Vd)
+    Ki, Vi = Kd.clone(), Vd.clone()
+    _, _, idx2, _ = jq.evict_inplace(sh, Qd, Ki, Vi)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2)
+    assert torch.equal(Ki[:, :B].view(torch.int16), Ko.view(torch.int16)) and torch.equal(Vi[:, :B].view(torch.int16), Vo.view(torch.int16))
+    assert torch.equal(Ki[:, B:].view(torch.int16), Kd[:, B:].view(torch.int16))
