@@ -207,6 +207,27 @@ def evict_batch(Q, K, V, cu_seqlens, budgets, pool_k: int, scale: float = 0.0, k
     return {"scores": scores, "pooled": pooled, "idx": idx, "K_out": Ko, "V_out": Vo}
 
 
+def stream_step(Q, K, V, pos, B: int, pool_k: int = 1, scale: float = 0.0, lse=None, keep_first: int = 0, keep_last: int = 0):
+    """One eviction step during decoding on a cache that earlier steps have pruned (the paper names streaming
+    eviction in the decoding phase as future work in its closing paragraph and defines nothing; the reading is the
+    Section 4.3 step applied to the cache as it stands).
+
+    K, V [rows, h_kv, d]: row b of head g is that head's own b-th cached row; pos [h_kv, rows] int: the token each
+    row came from.  The soft-token queries Q score the cached rows (softmax over the cached rows alone, or with the
+    supplied normalisers `lse`), the scores are pooled along the cache rows, the top B rows per head are kept (the
+    first keep_first and last keep_last rows always), and K, V and pos are gathered.  Returns a dict with idx (row
+    numbers), pooled, K_out, V_out and pos_out [h_kv, B]."""
+    r = evict(Q, K, V, B, pool_k, scale, lse=lse, keep_first=keep_first, keep_last=keep_last)
+    pos = np.asarray(pos)
+    h_kv = K.shape[1]
+    pos_out = np.empty((h_kv, B), dtype=np.int32)
+    for g in range(h_kv):
+        for b in range(B):
+            pos_out[g, b] = pos[g, r["idx"][g, b]]
+    r["pos_out"] = pos_out
+    return r
+
+
 def map_mse(score_a: np.ndarray, rows_a: float, score_b: np.ndarray, rows_b: float) -> np.ndarray:
     """Eq. 5 forward per KV head: mean over the prompt of (score_a/rows_a - score_b/rows_b)^2; scores [h_kv, L]."""
     a = np.ascontiguousarray(score_a, dtype=np.float64)
