@@ -15,6 +15,7 @@
  *   jq_compact_inplace  the same, written over the front of K and V themselves
  *   jq_evict        all of the above for n_layers x n_seq problems in one call
  *   jq_evict_inplace  the same, the pruned cache written over the front of K and V themselves
+ *   jq_evict_stream   the same step during decoding: re-evicts a pruned cache, carries the rows' positions along
  *   jq_score_lse, jq_evict_lse    the same with caller-supplied softmax normalisers
  *   jq_score_tail, jq_evict_tail  the same with the soft tokens' own keys in the softmax
  *   jq_score_paged, jq_evict_paged  the same on a paged cache (pools + block table)
@@ -249,6 +250,25 @@ int jq_evict_static(const jq_shape* shape, const void* Q, const void* K, const v
 int jq_evict_inplace_workspace_bytes(const jq_shape* shape, size_t* bytes);
 int jq_evict_inplace(const jq_shape* shape, const void* Q, void* K, void* V, const float* lse,
                      int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream);
+
+/* One step of eviction DURING DECODING (the paper's closing paragraph names streaming eviction in the decoding
+ * phase as future work and defines nothing; this is the Section 4.3 step applied to the cache as it stands).
+ * Between two steps a layer's cache holds, per KV head, the rows the last step kept plus the rows of the tokens
+ * decoded since; row b of head g is that head's own b-th row (heads keep different tokens), and
+ *   pos[l, g, cu_seqlens[s] + b]     (DEVICE int32 [n_layers, h_kv, T])
+ * says which token of the conversation it came from.  The soft tokens are appended after the generated text and run
+ * through the model as at the end of prefill; their queries Q score the cached rows -- softmax over the cached
+ * rows alone (lse NULL, two passes), or with the normalisers the attention kernel produced for those soft tokens
+ * (lse as in jq_score_lse, one pass) -- then pooling along the cache rows (pool_k = 1 is the natural choice once
+ * neighbouring rows are no longer neighbouring tokens), top-budgets[s] per head and the gather, exactly as
+ * jq_evict; keep_first / keep_last protect the first rows (sinks) and the newest rows (e.g. the tokens decoded
+ * since the last step).  Besides K_out, V_out and idx_out (ROW numbers in the cache that was passed in) the call
+ * writes
+ *   pos_out[l, g, cu_budgets[s] + b] = pos[l, g, cu_seqlens[s] + idx_out[l, g, cu_budgets[s] + b]]
+ * (DEVICE int32 [n_layers, h_kv, sum budgets]), so that positions survive any number of steps. */
+int jq_evict_stream(const jq_shape* shape, const void* Q, const void* K, const void* V, const int32_t* pos,
+                    const float* lse, void* K_out, void* V_out, int32_t* pos_out,
+                    int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream);
 
 /* jq_evict with caller-supplied normalisers (see jq_score_lse): one pass over K. */
 int jq_evict_lse(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,

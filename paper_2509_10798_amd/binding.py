@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_inplace_workspace_bytes", "jq_evict_inplace", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_inplace_workspace_bytes", "jq_evict_inplace", "jq_evict_stream", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
            "jq_copy_probe", "jq_reload_knobs", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_finalize_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
@@ -77,6 +77,7 @@ def lib() -> ctypes.CDLL:
         L.jq_evict_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.jq_evict_inplace_workspace_bytes.argtypes = [shp, ctypes.POINTER(sz)]
         L.jq_evict_inplace.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_evict_stream.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         pgp = ctypes.POINTER(_CPages)
         L.jq_score_paged.argtypes = [shp, pgp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_paged.argtypes = [shp, pgp, pgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -292,6 +293,31 @@ def evict_inplace(shape: Shape, Q, K, V, lse=None, idx_out=None, scores_out=None
     _check(lib().jq_evict_inplace(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(lse), _ptr(idx_out), _ptr(scores_out),
                                   _ptr(ws), ws.numel(), _stream(stream)), "jq_evict_inplace")
     return K, V, idx_out, scores_out
+
+
+def evict_stream(shape: Shape, Q, K, V, pos, lse=None, K_out=None, V_out=None, pos_out=None, idx_out=None, scores_out=None,
+                 ws=None, stream=None):
+    """One eviction step during decoding on a pruned cache K, V [n_layers, T, h_kv, d] whose rows came from the
+    tokens pos [n_layers, h_kv, T].  Returns (K_out, V_out, pos_out, idx_out, pooled scores)."""
+    import torch
+    dev = K.device
+    if K_out is None:
+        K_out = torch.empty((shape.n_layers, shape.TB, shape.h_kv, shape.d), dtype=K.dtype, device=dev)
+    if V_out is None:
+        V_out = torch.empty_like(K_out)
+    if pos_out is None:
+        pos_out = torch.empty((shape.n_layers, shape.h_kv, shape.TB), dtype=torch.int32, device=dev)
+    if idx_out is None:
+        idx_out = torch.empty((shape.n_layers, shape.h_kv, shape.TB), dtype=torch.int32, device=dev)
+    if scores_out is None:
+        scores_out = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = alloc_workspace(shape, dev)
+    cs = shape.c_struct()
+    _check(lib().jq_evict_stream(ctypes.byref(cs), _ptr(Q), _ptr(K), _ptr(V), _ptr(pos), _ptr(lse), _ptr(K_out), _ptr(V_out),
+                                 _ptr(pos_out), _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "jq_evict_stream")
+    return K_out, V_out, pos_out, idx_out, scores_out
 
 
 STATIC_WS_BYTES = 32 << 20

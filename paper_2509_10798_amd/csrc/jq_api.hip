@@ -375,7 +375,8 @@ int jq_compact_inplace(const jq_shape* shape, void* K, void* V, const int32_t* i
 static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse,
                       const void* k_tail, void* K_out, void* V_out, int32_t* idx_out, float* scores_out, void* ws,
                       size_t ws_bytes, void* stream, void* const* marks, const jq_pages* pages = nullptr,
-                      bool paged = false, const jq_pages* out_pages = nullptr) {
+                      bool paged = false, const jq_pages* out_pages = nullptr, const int32_t* pos_in = nullptr,
+                      int32_t* pos_out = nullptr) {
     Plan p;
     int rc = make_plan(shape, true, &p);
     if (rc != JQ_OK) return rc;
@@ -389,16 +390,17 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
         (k_tail && misaligned(k_tail, 16)))
         return JQ_ERR_UNSUPPORTED;
     const size_t nin = kv_bytes(p), nout = kv_out_bytes(p);
-    const void* ins[7] = {Q, K, V, lse ? (const void*)lse : k_tail, p.block_table, p.out_map.block_table, p.layer_budgets};
-    const size_t in_bytes[7] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p), table_bytes(p), out_table_bytes(p),
-                                lb_bytes(p)};
-    const void* outs[5] = {K_out, V_out, idx_out, scores_out, ws};
-    const size_t out_bytes[5] = {nout, nout, idx_bytes(p), score_bytes(p), p.ws_bytes};
-    for (int o = 0; o < 5; ++o) {
+    if ((pos_in && misaligned(pos_in, 4)) || (pos_out && misaligned(pos_out, 4))) return JQ_ERR_UNSUPPORTED;
+    const void* ins[8] = {Q, K, V, lse ? (const void*)lse : k_tail, p.block_table, p.out_map.block_table, p.layer_budgets, pos_in};
+    const size_t in_bytes[8] = {q_bytes(p), nin, nin, lse ? lse_bytes(p) : tail_bytes(p), table_bytes(p), out_table_bytes(p),
+                                lb_bytes(p), score_bytes(p)};
+    const void* outs[6] = {K_out, V_out, idx_out, scores_out, ws, pos_out};
+    const size_t out_bytes[6] = {nout, nout, idx_bytes(p), score_bytes(p), p.ws_bytes, idx_bytes(p)};
+    for (int o = 0; o < 6; ++o) {
         if (!outs[o]) continue;
-        for (int i = 0; i < 7; ++i)
+        for (int i = 0; i < 8; ++i)
             if (ins[i] && overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return JQ_ERR_ALIAS;
-        for (int o2 = o + 1; o2 < 5; ++o2)
+        for (int o2 = o + 1; o2 < 6; ++o2)
             if (outs[o2] && overlaps(outs[o], out_bytes[o], outs[o2], out_bytes[o2])) return JQ_ERR_ALIAS;
     }
 
@@ -413,7 +415,7 @@ static int evict_impl(const jq_shape* shape, const void* Q, const void* K, const
     hipError_t e = launch_score(p, Q, K, raw, w, st, hist, zero_words, lse, k_tail);  // also clears the selection histograms
     if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, w, st);
     bool gathered = false;  // the selection's last kernel gathers the kept rows itself unless it had to stream
-    if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st, K, V, K_out, V_out, &gathered);
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st, K, V, K_out, V_out, &gathered, nullptr, pos_in, pos_out);
     if (e == hipSuccess && !gathered) e = launch_compact(p, K, V, idx, K_out, V_out, st);
     return launch_status(e);
 }
@@ -469,6 +471,14 @@ int jq_evict_inplace(const jq_shape* shape, const void* Q, void* K, void* V, con
 int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
              int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
     return evict_impl(shape, Q, K, V, nullptr, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);
+}
+
+int jq_evict_stream(const jq_shape* shape, const void* Q, const void* K, const void* V, const int32_t* pos, const float* lse,
+                    void* K_out, void* V_out, int32_t* pos_out, int32_t* idx_out, float* scores_out, void* ws,
+                    size_t ws_bytes, void* stream) {
+    if (!pos || !pos_out) return JQ_ERR_NULL;
+    return evict_impl(shape, Q, K, V, lse, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr, nullptr,
+                      false, nullptr, pos, pos_out);
 }
 
 int jq_evict_lse(const jq_shape* shape, const void* Q, const void* K, const void* V, const float* lse, void* K_out,

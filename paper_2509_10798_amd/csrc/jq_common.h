@@ -208,10 +208,12 @@ bool select_fast_path(const Plan& p);
 // `*gathered` tells whether it did (otherwise launch_compact is still due).  With K, V and `stage` (in-place
 // eviction, dense layouts, no K_out / V_out) it copies the kept rows whose sources are about to be overwritten to
 // `stage` instead; launch_compact_inplace_write then finishes the job (`*gathered` false: the full
-// launch_compact_inplace is due).
+// launch_compact_inplace is due).  With pos_in / pos_out (streaming eviction: [n_layers][h_kv][T] and
+// [n_layers][h_kv][TB]) every kept row's entry of pos_in is written next to its position.
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
                          const void* K = nullptr, const void* V = nullptr, void* K_out = nullptr, void* V_out = nullptr,
-                         bool* gathered = nullptr, void* stage = nullptr);
+                         bool* gathered = nullptr, void* stage = nullptr, const int32_t* pos_in = nullptr,
+                         int32_t* pos_out = nullptr);
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
                           hipStream_t st);
 // In place: kept rows land at the front of K / V themselves; `stage` holds 2 * n_layers * TB * h_kv rows.

@@ -31,6 +31,9 @@ struct SelectArgs {
     const uint4* seg_hdr; // [n_layers][h_kv][n_seg]  (lowest bin of the block's window, elements inside it, last slot's key, -)
     int32_t head;         // entries kept per segment (a multiple of 64)
     int32_t* idx;         // [n_layers][h_kv][TB]
+    // streaming eviction: the cache rows' original positions [n_layers][h_kv][T] and where those of the kept rows
+    // go [n_layers][h_kv][TB] (both null otherwise)
+    const int32_t* pos_in; int32_t* pos_out;
     int32_t n_layers, h_kv;
     int32_t keep_first, keep_last;  // always-kept positions at either end of every sequence
     int32_t one_L, one_B;           // single-sequence calls: the sequence's length and budget (0 otherwise), next to
@@ -109,6 +112,11 @@ struct Problem {
     const float* x;
     int32_t* out;
     uint32_t* hist;
+    const int32_t* pos_in; int32_t* pos_out;  // this problem's slices of the position tables, or null
+    __device__ void emit(uint32_t slot, int row) const {
+        out[slot] = row;
+        if (pos_out) pos_out[slot] = pos_in[row];
+    }
 };
 
 __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
@@ -123,6 +131,8 @@ __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
         p.x = a.pooled ? a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T : nullptr;
         p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB;
         p.hist = a.hist + ((int64_t)p.layer * a.h_kv + p.g) * kHistStride;
+        p.pos_in = a.pos_out ? a.pos_in + ((int64_t)p.layer * a.h_kv + p.g) * a.T : nullptr;
+        p.pos_out = a.pos_out ? a.pos_out + ((int64_t)p.layer * a.h_kv + p.g) * a.TB : nullptr;
         return p;
     }
     p.g = prob % a.h_kv;
@@ -134,6 +144,8 @@ __device__ __forceinline__ Problem problem_of(const SelectArgs& a, int prob) {
     p.x = a.pooled ? a.pooled + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s] : nullptr;
     p.out = a.idx + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s];
     p.hist = a.hist + (((int64_t)p.layer * a.tab.n_seq + p.s) * a.h_kv + p.g) * kHistStride;
+    p.pos_in = a.pos_out ? a.pos_in + ((int64_t)p.layer * a.h_kv + p.g) * a.T + a.tab.cu_seq[p.s] : nullptr;
+    p.pos_out = a.pos_out ? a.pos_out + ((int64_t)p.layer * a.h_kv + p.g) * a.TB + a.tab.cu_bud[p.s] : nullptr;
     return p;
 }
 
@@ -201,7 +213,7 @@ __global__ __launch_bounds__(kSelectThreads) void jq_select_stream_kernel(Select
             const bool is_gt = kk[e] > tau, is_eq = kk[e] == tau;
             if (is_gt || (is_eq && eq_before < need)) {
                 const uint32_t slot = gt_before + min(eq_before, need);
-                if (slot < p.B) p.out[slot] = j0 + e;  // always true for consistent histograms
+                if (slot < p.B) p.emit(slot, j0 + e);  // always true for consistent histograms
             }
             gt_before += is_gt;
             eq_before += is_eq;
@@ -463,7 +475,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
             if (!((word >> bit) & 1u)) continue;
             const uint32_t o = wpre[pos >> 5] + __popc(word & ((1u << bit) - 1u));
             if (o >= o_begin && o < o_end) {
-                p.out[o] = (int)pos;
+                p.emit(o, (int)pos);
                 slot_pos[o - o_begin] = pos;
             }
         }
@@ -494,7 +506,7 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
             // (with consistent counts this is a kept position; the clamp keeps the gather inside the sequence whatever
             // the lists hold)
             const uint32_t at = min((uint32_t)(lo << 5) + pos, (uint32_t)p.L - 1u);
-            p.out[o] = (int)at;
+            p.emit(o, (int)at);
             slot_pos[threadIdx.x] = at;
         }
         if (!want_rows) continue;  // uniform
@@ -545,9 +557,11 @@ static hipError_t allow_large_lds() {
 }
 
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
-                         const void* K, const void* V, void* K_out, void* V_out, bool* gathered, void* stage) {
+                         const void* K, const void* V, void* K_out, void* V_out, bool* gathered, void* stage,
+                         const int32_t* pos_in, int32_t* pos_out) {
     SelectArgs a;
     a.pooled = pooled; a.hist = hist; a.idx = idx;
+    a.pos_in = pos_in; a.pos_out = pos_out;
     a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;
     a.stage = (char*)stage;
     if (gathered) *gathered = false;

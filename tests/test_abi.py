@@ -118,6 +118,10 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_compact_inplace_workspace_bytes(ctypes.byref(cs), None) == -1
     assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, None, n_in.value, None) == -1
     assert L.jq_compact_inplace(ctypes.byref(cs), K, V, Ko, ws, n_in.value - 1, None) == -5
+    assert L.jq_evict_stream(ctypes.byref(cs), Q, K, V, None, None, Ko, Vo, ws + (1 << 29), None, None, ws, need, None) == -1   # positions required
+    assert L.jq_evict_stream(ctypes.byref(cs), Q, K, V, lse, None, Ko, Vo, None, None, None, ws, need, None) == -1
+    assert L.jq_evict_stream(ctypes.byref(cs), Q, K, V, lse, None, Ko, Vo, Ko + 64, None, None, ws, need, None) == -6          # pos_out inside K_out
+    assert L.jq_evict_stream(ctypes.byref(cs), Q, K, V, lse + 2, None, Ko, Vo, kt, None, None, ws, need, None) == -4           # misaligned positions
     n_ev = ctypes.c_size_t()
     assert L.jq_evict_inplace_workspace_bytes(ctypes.byref(cs), ctypes.byref(n_ev)) == 0 and n_ev.value >= need + n_in.value
     assert L.jq_evict_inplace_workspace_bytes(ctypes.byref(cs), None) == -1
