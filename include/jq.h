@@ -310,11 +310,24 @@ int jq_score_paged(const jq_shape* shape, const jq_pages* pages, const void* Q, 
  * out_pages->block_table[s, b / page_size]: the pruned cache is paged again and can be handed to the
  * attention kernels as it is.  For the output the page size may be any power of two (1..65536), the pool may
  * exceed 4 GiB, and max_pages_per_seq must cover ceil(budgets[s] / page_size); the output pools must not
- * overlap the input pools (different pages of one pool are not supported: a kept row could land on a page
- * that is still being read). */
+ * overlap the input pools (jq_evict_paged_inplace writes into the input's own pools). */
 int jq_evict_paged(const jq_shape* shape, const jq_pages* pages, const jq_pages* out_pages, const void* Q,
                    const void* K_pool, const void* V_pool, const float* lse, void* K_out, void* V_out,
                    int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream);
+
+/* The paged eviction without a second cache: the kept rows are written into pages of the very pools they are
+ * taken from.  `out_pages` describes where (same page_size and n_pages as `pages`, its own block table
+ * [n_seq, max_pages_per_seq]): kept row b of sequence s goes to row (b % page_size) of page
+ * out_pages->block_table[s, b / page_size] -- any pages of the pool, in particular pages the sequences occupy now, so
+ * that everything else can be handed back to the allocator.  A kept row that lives on a page which receives rows is
+ * copied to the workspace before anything is written (a one-bit-per-page map of those pages is built first), then one
+ * more launch writes every kept row; no order between workgroups is assumed.  Pages named by out_pages must not be
+ * shared between sequences; rows of those pages beyond the kept rows keep their old contents.  `lse` as in
+ * jq_evict_paged.  `ws` must hold jq_evict_paged_inplace_workspace_bytes. */
+int jq_evict_paged_inplace_workspace_bytes(const jq_shape* shape, const jq_pages* pages, size_t* bytes);
+int jq_evict_paged_inplace(const jq_shape* shape, const jq_pages* pages, const jq_pages* out_pages, const void* Q,
+                           void* K_pool, void* V_pool, const float* lse, int32_t* idx_out, float* scores_out,
+                           void* ws, size_t ws_bytes, void* stream);
 
 /* jq_evict with kernel timing (the measurement hook of the benchmark): `marks` is a
  * HOST array of JQ_TRACE_MARKS hipEvent_t (passed as void*), created by the caller.

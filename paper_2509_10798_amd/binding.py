@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_inplace_workspace_bytes", "jq_evict_inplace", "jq_evict_stream", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_inplace_workspace_bytes", "jq_evict_inplace", "jq_evict_stream", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_paged_inplace_workspace_bytes", "jq_evict_paged_inplace", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
            "jq_copy_probe", "jq_reload_knobs", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_finalize_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         pgp = ctypes.POINTER(_CPages)
         L.jq_score_paged.argtypes = [shp, pgp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_paged.argtypes = [shp, pgp, pgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.jq_evict_paged_inplace_workspace_bytes.argtypes = [shp, pgp, ctypes.POINTER(sz)]
+        L.jq_evict_paged_inplace.argtypes = [shp, pgp, pgp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_traced.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp), ctypes.c_int]
         L.jq_copy_probe.argtypes = [vp, vp, sz, vp]
         L.jq_reload_knobs.argtypes = []
@@ -384,6 +386,28 @@ def evict_paged(shape: Shape, pages: Pages, Q, K_pool, V_pool, lse=None, K_out=N
                                 _ptr(K_out), _ptr(V_out), _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(),
                                 _stream(stream)), "jq_evict_paged")
     return K_out, V_out, idx_out, scores_out
+
+
+def evict_paged_inplace(shape: Shape, pages: Pages, out_pages: Pages, Q, K_pool, V_pool, lse=None, idx_out=None, scores_out=None,
+                        ws=None, stream=None):
+    """Fused eviction on a paged cache whose kept rows are written into pages of the same pools (`out_pages`: same
+    page size and pool size, its own block table).  Returns (K_pool, V_pool, idx_out, pooled scores)."""
+    import torch
+    dev = K_pool.device
+    if idx_out is None:
+        idx_out = torch.empty((shape.n_layers, shape.h_kv, shape.TB), dtype=torch.int32, device=dev)
+    if scores_out is None:
+        scores_out = torch.empty((shape.n_layers, shape.h_kv, shape.T), dtype=torch.float32, device=dev)
+    cs, cp, co = shape.c_struct(), pages.c_struct(), out_pages.c_struct()
+    if ws is None:
+        n = ctypes.c_size_t(0)
+        _check(lib().jq_evict_paged_inplace_workspace_bytes(ctypes.byref(cs), ctypes.byref(cp), ctypes.byref(n)),
+               "jq_evict_paged_inplace_workspace_bytes")
+        ws = torch.empty(int(n.value), dtype=torch.uint8, device=dev)
+    _check(lib().jq_evict_paged_inplace(ctypes.byref(cs), ctypes.byref(cp), ctypes.byref(co), _ptr(Q), _ptr(K_pool), _ptr(V_pool),
+                                        _ptr(lse), _ptr(idx_out), _ptr(scores_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "jq_evict_paged_inplace")
+    return K_pool, V_pool, idx_out, scores_out
 
 
 def hit_rate(shape: Shape, idx_cur, idx_ref, ref_budgets=None, rate=None, stream=None):

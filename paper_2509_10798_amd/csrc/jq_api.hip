@@ -468,6 +468,70 @@ int jq_evict_inplace(const jq_shape* shape, const void* Q, void* K, void* V, con
     return launch_status(e);
 }
 
+// workspace of the paged in-place eviction: the scratch of jq_evict, the staged rows, the destination-page bitmap
+static size_t paged_inplace_bytes(const Plan& p, size_t* off_stage, size_t* off_bits) {
+    *off_stage = p.ws_bytes;
+    *off_bits = *off_stage + align_up(2 * (size_t)p.n_layers * p.TB * p.h_kv * p.d * 2);
+    return *off_bits + align_up(((size_t)p.n_pages + 31) / 32 * 4);
+}
+
+int jq_evict_paged_inplace_workspace_bytes(const jq_shape* shape, const jq_pages* pages, size_t* bytes) {
+    if (!bytes) return JQ_ERR_NULL;
+    Plan p;
+    int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if ((rc = apply_pages(pages, &p)) != JQ_OK) return rc;
+    size_t o1, o2;
+    *bytes = paged_inplace_bytes(p, &o1, &o2);
+    return JQ_OK;
+}
+
+int jq_evict_paged_inplace(const jq_shape* shape, const jq_pages* pages, const jq_pages* out_pages, const void* Q, void* K_pool,
+                           void* V_pool, const float* lse, int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes,
+                           void* stream) {
+    Plan p;
+    int rc = make_plan(shape, true, &p);
+    if (rc != JQ_OK) return rc;
+    if ((rc = apply_pages(pages, &p)) != JQ_OK) return rc;
+    if ((rc = apply_out_pages(out_pages, &p)) != JQ_OK) return rc;
+    // the kept rows go to other (or the same) pages of the very pools they are taken from
+    if (out_pages->page_size != pages->page_size || out_pages->n_pages != pages->n_pages) return JQ_ERR_SHAPE;
+    if (!Q || !K_pool || !V_pool || !ws) return JQ_ERR_NULL;
+    size_t off_stage, off_bits;
+    const size_t need = paged_inplace_bytes(p, &off_stage, &off_bits);
+    if (misaligned(ws, 16) || ws_bytes < need) return JQ_ERR_WORKSPACE;
+    if (misaligned(Q, 16) || misaligned(K_pool, 16) || misaligned(V_pool, 16) || (idx_out && misaligned(idx_out, 4)) ||
+        (scores_out && misaligned(scores_out, 4)) || (lse && misaligned(lse, 4)))
+        return JQ_ERR_UNSUPPORTED;
+    const size_t nin = kv_bytes(p);
+    const void* bufs[10] = {Q, K_pool, V_pool, lse, p.layer_budgets, p.block_table, p.out_map.block_table, idx_out, scores_out, ws};
+    const size_t sizes[10] = {q_bytes(p), nin, nin, lse_bytes(p), lb_bytes(p), table_bytes(p), out_table_bytes(p), idx_bytes(p),
+                              score_bytes(p), need};
+    for (int i = 0; i < 10; ++i)  // the pools are written: nothing may overlap them; outputs and workspace overlap nothing
+        for (int j = i + 1; j < 10; ++j)
+            if (bufs[i] && bufs[j] && (i == 1 || i == 2 || j == 1 || j == 2 || j >= 7) && overlaps(bufs[i], sizes[i], bufs[j], sizes[j]))
+                return JQ_ERR_ALIAS;
+
+    hipStream_t st = (hipStream_t)stream;
+    char* w = (char*)ws;
+    char* stage = w + off_stage;
+    uint32_t* dest_bits = (uint32_t*)(w + off_bits);
+    uint32_t* hist = (uint32_t*)(w + p.off_hist);
+    float* raw = (float*)(w + p.off_scores);
+    float* pooled = scores_out ? scores_out : (float*)(w + p.off_pooled);
+    int32_t* idx = idx_out ? idx_out : (int32_t*)(w + p.off_idx);
+    const size_t zero_words = (size_t)p.n_layers * p.n_seq * p.h_kv * kHistStride;
+    hipError_t e = launch_mark_dest_pages(p, dest_bits, st);  // which pages receive kept rows (read by the last two kernels)
+    if (e == hipSuccess) e = launch_score(p, Q, K_pool, raw, w, st, hist, zero_words, lse, nullptr);
+    if (e == hipSuccess) e = launch_pool(p, raw, pooled, hist, w, st);
+    bool staged = false;
+    if (e == hipSuccess) e = launch_select(p, pooled, hist, w, idx, st, K_pool, V_pool, nullptr, nullptr, &staged, stage, nullptr, nullptr, dest_bits);
+    if (e == hipSuccess)
+        e = staged ? launch_compact_inplace_write(p, K_pool, V_pool, idx, stage, st, dest_bits)
+                   : launch_compact_inplace(p, K_pool, V_pool, idx, stage, st, dest_bits);
+    return launch_status(e);
+}
+
 int jq_evict(const jq_shape* shape, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
              int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
     return evict_impl(shape, Q, K, V, nullptr, nullptr, K_out, V_out, idx_out, scores_out, ws, ws_bytes, stream, nullptr);

@@ -98,6 +98,16 @@ __device__ inline int64_t kv_row(const PageMap& pm, const int32_t* cu, int64_t T
     return (page << pm.page_shift) + (pos & ((1 << pm.page_shift) - 1));
 }
 
+// In-place eviction: is the row that holds token `pos` of sequence `s` (row `src_row` of its layer when dense)
+// among the rows the call overwrites?  Dense: the front TB rows of the layer.  Paged into the input's own pool:
+// any row of a page that the output table names (`dest_bits`: one bit per page of the pool).
+__device__ inline bool row_is_overwritten(const PageMap& pm, const uint32_t* dest_bits, int64_t src_row_dense, int64_t TB, int s,
+                                          int pos) {
+    if (!pm.block_table) return src_row_dense < TB;
+    const int32_t e = clamp_page(pm.block_table[(int64_t)s * pm.max_pages + (pos >> pm.page_shift)], pm.n_pages);
+    return (dest_bits[e >> 5] >> (e & 31)) & 1u;
+}
+
 // The same with the sequence's first dense row (`cu[s]` of kv_row) already looked up.
 __device__ inline int64_t kv_row_from(const PageMap& pm, int64_t seq_row0, int64_t T, int layer, int s, int pos) {
     if (!pm.block_table) return (int64_t)layer * T + seq_row0 + pos;
@@ -213,13 +223,19 @@ bool select_fast_path(const Plan& p);
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
                          const void* K = nullptr, const void* V = nullptr, void* K_out = nullptr, void* V_out = nullptr,
                          bool* gathered = nullptr, void* stage = nullptr, const int32_t* pos_in = nullptr,
-                         int32_t* pos_out = nullptr);
+                         int32_t* pos_out = nullptr, const uint32_t* dest_bits = nullptr);
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
                           hipStream_t st);
 // In place: kept rows land at the front of K / V themselves; `stage` holds 2 * n_layers * TB * h_kv rows.
-hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st);
+hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st,
+                                  const uint32_t* dest_bits = nullptr);
 // Only its second launch: every kept row written, from `stage` (rows staged earlier) or from its untouched source.
-hipError_t launch_compact_inplace_write(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st);
+// With paged K / V (p.block_table) the kept rows go where p.out_map says, inside the same pools; `dest_bits` then
+// marks the pages that receive rows (one bit per page; null for the dense layout).
+hipError_t launch_compact_inplace_write(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st,
+                                        const uint32_t* dest_bits = nullptr);
+// Bitmap of the pages that p.out_map's table names for kept rows (one launch; ceil(n_pages / 32) words).
+hipError_t launch_mark_dest_pages(const Plan& p, uint32_t* dest_bits, hipStream_t st);
 
 // `cu_ref_budgets`: n_seq + 1 prefix sums of the reference list lengths, `tb_ref` their total.
 hipError_t launch_hit_rate(const Plan& p, const int32_t* cu_ref_budgets, int64_t tb_ref, const int32_t* cur,

@@ -70,6 +70,8 @@ struct InplaceArgs {
     char* K; char* V;
     char* stage;         // [2][n_layers][TB][h_kv][d] bf16: K rows, then V rows
     const int32_t* idx;  // [n_layers][h_kv][TB], sequence-local
+    const uint32_t* dest_bits;  // paged: one bit per page of the pool, set for pages that receive kept rows
+    PageMap pm, pm_out;         // paged: where the rows live / where the kept rows go (same pools); dense: no tables
     int32_t n_layers, h_kv;
     int64_t T, TB;
     const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null
@@ -92,9 +94,9 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_inplace_kernel(Inp
     if ((uint32_t)(tb - a.tab.cu_bud[s]) >= budget_of(a.layer_budgets, a.tab, layer, s, a.forced)) return;  // slot not used by this layer
     int j = a.idx[((int64_t)layer * a.h_kv + g) * a.TB + tb];
     j = min(max(j, 0), L - 1);
-    const int64_t src_row = (int64_t)a.tab.cu_seq[s] + j;  // within the layer
-    const bool staged = src_row < a.TB;                     // the source is a row that this call overwrites
-    const int64_t src = ((((int64_t)layer * a.T + src_row) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
+    const int64_t src_row = (int64_t)a.tab.cu_seq[s] + j;  // within the layer (dense layout)
+    const bool staged = row_is_overwritten(a.pm, a.dest_bits, src_row, a.TB, s, j);  // the source is a row that this call overwrites
+    const int64_t src = ((kv_row(a.pm, a.tab.cu_seq, a.T, layer, s, j) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
     const int64_t stg = item * (kHeadDim * 2) + part * 16;
     const int64_t v_stage = n_items * (kHeadDim * 2);
     if (!WRITE) {
@@ -102,7 +104,10 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_inplace_kernel(Inp
         *(u32x4*)(a.stage + stg) = *(const u32x4*)(a.K + src);
         *(u32x4*)(a.stage + v_stage + stg) = *(const u32x4*)(a.V + src);
     } else {
-        const int64_t dst = ((((int64_t)layer * a.T + tb) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
+        // dense: row tb of the layer's own K / V; paged: where the output table puts kept row tb - cu_bud[s]
+        const int64_t dst_row = a.pm_out.block_table ? kv_row(a.pm_out, a.tab.cu_bud, a.TB, layer, s, (int)(tb - a.tab.cu_bud[s]))
+                                                     : (int64_t)layer * a.T + tb;
+        const int64_t dst = ((dst_row * a.h_kv + g) * kHeadDim) * 2 + part * 16;
         const u32x4 kv = staged ? *(const u32x4*)(a.stage + stg) : *(const u32x4*)(a.K + src);
         const u32x4 vv = staged ? *(const u32x4*)(a.stage + v_stage + stg) : *(const u32x4*)(a.V + src);
         *(u32x4*)(a.K + dst) = kv;
@@ -110,9 +115,13 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_inplace_kernel(Inp
     }
 }
 
-static InplaceArgs inplace_args(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, dim3* grid) {
+static InplaceArgs inplace_args(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, dim3* grid,
+                                const uint32_t* dest_bits = nullptr) {
     InplaceArgs a;
     a.K = (char*)K; a.V = (char*)V; a.stage = (char*)stage; a.idx = idx;
+    a.dest_bits = dest_bits;
+    a.pm = p.page_map();
+    a.pm_out = p.out_map;
     a.n_layers = p.n_layers; a.h_kv = p.h_kv; a.T = p.T; a.TB = p.TB;
     a.layer_budgets = p.layer_budgets;
     a.forced = p.keep_first + p.keep_last;
@@ -122,18 +131,49 @@ static InplaceArgs inplace_args(const Plan& p, void* K, void* V, const int32_t* 
     return a;
 }
 
-hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st) {
+hipError_t launch_compact_inplace(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st,
+                                  const uint32_t* dest_bits) {
     dim3 grid;
-    const InplaceArgs a = inplace_args(p, K, V, idx, stage, &grid);
+    const InplaceArgs a = inplace_args(p, K, V, idx, stage, &grid, dest_bits);
     hipError_t e = launch_kernel(jq_compact_inplace_kernel<false>, grid, dim3(kCompactThreads), 0, st, nullptr, -1, a);
     if (e != hipSuccess) return e;
     return launch_kernel(jq_compact_inplace_kernel<true>, grid, dim3(kCompactThreads), 0, st, nullptr, -1, a);
 }
 
-hipError_t launch_compact_inplace_write(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st) {
+hipError_t launch_compact_inplace_write(const Plan& p, void* K, void* V, const int32_t* idx, void* stage, hipStream_t st,
+                                        const uint32_t* dest_bits) {
     dim3 grid;
-    const InplaceArgs a = inplace_args(p, K, V, idx, stage, &grid);
+    const InplaceArgs a = inplace_args(p, K, V, idx, stage, &grid, dest_bits);
     return launch_kernel(jq_compact_inplace_kernel<true>, grid, dim3(kCompactThreads), 0, st, nullptr, -1, a);
+}
+
+// One workgroup: clear the bitmap, then set the bit of every page that the output table names for a kept row.
+struct MarkArgs {
+    uint32_t* bits;
+    PageMap out;       // the output table
+    int32_t n_words;   // ceil(n_pages / 32)
+    SeqTab tab;        // cu_bud: kept rows per sequence
+};
+__global__ __launch_bounds__(1024) void jq_mark_dest_pages_kernel(MarkArgs a) {
+    for (int w = threadIdx.x; w < a.n_words; w += 1024) a.bits[w] = 0u;
+    __syncthreads();
+    for (int s = 0; s < a.tab.n_seq; ++s) {
+        const int B = a.tab.cu_bud[s + 1] - a.tab.cu_bud[s];
+        const int n = (B + (1 << a.out.page_shift) - 1) >> a.out.page_shift;  // pages of sequence s that receive rows
+        for (int j = threadIdx.x; j < n; j += 1024) {
+            const int32_t e = clamp_page(a.out.block_table[(int64_t)s * a.out.max_pages + j], a.out.n_pages);
+            atomicOr(&a.bits[e >> 5], 1u << (e & 31));
+        }
+    }
+}
+
+hipError_t launch_mark_dest_pages(const Plan& p, uint32_t* dest_bits, hipStream_t st) {
+    MarkArgs a;
+    a.bits = dest_bits;
+    a.out = p.out_map;
+    a.n_words = (p.out_map.n_pages + 31) / 32;
+    a.tab = p.tab;
+    return launch_kernel(jq_mark_dest_pages_kernel, dim3(1), dim3(1024), 0, st, nullptr, -1, a);
 }
 
 // Critical-KV hit rate (paper Eq. 6): |I_cur & I_ref| / |I_ref| per (layer, sequence, KV head) for two kept

@@ -47,6 +47,7 @@ struct SelectArgs {
     // in-place eviction (dense layouts; K_out, V_out null): kept rows whose source lies inside the front that a later
     // kernel overwrites are copied to `stage` [2][n_layers][TB][h_kv][d] here; that kernel then writes every kept row
     char* stage;
+    const uint32_t* dest_bits;  // in-place eviction inside a paged pool: the pages that receive kept rows (else null)
     PageMap pm;      // where the rows of K and V live (dense or paged)
     PageMap pm_out;  // where the kept rows go
     const int32_t* layer_budgets;  // DEVICE [n_layers][n_seq] or null
@@ -446,9 +447,9 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         if (a.stage) {  // uniform
             const int64_t v_stage = (int64_t)a.n_layers * a.TB * a.h_kv * (kHeadDim * 2);
             for (uint32_t rr = threadIdx.x >> 4; rr < n_rows; rr += kFinThreads / 16) {
-                const int64_t src_row = (int64_t)p.tok0 + slot_pos[rr];  // within the layer
-                if (src_row >= a.TB) continue;                             // not overwritten: read in place later
-                const int64_t src = ((((int64_t)p.layer * a.T + src_row) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
+                const int64_t src_row = (int64_t)p.tok0 + slot_pos[rr];  // within the layer (dense layout)
+                if (!row_is_overwritten(a.pm, a.dest_bits, src_row, a.TB, p.s, (int)slot_pos[rr])) continue;  // read in place later
+                const int64_t src = ((kv_row_from(a.pm, p.tok0, a.T, p.layer, p.s, (int)slot_pos[rr]) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
                 const int64_t stg = ((((int64_t)p.layer * a.TB + p.bud0 + o0 + rr) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
                 *(uint4*)(a.stage + stg) = *(const uint4*)(a.K + src);
                 *(uint4*)(a.stage + v_stage + stg) = *(const uint4*)(a.V + src);
@@ -558,8 +559,9 @@ static hipError_t allow_large_lds() {
 
 hipError_t launch_select(const Plan& p, const float* pooled, uint32_t* hist, char* ws, int32_t* idx, hipStream_t st,
                          const void* K, const void* V, void* K_out, void* V_out, bool* gathered, void* stage,
-                         const int32_t* pos_in, int32_t* pos_out) {
+                         const int32_t* pos_in, int32_t* pos_out, const uint32_t* dest_bits) {
     SelectArgs a;
+    a.dest_bits = dest_bits;
     a.pooled = pooled; a.hist = hist; a.idx = idx;
     a.pos_in = pos_in; a.pos_out = pos_out;
     a.K = (const char*)K; a.V = (const char*)V; a.K_out = (char*)K_out; a.V_out = (char*)V_out;

@@ -122,7 +122,7 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_evict_stream(ctypes.byref(cs), Q, K, V, lse, None, Ko, Vo, None, None, None, ws, need, None) == -1
     assert L.jq_evict_stream(ctypes.byref(cs), Q, K, V, lse, None, Ko, Vo, Ko + 64, None, None, ws, need, None) == -6          # pos_out inside K_out
     assert L.jq_evict_stream(ctypes.byref(cs), Q, K, V, lse + 2, None, Ko, Vo, kt, None, None, ws, need, None) == -4           # misaligned positions
-    n_ev = ctypes.c_size_t()
+    n_ev = ctypes.c_size_t()  # (paged in-place eviction: checked in test_paged_descriptor_errors)
     assert L.jq_evict_inplace_workspace_bytes(ctypes.byref(cs), ctypes.byref(n_ev)) == 0 and n_ev.value >= need + n_in.value
     assert L.jq_evict_inplace_workspace_bytes(ctypes.byref(cs), None) == -1
     assert L.jq_evict_inplace(ctypes.byref(cs), Q, None, V, None, None, None, ws, n_ev.value, None) == -1
@@ -193,6 +193,20 @@ def test_paged_descriptor_errors_come_before_any_launch():
     assert evict((64, 16, 5), out=(4, 4, 2, otab + 2)) == -4            # misaligned output table
     assert evict((64, 16, 5), out=(4, 4, 2, Ko + 64)) == -6             # output table inside the output pool
     assert evict((64, 16, 5), out=(4, 1 << 20, 2, otab), ko=K - (1 << 29)) == -6   # a large output pool reaches into K
+
+    # the same eviction with the kept rows written into the input's own pools
+    def inplace(pg, out, table=tab, q=Q, wsb=None):
+        cp, co = _CPages(*pg, table), _CPages(*out)
+        n = ctypes.c_size_t()
+        assert L.jq_evict_paged_inplace_workspace_bytes(ctypes.byref(cs), ctypes.byref(cp), ctypes.byref(n)) == 0 and n.value > need
+        return L.jq_evict_paged_inplace(ctypes.byref(cs), ctypes.byref(cp), ctypes.byref(co), q, K, V, None, None, None, ws,
+                                        n.value if wsb is None else wsb, None)
+    assert inplace((64, 16, 5), (32, 16, 1, otab)) == -2                # the output pages are pages of the same pool: same page size
+    assert inplace((64, 16, 5), (64, 8, 1, otab)) == -2                 # ... and same pool size
+    assert inplace((64, 16, 5), (64, 16, 1, None)) == -1
+    assert inplace((64, 16, 5), (64, 16, 1, otab), wsb=need) == -5      # no room for the staged rows and the page map
+    assert inplace((64, 16, 5), (64, 16, 1, otab), q=K + 64) == -6      # Q inside a pool that is written
+    assert inplace((64, 16, 5), (64, 16, 1, ws + 256)) == -6            # output table inside the workspace
 
 
 def test_knobs_are_read_once_and_again_on_request(monkeypatch):

@@ -252,3 +252,55 @@ def test_pages_at_the_top_of_a_pool_just_below_four_gib():
     assert_scores_close(pooled[0].cpu().numpy(), ref_p, n_q / L, "pooled")
     rk, rv = oracle.compact(K[0], V[0], np.ascontiguousarray(idx[0].cpu().numpy()))
     np.testing.assert_array_equal(from_dev_bf16(Ko)[0], rk)
+
+
+@pytest.mark.parametrize("where", ["own_first_pages", "other_sequences_pages", "free_pages"])
+def test_evict_paged_inplace_writes_the_pruned_cache_into_the_same_pools(where):
+    # The kept rows land on pages of the pools they are taken from: each sequence's own first pages (so the rest
+    # can be freed), pages that another sequence of the call still reads, or spare pages.  Read back through the
+    # output table they are the pruned cache of the ordinary paged call; pages that receive nothing are untouched.
+    torch = torch_()
+    print("paged in-place", where, flush=True)
+    ps = 64
+    w = make_workload(1, seq_lens=[1500, 700], budget=[200, 70], n_layers=2)
+    Q, K, V = w.assemble()
+    Kp_, Vp_, tab_ = page_out(K, V, w.seq_lens, ps, seed=21, spare_pages=8)
+    pages = jq.Pages(page_size=ps, n_pages=Kp_.shape[1], block_table=torch.from_numpy(tab_).cuda())
+    Kp, Vp = to_dev_bf16(Kp_), to_dev_bf16(Vp_)
+    sh = jq.Shape(n_layers=2, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets)
+    Qd = to_dev_bf16(Q)
+    Ko, Vo, idx, pooled = jq.evict_paged(sh, pages, Qd, Kp, Vp)               # reference: dense pruned cache
+    table = pages.block_table.cpu().numpy()
+    n_out = [-(-b // ps) for b in w.budgets]                                  # pages each sequence's kept rows need
+    used = set(int(x) for s_, L in enumerate(w.seq_lens) for x in table[s_, :-(-L // ps)])
+    spare = [pg for pg in range(pages.n_pages) if pg not in used]
+    out_table = np.zeros((2, max(n_out)), dtype=np.int32)
+    if where == "own_first_pages":
+        for s_ in range(2):
+            out_table[s_, :n_out[s_]] = table[s_, :n_out[s_]]
+    elif where == "other_sequences_pages":                                    # sequence 0 writes onto sequence 1's pages and vice versa
+        out_table[0, :n_out[0]] = table[1, :n_out[0]]
+        out_table[1, :n_out[1]] = table[0, 5:5 + n_out[1]]
+    else:
+        assert len(spare) >= sum(n_out)
+        out_table[0, :n_out[0]] = spare[:n_out[0]]
+        out_table[1, :n_out[1]] = spare[n_out[0]:n_out[0] + n_out[1]]
+    out_pages = jq.Pages(page_size=ps, n_pages=pages.n_pages, block_table=torch.from_numpy(out_table).cuda())
+    Kq, Vq = Kp.clone(), Vp.clone()
+    _, _, idx2, pooled2 = jq.evict_paged_inplace(sh, pages, out_pages, Qd, Kq, Vq)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(pooled, pooled2)
+    Kq_h, Vq_h, Kp_h = from_dev_bf16(Kq), from_dev_bf16(Vq), from_dev_bf16(Kp)
+    Ko_h, Vo_h = from_dev_bf16(Ko), from_dev_bf16(Vo)
+    cb = w.cu_budgets
+    written = set()
+    for s_ in range(2):
+        for b in range(w.budgets[s_]):
+            pg, r = int(out_table[s_, b // ps]), b % ps
+            np.testing.assert_array_equal(Kq_h[:, pg, r], Ko_h[:, cb[s_] + b])
+            np.testing.assert_array_equal(Vq_h[:, pg, r], Vo_h[:, cb[s_] + b])
+            written.add((pg, r))
+    for pg in range(pages.n_pages):                                           # every other row of the pools is as before
+        for r in range(ps):
+            if (pg, r) not in written:
+                assert np.array_equal(Kq_h[:, pg, r], Kp_h[:, pg, r]), (pg, r)
