@@ -55,6 +55,65 @@ def kernel_sources_sha16():
     return h.hexdigest()[:16]
 
 
+def side_legs(args, w, sh, sets, Qd, Ko, Vo, idx, pooled, ws, step, timed_loop, side):
+    """The other ways to call the same eviction on the headline workload, `side` timed steps each (ms per step)."""
+    import time
+    import torch
+    import paper_2509_10798_amd as jq
+    # same buffers every step (what a cache-warm caller would see)
+    ms_same = timed_loop(lambda i: step(0), 30, side) * 1e3
+
+    # one pass over K when the caller supplies the softmax normalisers (jq_evict_lse); a constant above every logit
+    # keeps exp() finite, the timing does not depend on the values
+    lse = torch.full((w.n_layers, w.n_seq, w.n_q, w.h_q), 30.0, dtype=torch.float32, device="cuda")
+
+    def step_lse(i):
+        Kd, Vd = sets[i % len(sets)]
+        jq.evict(sh, Qd, Kd, Vd, K_out=Ko, V_out=Vo, idx_out=idx, scores_out=pooled, ws=ws, lse=lse)
+    ms_lse = timed_loop(step_lse, 30, side) * 1e3
+
+    # the softmax also covering the soft tokens' own keys (jq_evict_tail): two passes, the keys as further tiles of
+    # the first; they are the last n_q key rows of the first buffer set
+    k_tail = sets[0][0][:, -w.n_q:].reshape(w.n_layers, 1, w.n_q, w.h_kv, w.d).expand(-1, w.n_seq, -1, -1, -1).contiguous()
+
+    def step_tail(i):
+        Kd, Vd = sets[i % len(sets)]
+        jq.evict(sh, Qd, Kd, Vd, K_out=Ko, V_out=Vo, idx_out=idx, scores_out=pooled, ws=ws, k_tail=k_tail)
+    ms_tail = timed_loop(step_tail, 30, side) * 1e3
+
+    # the same eviction on a paged cache (jq_evict_paged): pools of 256-token pages handed out in a random order
+    ms_paged, page_size = None, args.page_size
+    if all(L % page_size == 0 for L in w.seq_lens):
+        n_pages = w.total_tokens // page_size
+        gen = torch.Generator(device="cpu"); gen.manual_seed(w.seed)
+        perm = torch.randperm(n_pages, generator=gen).cuda()
+        table = torch.full((w.n_seq, max(w.seq_lens) // page_size), -1, dtype=torch.int32, device="cuda")
+        first = 0
+        for s_, L in enumerate(w.seq_lens):
+            table[s_, :L // page_size] = perm[first:first + L // page_size].to(torch.int32)
+            first += L // page_size
+        pages = jq.Pages(page_size=page_size, n_pages=n_pages, block_table=table)
+        psets = []
+        for Kd, Vd in sets:
+            Kp = torch.empty((w.n_layers, n_pages, page_size, w.h_kv, w.d), dtype=torch.bfloat16, device="cuda")
+            Vp = torch.empty_like(Kp)
+            Kp[:, perm] = Kd.view(w.n_layers, n_pages, page_size, w.h_kv, w.d)
+            Vp[:, perm] = Vd.view(w.n_layers, n_pages, page_size, w.h_kv, w.d)
+            psets.append((Kp, Vp))
+
+        def step_paged(i):
+            Kp, Vp = psets[i % len(psets)]
+            jq.evict_paged(sh, pages, Qd, Kp, Vp, K_out=Ko, V_out=Vo, idx_out=idx, scores_out=pooled, ws=ws)
+        ms_paged = timed_loop(step_paged, 30, side) * 1e3
+        del psets
+
+    # the same protocol (W warm-up steps, K timed) on a GPU that has been idle for a second: no prefill stand-in
+    torch.cuda.synchronize()
+    time.sleep(1.0)
+    ms_from_idle = timed_loop(step, args.warmup, args.steps) * 1e3
+    return ms_same, ms_lse, ms_tail, ms_paged, ms_from_idle
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +127,9 @@ def main():
                          "precedes an eviction; 0 starts from whatever state the set-up left")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--no-others", action="store_true", help="skip the other named workloads")
+    ap.add_argument("--no-sides", action="store_true",
+                    help="skip the side legs (same buffers, supplied normalisers, soft-token keys, paged cache, from idle): "
+                         "what a profiler run of the headline loop uses")
     ap.add_argument("--trace-steps", type=int, default=200)
     ap.add_argument("--page-size", type=int, default=256, help="tokens per page of the paged-cache leg")
     ap.add_argument("--probe-copy", action="store_true",
@@ -181,58 +243,10 @@ def main():
     torch.cuda.synchronize()
     per_call = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(len(evs) - 1)])
 
-    side = min(args.steps, 300)  # steps of the side legs below
-    # same buffers every step (what a cache-warm caller would see)
-    ms_same = timed_loop(lambda i: step(0), 30, side) * 1e3
-
-    # one pass over K when the caller supplies the softmax normalisers (jq_evict_lse); a constant above every logit
-    # keeps exp() finite, the timing does not depend on the values
-    lse = torch.full((w.n_layers, w.n_seq, w.n_q, w.h_q), 30.0, dtype=torch.float32, device="cuda")
-
-    def step_lse(i):
-        Kd, Vd = sets[i % len(sets)]
-        jq.evict(sh, Qd, Kd, Vd, K_out=Ko, V_out=Vo, idx_out=idx, scores_out=pooled, ws=ws, lse=lse)
-    ms_lse = timed_loop(step_lse, 30, side) * 1e3
-
-    # the softmax also covering the soft tokens' own keys (jq_evict_tail): two passes, the keys as further tiles of
-    # the first; they are the last n_q key rows of the first buffer set
-    k_tail = sets[0][0][:, -w.n_q:].reshape(w.n_layers, 1, w.n_q, w.h_kv, w.d).expand(-1, w.n_seq, -1, -1, -1).contiguous()
-
-    def step_tail(i):
-        Kd, Vd = sets[i % len(sets)]
-        jq.evict(sh, Qd, Kd, Vd, K_out=Ko, V_out=Vo, idx_out=idx, scores_out=pooled, ws=ws, k_tail=k_tail)
-    ms_tail = timed_loop(step_tail, 30, side) * 1e3
-
-    # the same eviction on a paged cache (jq_evict_paged): pools of 256-token pages handed out in a random order
-    ms_paged, page_size = None, args.page_size
-    if all(L % page_size == 0 for L in w.seq_lens):
-        n_pages = w.total_tokens // page_size
-        gen = torch.Generator(device="cpu"); gen.manual_seed(w.seed)
-        perm = torch.randperm(n_pages, generator=gen).cuda()
-        table = torch.full((w.n_seq, max(w.seq_lens) // page_size), -1, dtype=torch.int32, device="cuda")
-        first = 0
-        for s_, L in enumerate(w.seq_lens):
-            table[s_, :L // page_size] = perm[first:first + L // page_size].to(torch.int32)
-            first += L // page_size
-        pages = jq.Pages(page_size=page_size, n_pages=n_pages, block_table=table)
-        psets = []
-        for Kd, Vd in sets:
-            Kp = torch.empty((w.n_layers, n_pages, page_size, w.h_kv, w.d), dtype=torch.bfloat16, device="cuda")
-            Vp = torch.empty_like(Kp)
-            Kp[:, perm] = Kd.view(w.n_layers, n_pages, page_size, w.h_kv, w.d)
-            Vp[:, perm] = Vd.view(w.n_layers, n_pages, page_size, w.h_kv, w.d)
-            psets.append((Kp, Vp))
-
-        def step_paged(i):
-            Kp, Vp = psets[i % len(psets)]
-            jq.evict_paged(sh, pages, Qd, Kp, Vp, K_out=Ko, V_out=Vo, idx_out=idx, scores_out=pooled, ws=ws)
-        ms_paged = timed_loop(step_paged, 30, side) * 1e3
-        del psets
-
-    # the same protocol (W warm-up steps, K timed) on a GPU that has been idle for a second: no prefill stand-in
-    torch.cuda.synchronize()
-    time.sleep(1.0)
-    ms_from_idle = timed_loop(step, args.warmup, args.steps) * 1e3
+    side = 0 if args.no_sides else min(args.steps, 300)  # steps of the side legs below
+    ms_same = ms_lse = ms_tail = ms_paged = ms_from_idle = None
+    if side:
+        ms_same, ms_lse, ms_tail, ms_paged, ms_from_idle = side_legs(args, w, sh, sets, Qd, Ko, Vo, idx, pooled, ws, step, timed_loop, side)
 
     ab = algorithmic_bytes(w)
     # one launch of either K pass reads K and Q once for all layers of the call; the score pass also writes scores
@@ -271,26 +285,27 @@ def main():
                    "pool_k": w.pool_k, "kv_buffers_rotated": len(sets), "seed": w.seed},
         "gpu_state_before_warmup": ("prefill stand-in: %d bf16 4096^3 GEMMs (~%g ms), no host synchronisation before the warm-up steps"
                                     % (gemms, args.prefill_ms)) if gemms else "as the set-up left it",
-        "from_idle": {"ms_per_step": round(ms_from_idle, 5), "steps": args.steps, "warmup": args.warmup,
-                      "note": "same protocol after 1 s of idle, no stand-in"},
         "frac_hbm_peak_vs_bytes_min": round(ab["total"] * w.n_layers / sec_per_step / 1e9 / HBM_PEAK_GBS, 4),
         "bytes_min_per_layer": ab["total"],
         "both_k_passes": {"bytes": sum(pass_bytes.values()), "us": round(k_passes, 2),
                           "frac_hbm_peak": round(sum(pass_bytes.values()) / (k_passes * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "ms_per_call_event_timed": {"median": round(float(np.median(per_call)), 5), "mean": round(float(per_call.mean()), 5),
                                     "calls": int(per_call.size)},
-        "ms_per_step_same_buffers": round(ms_same, 5),
-        "supplied_lse_one_pass": {"entry": "jq_evict_lse", "ms_per_step": round(ms_lse, 5),
-                                  "tokens_per_s_per_layer": round(w.total_tokens * w.n_layers / (ms_lse * 1e-3), 1)},
-        "soft_token_keys_in_softmax": {"entry": "jq_evict_tail", "ms_per_step": round(ms_tail, 5),
-                                       "tokens_per_s_per_layer": round(w.total_tokens * w.n_layers / (ms_tail * 1e-3), 1)},
         "kernel_us": kernels_us,
         "kernel_us_median": kernels_us_median,
         "roofline": roofline,
     }
-    if ms_paged is not None:
-        out["paged_cache"] = {"entry": "jq_evict_paged", "page_size": page_size, "ms_per_step": round(ms_paged, 5),
-                              "tokens_per_s_per_layer": round(w.total_tokens * w.n_layers / (ms_paged * 1e-3), 1)}
+    if side:
+        def rate(ms):
+            return round(w.total_tokens * w.n_layers / (ms * 1e-3), 1)
+        out["from_idle"] = {"ms_per_step": round(ms_from_idle, 5), "steps": args.steps, "warmup": args.warmup,
+                            "note": "same protocol after 1 s of idle, no stand-in"}
+        out["ms_per_step_same_buffers"] = round(ms_same, 5)
+        out["supplied_lse_one_pass"] = {"entry": "jq_evict_lse", "ms_per_step": round(ms_lse, 5), "tokens_per_s_per_layer": rate(ms_lse)}
+        out["soft_token_keys_in_softmax"] = {"entry": "jq_evict_tail", "ms_per_step": round(ms_tail, 5), "tokens_per_s_per_layer": rate(ms_tail)}
+        if ms_paged is not None:
+            out["paged_cache"] = {"entry": "jq_evict_paged", "page_size": args.page_size, "ms_per_step": round(ms_paged, 5),
+                                  "tokens_per_s_per_layer": rate(ms_paged)}
 
     if not args.no_others and args.config == 3:
         # the other named workloads, one fused call each (32768-token layer; 8 of the 32 layers of the 65536-token
