@@ -290,10 +290,14 @@ __device__ __forceinline__ f32x16 stats_chain(const bf16x8 (&kf)[8], const bf16x
 
 // FIXED: keep the offsets m as they are and only accumulate Z += sum 2^(t - m).  Any offset gives the same
 // (m, Z) pair up to rounding as long as no term overflows; terms that underflow are negligible next to
-// the 2^0 the offset's own key contributed.
+// the 2^0 the offset's own key contributed.  `first` (FIXED, unmasked tiles only): this is the wave's first
+// tile, which sets each lane's offset -- to the largest of four of the lane's 16 logits, so that the first tile
+// runs through the very code of all later ones (a separate copy of the tile body for it cost the first pass
+// 1 us: 5 KB more code to fetch cold at the start of every launch).
 template <int NQT, bool MASKED, bool FIXED>
 __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (&qf)[NQT][8], float (&m)[NQT],
-                                           float (&z)[NQT], float c, const int (&valid)[NQT], int half) {
+                                           float (&z)[NQT], float c, const int (&valid)[NQT], int half,
+                                           bool first = false) {
     // software pipeline: the MFMA chain of query tile qt+1 is interleaved with the max/exp2/add work of tile qt
     f32x16 acc = stats_chain(kf, qf[0]);
 #pragma unroll
@@ -306,6 +310,7 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
                 if (8 * (v >> 2) + 4 * half + (v & 3) >= valid[qt]) acc[v] = -INFINITY;
         }
         float mnew = m[qt];
+        if (FIXED && !MASKED) mnew = first ? fmaxf(fmaxf(acc[0], acc[5]), fmaxf(acc[10], acc[15])) * c : mnew;
         if (!FIXED) {
             float tmax = fmaxf(acc[0], acc[1]);
 #pragma unroll
@@ -325,6 +330,7 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
         }
         if (FIXED) {
             z[qt] += (s0 + s1) + (s2 + s3);
+            if (!MASKED) m[qt] = mnew;
         } else {
             z[qt] = z[qt] * __builtin_amdgcn_exp2f(m[qt] - mnew) + ((s0 + s1) + (s2 + s3));
             m[qt] = mnew;
@@ -409,7 +415,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) soft_i[qt] = ((a.row_tile0 + qt) * kRowTile + (lane & 31)) / a.group;
     // One sweep over the wave's tiles (the first two are already requested).  FAST: the first tile sets each
-    // lane's offset m to the maximum of its logits there, later tiles keep it -- no maximum to track.
+    // lane's offset m from its logits there, later tiles keep it -- no maximum to track.
     auto full_tile = [&](int k, auto fixed) __attribute__((always_inline)) {
         wait_tile_landed(D == 2 && k + 1 < n_all);
         bf16x8 kf[8];
@@ -421,7 +427,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         int valid[NQT];
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) valid[qt] = kKeyTile;
-        stats_tile<NQT, false, decltype(fixed)::value>(kf, qf, m, z, c, valid, half);
+        stats_tile<NQT, false, decltype(fixed)::value>(kf, qf, m, z, c, valid, half, k == 0);
     };
     auto masked_tile = [&](int k, const int (&valid)[NQT], bool fixed) __attribute__((always_inline)) {
         wait_tile_landed(D == 2 && k + 1 < n_all);
@@ -435,8 +441,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         else stats_tile<NQT, true, false>(kf, qf, m, z, c, valid, half);
     };
     auto sweep = [&](auto fast) __attribute__((always_inline)) {
-        if (n_full > 0) full_tile(0, std::false_type{});
-        for (int k = 1; k < n_full; ++k) full_tile(k, fast);
+        for (int k = 0; k < n_full; ++k) full_tile(k, fast);
         int valid[NQT];
         for (int k = n_full; k < w.n_tiles; ++k) {  // partial last tile of the prompt, tiles that reach into the window
             const int t0 = (w.wave + k * w.n_waves) * kKeyTile;
@@ -451,13 +456,13 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
         }
     };
     sweep(std::true_type{});
-    // A logit more than 2^7 (base 2) above the first tile's maximum overflows 2^(t - m) to infinity.  That
-    // cannot be repaired afterwards, so such a wave (wave-uniform decision) repeats its sweep with the
+    // A logit more than 2^7 (base 2) above the offset the first tile chose overflows 2^(t - m) to infinity.
+    // That cannot be repaired afterwards, so such a wave (wave-uniform decision) repeats its sweep with the
     // running maximum.
     bool overflow = false;
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) overflow |= !(z[qt] < INFINITY);
-    if (__any(overflow)) {
+    if (__builtin_expect(__any(overflow), 0)) {
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
         wait_frags_read();
