@@ -21,6 +21,7 @@
  *   jq_score_paged, jq_evict_paged  the same on a paged cache (pools + block table)
  *   jq_hit_rate     critical-KV hit rate between two kept sets (Eq. 6)
  *   jq_map_mse      forward value of the training objective (Eq. 5) from two score maps
+ *   jq_map_mse_fused  the same from the two query sets, the second map never stored
  *
  * Conventions common to every entry point
  * ---------------------------------------
@@ -216,6 +217,20 @@ int jq_hit_rate(const jq_shape* shape, const int32_t* idx_cur, const int32_t* id
  * n_layers, n_seq, h_kv and cu_seqlens of `shape` matter here. */
 int jq_map_mse(const jq_shape* shape, const float* scores_a, float rows_a, const float* scores_b, float rows_b,
                float* mse, void* stream);
+
+/* The same value (Section 4.2: the maps of Eq. 3 and Eq. 4, the loss of Eq. 5) straight from the two query sets,
+ * without handing the maps to the caller: Q_a [n_layers, n_seq, shape->n_q, h_q, d] are the soft tokens' queries,
+ * Q_b [n_layers, n_seq, n_q_b, h_q, d] the response tokens' (any n_q_b >= 1; rows beyond 128 per KV head take
+ * further passes over K), K the prompt's keys as in jq_score.  The soft tokens' map is computed first; the
+ * launch that completes the response's map does not store it but accumulates
+ *   ( map_a[t] / (n_q * G) - map_b[t] / (n_q_b * G) )^2,  G = h_q / h_kv,
+ * per workgroup in fp64, and a last small launch adds the workgroups' sums in a fixed order:
+ *   mse[l,s,g] as in jq_map_mse, [n_layers, n_seq, h_kv] fp32 (DEVICE).
+ * Dense caches, prompt-only softmax (shape->window must be 0).  `ws` (DEVICE, 16-byte aligned) must hold
+ * jq_map_mse_fused_workspace_bytes; nothing may overlap anything else. */
+int jq_map_mse_fused_workspace_bytes(const jq_shape* shape, int32_t n_q_b, size_t* bytes);
+int jq_map_mse_fused(const jq_shape* shape, const void* Q_a, const void* Q_b, int32_t n_q_b, const void* K, float* mse,
+                     void* ws, size_t ws_bytes, void* stream);
 
 /* The whole eviction step of Section 4.3 at the end of prefill (Eq. 3 scores -> pooling -> top-k retention ->
  * pruned cache) for n_layers x n_seq problems: score -> pool -> select -> compact in one call.  `idx_out` (kept positions) and

@@ -21,7 +21,7 @@ _lib = None
 JQ_MAX_SEQ = 128
 STATUS = {0: "JQ_OK", -1: "JQ_ERR_NULL", -2: "JQ_ERR_SHAPE", -3: "JQ_ERR_BUDGET", -4: "JQ_ERR_UNSUPPORTED",
           -5: "JQ_ERR_WORKSPACE", -6: "JQ_ERR_ALIAS", -7: "JQ_ERR_LAUNCH"}
-EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_inplace_workspace_bytes", "jq_evict_inplace", "jq_evict_stream", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_paged_inplace_workspace_bytes", "jq_evict_paged_inplace", "jq_evict_traced", "jq_hit_rate", "jq_map_mse",
+EXPORTS = ("jq_workspace_bytes", "jq_score", "jq_score_lse", "jq_evict_lse", "jq_score_tail", "jq_evict_tail", "jq_pool", "jq_select_topk", "jq_compact", "jq_compact_inplace_workspace_bytes", "jq_compact_inplace", "jq_evict", "jq_evict_inplace_workspace_bytes", "jq_evict_inplace", "jq_evict_stream", "jq_evict_static", "jq_score_paged", "jq_evict_paged", "jq_evict_paged_inplace_workspace_bytes", "jq_evict_paged_inplace", "jq_evict_traced", "jq_hit_rate", "jq_map_mse", "jq_map_mse_fused_workspace_bytes", "jq_map_mse_fused",
            "jq_copy_probe", "jq_reload_knobs", "jq_status_string")
 TRACE_KERNELS = ("jq_stats_kernel", "jq_score_kernel", "jq_pool_kernel", "jq_select_finalize_kernel")
 TRACE_MARKS = 2 * len(TRACE_KERNELS)
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.jq_evict_lse.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_hit_rate.argtypes = [shp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, vp]
         L.jq_map_mse.argtypes = [shp, vp, ctypes.c_float, vp, ctypes.c_float, vp, vp]
+        L.jq_map_mse_fused_workspace_bytes.argtypes = [shp, ctypes.c_int32, ctypes.POINTER(sz)]
+        L.jq_map_mse_fused.argtypes = [shp, vp, vp, ctypes.c_int32, vp, vp, vp, sz, vp]
         L.jq_score_tail.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_evict_tail.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.jq_pool.argtypes = [shp, vp, vp, vp]
@@ -435,6 +437,23 @@ def map_mse(shape: Shape, scores_a, rows_a: float, scores_b, rows_b: float, mse=
     cs = shape.c_struct()
     _check(lib().jq_map_mse(ctypes.byref(cs), _ptr(scores_a), float(rows_a), _ptr(scores_b), float(rows_b), _ptr(mse),
                             _stream(stream)), "jq_map_mse")
+    return mse
+
+
+def map_mse_fused(shape: Shape, Q_a, Q_b, K, mse=None, ws=None, stream=None):
+    """Eq. 3-5 forward from the two query sets (Q_a [.., shape.n_q, h_q, d] soft tokens, Q_b [.., n_q_b, h_q, d] response
+    tokens): the second map is compared with the first inside the launch that completes it and never stored."""
+    import torch
+    n_q_b = int(Q_b.shape[2])
+    if mse is None:
+        mse = torch.empty((shape.n_layers, shape.n_seq, shape.h_kv), dtype=torch.float32, device=K.device)
+    cs = shape.c_struct()
+    if ws is None:
+        n = ctypes.c_size_t()
+        _check(lib().jq_map_mse_fused_workspace_bytes(ctypes.byref(cs), n_q_b, ctypes.byref(n)), "jq_map_mse_fused_workspace_bytes")
+        ws = torch.empty((n.value,), dtype=torch.uint8, device=K.device)
+    _check(lib().jq_map_mse_fused(ctypes.byref(cs), _ptr(Q_a), _ptr(Q_b), n_q_b, _ptr(K), _ptr(mse), _ptr(ws), ws.numel(),
+                                  _stream(stream)), "jq_map_mse_fused")
     return mse
 
 

@@ -657,6 +657,59 @@ int jq_map_mse(const jq_shape* shape, const float* scores_a, float rows_a, const
     return launch_status(launch_map_mse(p, scores_a, rows_a, scores_b, rows_b, mse, (hipStream_t)stream));
 }
 
+// Layout of the fused forward's workspace: the plan of either query set in full, then the partial sums.
+static int mse_fused_plans(const jq_shape* shape, int32_t n_q_b, Plan* pa, Plan* pb, size_t* off_b, size_t* off_part, size_t* total) {
+    int rc = make_plan(shape, false, pa);
+    if (rc != JQ_OK) return rc;
+    if (n_q_b < 1) return JQ_ERR_SHAPE;
+    if (pa->window) return JQ_ERR_SHAPE;  // the maps of Eq. 3 / Eq. 4 have no window mode
+    jq_shape sb = *shape;
+    sb.n_q = n_q_b;
+    if ((rc = make_plan(&sb, false, pb)) != JQ_OK) return rc;
+    *off_b = pa->ws_bytes;
+    *off_part = *off_b + pb->ws_bytes;
+    *total = *off_part + align_up((size_t)pb->n_layers * pb->cu_cgrp2[pb->n_seq] * pb->h_kv * sizeof(double));
+    return JQ_OK;
+}
+
+int jq_map_mse_fused_workspace_bytes(const jq_shape* shape, int32_t n_q_b, size_t* bytes) {
+    if (!bytes) return JQ_ERR_NULL;
+    Plan pa, pb;
+    size_t off_b, off_part;
+    return mse_fused_plans(shape, n_q_b, &pa, &pb, &off_b, &off_part, bytes);
+}
+
+int jq_map_mse_fused(const jq_shape* shape, const void* Q_a, const void* Q_b, int32_t n_q_b, const void* K, float* mse,
+                     void* ws, size_t ws_bytes, void* stream) {
+    Plan pa, pb;
+    size_t off_b, off_part, total;
+    const int rc = mse_fused_plans(shape, n_q_b, &pa, &pb, &off_b, &off_part, &total);
+    if (rc != JQ_OK) return rc;
+    if (!Q_a || !Q_b || !K || !mse) return JQ_ERR_NULL;
+    if (!ws) return JQ_ERR_NULL;
+    if (misaligned(ws, 16) || ws_bytes < total) return JQ_ERR_WORKSPACE;
+    if (misaligned(Q_a, 16) || misaligned(Q_b, 16) || misaligned(K, 16) || misaligned(mse, 4)) return JQ_ERR_UNSUPPORTED;
+    const size_t out_bytes = (size_t)pa.n_layers * pa.n_seq * pa.h_kv * sizeof(float);
+    const void* ins[3] = {Q_a, Q_b, K};
+    const size_t in_bytes[3] = {q_bytes(pa), q_bytes(pb), kv_bytes(pa)};
+    for (int i = 0; i < 3; ++i)
+        if (overlaps(ws, total, ins[i], in_bytes[i]) || overlaps(mse, out_bytes, ins[i], in_bytes[i])) return JQ_ERR_ALIAS;
+    if (overlaps(mse, out_bytes, ws, total)) return JQ_ERR_ALIAS;
+    hipStream_t st = (hipStream_t)stream;
+    char* w = (char*)ws;
+    float* map_a = (float*)(w + pa.off_scores);
+    float* map_b = (float*)(w + off_b + pb.off_scores);  // holds the sums of the response's earlier row groups, if any
+    hipError_t e = launch_score(pa, Q_a, K, map_a, w, st);
+    MseFuse fuse;
+    fuse.ref = map_a;
+    fuse.inv_rows_ref = 1.0f / (float)pa.rows;
+    fuse.inv_rows_own = 1.0f / (float)pb.rows;
+    fuse.part = (double*)(w + off_part);
+    if (e == hipSuccess) e = launch_score(pb, Q_b, K, map_b, w + off_b, st, nullptr, 0, nullptr, nullptr, &fuse);
+    if (e == hipSuccess) e = launch_mse_reduce(pb, fuse.part, mse, st);
+    return launch_status(e);
+}
+
 int jq_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
     if (!src || !dst) return JQ_ERR_NULL;
     if (bytes == 0 || bytes % 16 != 0) return JQ_ERR_SHAPE;

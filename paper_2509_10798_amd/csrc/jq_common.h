@@ -201,9 +201,18 @@ inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, size_t lds
 // `zero_words` words at `zero` (nullable) are cleared on the way (between the two K passes).
 // With `lse` (nullable, [n_layers, n_seq, n_q, h_q] natural-log normalisers) the statistics pass is skipped.
 // With `k_tail` (nullable, [n_layers, n_seq, n_q, h_kv, d] bf16) the normalisers also cover those keys, causally.
+// With `fuse` the last launch of the second pass does not store its scores: it compares them with a reference
+// map and leaves one partial sum of squared differences per workgroup (Eq. 5 forward, see launch_mse_reduce).
+struct MseFuse {
+    const float* ref;         // [n_layers][h_kv][T] scores of the other query set
+    float inv_rows_ref, inv_rows_own;
+    double* part;             // [n_layers][workgroups of the second pass per layer and head][h_kv]
+};
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
                         uint32_t* zero = nullptr, size_t zero_words = 0, const float* lse = nullptr,
-                        const void* k_tail = nullptr);
+                        const void* k_tail = nullptr, const MseFuse* fuse = nullptr);
+// Sums the per-workgroup partials of a fused launch in workgroup order and divides by the sequence length.
+hipError_t launch_mse_reduce(const Plan& p, const double* part, float* mse, hipStream_t st);
 // With `hist` the pooling kernel also builds the selection's level-1 histograms, and with `ws` on top of that
 // the per-workgroup sorted lists (segments) that the selection's fast path reads.
 hipError_t launch_pool(const Plan& p, const float* scores, float* pooled, uint32_t* hist_or_null, char* ws_or_null,

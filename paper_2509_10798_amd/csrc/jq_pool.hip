@@ -277,6 +277,33 @@ hipError_t launch_map_mse(const Plan& p, const float* scores_a, float rows_a, co
                          -1, a);
 }
 
+// The fused forward's last step: one thread per (layer, sequence, KV head) adds the partial sums that the
+// sequence's workgroups of the comparing launch left, in workgroup order, and divides by the sequence length.
+struct MseReduceArgs {
+    const double* part;  // [n_layers][n_cgrp][h_kv]
+    float* mse;          // [n_layers][n_seq][h_kv]
+    int32_t n_layers, n_seq, h_kv, n_cgrp;
+    int32_t cu_cgrp[JQ_MAX_SEQ + 1];
+    int32_t cu_seq[JQ_MAX_SEQ + 1];
+};
+__global__ __launch_bounds__(64) void jq_mse_reduce_kernel(MseReduceArgs a) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.n_layers * a.n_seq * a.h_kv) return;
+    const int g = i % a.h_kv, s = (i / a.h_kv) % a.n_seq, layer = i / (a.h_kv * a.n_seq);
+    double sum = 0.0;
+    for (int cg = a.cu_cgrp[s]; cg < a.cu_cgrp[s + 1]; ++cg) sum += a.part[((int64_t)layer * a.n_cgrp + cg) * a.h_kv + g];
+    a.mse[i] = (float)(sum / (double)(a.cu_seq[s + 1] - a.cu_seq[s]));
+}
+
+hipError_t launch_mse_reduce(const Plan& p, const double* part, float* mse, hipStream_t st) {
+    MseReduceArgs a;
+    a.part = part; a.mse = mse;
+    a.n_layers = p.n_layers; a.n_seq = p.n_seq; a.h_kv = p.h_kv; a.n_cgrp = p.cu_cgrp2[p.n_seq];
+    for (int s = 0; s <= p.n_seq; ++s) { a.cu_cgrp[s] = p.cu_cgrp2[s]; a.cu_seq[s] = p.tab.cu_seq[s]; }
+    const int n = p.n_layers * p.n_seq * p.h_kv;
+    return launch_kernel(jq_mse_reduce_kernel, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, st, nullptr, -1, a);
+}
+
 __global__ __launch_bounds__(256) void jq_fill_u32_kernel(uint32_t* dst, size_t n, uint32_t v) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;

@@ -71,6 +71,11 @@ struct ScoreArgs {
     // arguments, which a wave fetches in one go
     int32_t cu_part[JQ_MAX_SEQ + 1];
     SeqTab tab;
+    // DIFF kernels (training-side forward, Eq. 3-5): instead of storing its scores the launch compares them with
+    // the map of the other query set and leaves one partial sum of squared differences per workgroup
+    const float* diff_ref;    // [n_layers][h_kv][T]
+    double* diff_part;        // [n_layers][n_cgrp][h_kv]
+    float diff_inv_ref, diff_inv_own;  // 1 / summed probability rows of either map
 };
 
 constexpr int kSlotBytes = kKeyTile * kHeadDim * 2;  // 8 KiB
@@ -576,9 +581,13 @@ __device__ __forceinline__ f32x16 score_chain(const bf16x8 (&q)[8], bf16x8 qaug,
 // FROM_LSE: the caller supplied the normalisers and no statistics pass has run: lse becomes the -beta/c terms
 // on the fly (beta = lse * log2 e, c = scale * log2 e, so -beta/c = -lse / scale), and the launch also clears
 // the words the selection stage needs cleared.
-template <int NQT, bool FROM_LSE, bool PAGED>
+// DIFF: the scores are not stored; (ref / rows_ref - score / rows_own)^2 is summed instead (Eq. 5 of the paper on
+// the maps of Eq. 3 and Eq. 4), in fp64 per lane, then in a fixed order over lanes and waves.
+template <int NQT, bool FROM_LSE, bool PAGED, bool DIFF = false>
 __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kScoreWaves][2][kSlotBytes];
+    __shared__ double diff_s[DIFF ? kScoreWaves : 1];
+    if (DIFF && threadIdx.x < kScoreWaves) diff_s[threadIdx.x] = 0.0;  // before the start-up's barriers
     WaveItem w;
     wave_item(a, true, w);  // reversed order: the keys pass 1 read last are fetched first
     const int lane = threadIdx.x & 63;
@@ -653,7 +662,10 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         wait_frags_read();
         __syncthreads();  // the slot is refilled with a key tile next
     }
-    if (w.n_tiles == 0) return;  // surplus wave of the sequence's last workgroup
+    if (w.n_tiles == 0) {  // surplus wave of the sequence's last workgroup
+        if (DIFF) __syncthreads();  // the workgroup's final merge
+        return;
+    }
     const int D = a.depth;  // uniform
     if (D == 2 && w.n_tiles > 1) fetch(1);
     if (!fused) {
@@ -681,12 +693,19 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     float pending = 0.f;  // previous tile's result, stored one iteration late so that the store has a
                           // whole tile of compute to retire before the next wait on outstanding loads
     const int n_scored = a.window ? w.L - a.n_q : w.L;  // the window's own positions report 0
+    double dacc = 0.0;  // DIFF: this lane's sum of squared map differences
     auto store_tile = [&](int k, float v) {  // only the sequence's last tile can be partial
         const int t = tile_of(k);
         if (lane < 32 && t * kKeyTile + lane < w.L) {
             float* o = out + t * kKeyTile + lane;
             if (t * kKeyTile + lane >= n_scored) v = 0.f;
-            *o = a.accumulate ? *o + v : v;
+            if (DIFF) {
+                const float own = a.accumulate ? *o + v : v;
+                const double d = (double)a.diff_ref[o - a.scores] * (double)a.diff_inv_ref - (double)own * (double)a.diff_inv_own;
+                dacc += d * d;
+            } else {
+                *o = a.accumulate ? *o + v : v;
+            }
         }
     };
 
@@ -732,6 +751,20 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         pending = s;
     }
     store_tile(w.n_tiles - 1, pending);
+    if (DIFF) {  // lanes 0..31 hold the sums: butterfly within the half wave, then the four waves in wave order
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) dacc += __shfl_xor(dacc, off);
+        const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        if (lane == 0) diff_s[wv] = dacc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int cg = (a.one_L ? 0 : a.tab.cu_cgrp[w.seq]) + w.wave / kScoreWaves;  // wave 0 always has tiles
+            double sum = 0.0;
+#pragma unroll
+            for (int i = 0; i < kScoreWaves; ++i) sum += diff_s[i];
+            a.diff_part[((int64_t)w.layer * a.n_cgrp + cg) * a.h_kv + w.g] = sum;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -759,8 +792,18 @@ static hipError_t launch_score_n(int nqt, const ScoreArgs& a, dim3 grid, hipStre
     }
 }
 
+static hipError_t launch_score_diff_n(int nqt, const ScoreArgs& a, dim3 grid, hipStream_t st) {
+    dim3 block(kScoreWaves * 64);
+    switch (nqt) {
+        case 1: return launch_kernel(jq_score_kernel<1, false, false, true>, grid, block, 0, st, nullptr, -1, a);
+        case 2: return launch_kernel(jq_score_kernel<2, false, false, true>, grid, block, 0, st, nullptr, -1, a);
+        case 3: return launch_kernel(jq_score_kernel<3, false, false, true>, grid, block, 0, st, nullptr, -1, a);
+        default: return launch_kernel(jq_score_kernel<4, false, false, true>, grid, block, 0, st, nullptr, -1, a);
+    }
+}
+
 hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scores, char* ws, hipStream_t st,
-                        uint32_t* zero, size_t zero_words, const float* lse, const void* k_tail) {
+                        uint32_t* zero, size_t zero_words, const float* lse, const void* k_tail, const MseFuse* fuse) {
     void* const* marks = p.marks;
     ScoreArgs a;
     a.Q = (const uint16_t*)Q;
@@ -787,7 +830,9 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
     a.zero = zero; a.zero_words = zero_words;
     a.tab = p.tab;
     a.block_table = p.block_table; a.page_shift = p.page_shift; a.n_pages = p.n_pages; a.max_pages = p.max_pages;
+    a.diff_ref = nullptr; a.diff_part = nullptr; a.diff_inv_ref = a.diff_inv_own = 0.0f;
     const bool paged = p.block_table != nullptr;
+    if (fuse && (paged || lse)) return hipErrorInvalidValue;  // the fused comparison exists for dense two-pass calls
     a.chunk_keys = p.chunk_keys; a.n_chunks = p.n_chunks;
     a.n_cgrp = p.tab.cu_cgrp[p.n_seq];
     a.one_L = p.n_seq == 1 ? p.tab.cu_seq[1] : 0;
@@ -833,6 +878,13 @@ hipError_t launch_score(const Plan& p, const void* Q, const void* K, float* scor
         a.accumulate = rg > 0;
         if (rg > 0) a.zero = nullptr;  // cleared once, by the first launch (normalisers supplied: no combine step does it)
         const int nqt = min(kMaxRowTiles, p.row_tiles - a.row_tile0);
+        if (fuse && rg == p.row_groups - 1) {  // the last row group completes the scores: compare instead of storing
+            a.diff_ref = fuse->ref; a.diff_part = fuse->part;
+            a.diff_inv_ref = fuse->inv_rows_ref; a.diff_inv_own = fuse->inv_rows_own;
+            e = launch_score_diff_n(nqt, a, grid, st);
+            if (e != hipSuccess) return e;
+            continue;
+        }
         if (paged) e = lse ? launch_score_n<true, true>(nqt, a, grid, st, marks) : launch_score_n<false, true>(nqt, a, grid, st, marks);
         else e = lse ? launch_score_n<true, false>(nqt, a, grid, st, marks) : launch_score_n<false, false>(nqt, a, grid, st, marks);
         if (e != hipSuccess) return e;

@@ -109,6 +109,19 @@ def test_null_and_alias_errors_come_before_any_launch():
     assert L.jq_map_mse(ctypes.byref(cs), K, 1.0, None, 1.0, ws, None) == -1
     assert L.jq_map_mse(ctypes.byref(cs), K, 0.0, V, 1.0, ws, None) == -2                          # no rows
     assert L.jq_map_mse(ctypes.byref(cs), K, 1.0, V, 1.0, K + 64, None) == -6                      # result inside an input
+    # the same objective from the two query sets
+    nf = ctypes.c_size_t()
+    assert L.jq_map_mse_fused_workspace_bytes(ctypes.byref(cs), 70, ctypes.byref(nf)) == 0 and nf.value > need
+    assert L.jq_map_mse_fused_workspace_bytes(ctypes.byref(cs), 0, ctypes.byref(nf)) == -2          # no response tokens
+    assert L.jq_map_mse_fused_workspace_bytes(ctypes.byref(cs), 70, None) == -1
+    L.jq_map_mse_fused_workspace_bytes(ctypes.byref(cs), 70, ctypes.byref(nf))
+    fused = lambda qa=Q, qb=Q + (1 << 22), k=K, out=V, w=ws, wb=None: L.jq_map_mse_fused(
+        ctypes.byref(cs), qa, qb, 70, k, out, w, nf.value if wb is None else wb, None)
+    assert fused(qb=None) == -1 and fused(out=None) == -1 and fused(w=None) == -1
+    assert fused(wb=nf.value - 1) == -5
+    assert fused(out=K + 64) == -6                                                                  # result inside the keys
+    assert fused(qb=ws + 256) == -6                                                                 # queries inside the workspace
+    assert fused(qa=Q + 2) == -4                                                                    # misaligned queries
     assert L.jq_copy_probe(K, K + 64, 1024, None) == -6 and L.jq_copy_probe(K, Ko, 24, None) == -2
     assert L.jq_compact(ctypes.byref(cs), K, V, ws, V, Vo, None) == -6
     assert L.jq_pool(ctypes.byref(cs), K, K, None) == -6

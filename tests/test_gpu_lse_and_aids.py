@@ -197,3 +197,50 @@ def test_map_mse_of_soft_and_response_maps_matches_oracle():
         # and the reduction itself is exact to fp32 rounding when fed the GPU's own maps
         own = oracle.map_mse(sa[0, :, cu[s]:cu[s + 1]].cpu().numpy(), n * G, sb[0, :, cu[s]:cu[s + 1]].cpu().numpy(), m * G)
         np.testing.assert_allclose(got[0, s], own, rtol=2e-6)
+
+
+@pytest.mark.parametrize("n,m,seq_lens", [
+    (8, 70, [900, 333]),      # response rows beyond 128 per head: two earlier row groups are summed, the third compares
+    (32, 24, [4099]),         # one row group each; many workgroups, ragged last tile
+    (4, 1, [31, 64, 1]),      # sub-tile sequences, surplus waves in every workgroup
+])
+def test_map_mse_fused_matches_oracle_and_the_two_call_composition(n, m, seq_lens):
+    # Eq. 3-5 forward from the two query sets: the response's map is never stored
+    torch = torch_()
+    rng = np.random.default_rng(82 + n)
+    h_q, h_kv, d = 8, 2, 128
+    T, ns = sum(seq_lens), len(seq_lens)
+    K = f32_to_bf16_bits(rng.standard_normal((2, T, h_kv, d)).astype(np.float32))
+    Qs = f32_to_bf16_bits(rng.standard_normal((2, ns, n, h_q, d)).astype(np.float32))
+    Qr = f32_to_bf16_bits(rng.standard_normal((2, ns, m, h_q, d)).astype(np.float32))
+    G = h_q // h_kv
+    Kd, Qsd, Qrd = to_dev_bf16(K), to_dev_bf16(Qs), to_dev_bf16(Qr)
+    sh_s = jq.Shape(n_layers=2, seq_lens=seq_lens, n_q=n, h_q=h_q, h_kv=h_kv)
+    sh_r = jq.Shape(n_layers=2, seq_lens=seq_lens, n_q=m, h_q=h_q, h_kv=h_kv)
+    got = jq.map_mse_fused(sh_s, Qsd, Qrd, Kd)
+    two = jq.map_mse(sh_s, jq.score(sh_s, Qsd, Kd), n * G, jq.score(sh_r, Qrd, Kd), m * G)
+    torch.cuda.synchronize()
+    got, two = got.cpu().numpy(), two.cpu().numpy()
+    # same maps, same fp64 squares; only the order of the additions differs from the stand-alone reduction
+    np.testing.assert_allclose(got, two, rtol=1e-5)
+    cu = np.concatenate([[0], np.cumsum(seq_lens)])
+    for layer in range(2):
+        for s in range(ns):
+            ra = oracle.score(Qs[layer, s], K[layer, cu[s]:cu[s + 1]])
+            rb = oracle.score(Qr[layer, s], K[layer, cu[s]:cu[s + 1]])
+            np.testing.assert_allclose(got[layer, s], oracle.map_mse(ra, n * G, rb, m * G), rtol=8e-3)
+    # a second call on the same workspace gives the same bits (fixed summation order)
+    again = jq.map_mse_fused(sh_s, Qsd, Qrd, Kd)
+    torch.cuda.synchronize()
+    assert np.array_equal(again.cpu().numpy(), got)
+
+
+def test_map_mse_fused_of_identical_query_sets_is_zero():
+    torch = torch_()
+    rng = np.random.default_rng(90)
+    K = to_dev_bf16(f32_to_bf16_bits(rng.standard_normal((1, 2000, 2, 128)).astype(np.float32)))
+    Q = to_dev_bf16(f32_to_bf16_bits(rng.standard_normal((1, 1, 16, 8, 128)).astype(np.float32)))
+    sh = jq.Shape(n_layers=1, seq_lens=[2000], n_q=16, h_q=8, h_kv=2)
+    got = jq.map_mse_fused(sh, Q, Q.clone(), K)
+    torch.cuda.synchronize()
+    assert float(got.abs().max()) == 0.0
