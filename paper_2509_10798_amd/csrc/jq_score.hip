@@ -293,16 +293,16 @@ __device__ __forceinline__ f32x16 stats_chain(const bf16x8 (&kf)[8], const bf16x
     return acc;
 }
 
-// FIXED: keep the offsets m as they are and only accumulate Z += sum 2^(t - m).  Any offset gives the same
-// (m, Z) pair up to rounding as long as no term overflows; terms that underflow are negligible next to
-// the 2^0 the offset's own key contributed.  `first` (FIXED, unmasked tiles only): this is the wave's first
-// tile, which sets each lane's offset -- to the largest of four of the lane's 16 logits, so that the first tile
-// runs through the very code of all later ones (a separate copy of the tile body for it cost the first pass
-// 1 us: 5 KB more code to fetch cold at the start of every launch).
+// Two instances exist.  <false, true>, the hot one: unmasked tile, offsets m kept as they are, only
+// Z += sum 2^(t - m).  Any offset gives the same (m, Z) pair up to rounding as long as no term overflows; terms
+// that underflow are negligible next to the contribution of the offset's own key.  `flag` there marks the wave's
+// first tile, which sets each lane's offset -- to the largest of four of the lane's 16 logits, so that the first
+// tile runs through the very code of all later ones.  <true, false>, the general one: masked, and `flag` says
+// whether the offsets are kept (then m stays and the update below reduces to Z += sum) or follow the running
+// maximum.
 template <int NQT, bool MASKED, bool FIXED>
 __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (&qf)[NQT][8], float (&m)[NQT],
-                                           float (&z)[NQT], float c, const int (&valid)[NQT], int half,
-                                           bool first = false) {
+                                           float (&z)[NQT], float c, const int (&valid)[NQT], int half, bool flag) {
     // software pipeline: the MFMA chain of query tile qt+1 is interleaved with the max/exp2/add work of tile qt
     f32x16 acc = stats_chain(kf, qf[0]);
 #pragma unroll
@@ -315,12 +315,12 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
                 if (8 * (v >> 2) + 4 * half + (v & 3) >= valid[qt]) acc[v] = -INFINITY;
         }
         float mnew = m[qt];
-        if (FIXED && !MASKED) mnew = first ? fmaxf(fmaxf(acc[0], acc[5]), fmaxf(acc[10], acc[15])) * c : mnew;
+        if (FIXED) mnew = flag ? fmaxf(fmaxf(acc[0], acc[5]), fmaxf(acc[10], acc[15])) * c : mnew;
         if (!FIXED) {
             float tmax = fmaxf(acc[0], acc[1]);
 #pragma unroll
             for (int v = 2; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
-            mnew = fmaxf(m[qt], tmax * c);
+            mnew = flag ? mnew : fmaxf(m[qt], tmax * c);  // a fully masked column keeps m: 2^(-inf - m) = 0 either way
         }
         float s0 = __builtin_amdgcn_exp2f(fmaf(acc[0], c, -mnew));
         float s1 = __builtin_amdgcn_exp2f(fmaf(acc[1], c, -mnew));
@@ -335,7 +335,7 @@ __device__ __forceinline__ void stats_tile(const bf16x8 (&kf)[8], const bf16x8 (
         }
         if (FIXED) {
             z[qt] += (s0 + s1) + (s2 + s3);
-            if (!MASKED) m[qt] = mnew;
+            m[qt] = mnew;
         } else {
             z[qt] = z[qt] * __builtin_amdgcn_exp2f(m[qt] - mnew) + ((s0 + s1) + (s2 + s3));
             m[qt] = mnew;
@@ -419,62 +419,63 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     int soft_i[NQT];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) soft_i[qt] = ((a.row_tile0 + qt) * kRowTile + (lane & 31)) / a.group;
-    // One sweep over the wave's tiles (the first two are already requested).  FAST: the first tile sets each
-    // lane's offset m from its logits there, later tiles keep it -- no maximum to track.
-    auto full_tile = [&](int k, auto fixed) __attribute__((always_inline)) {
+    // The kernel holds TWO copies of the tile body, not one per case: the hot one (unmasked tile, offsets fixed
+    // after the wave's first tile) and a general one whose masking and offset rule are run-time flags, used by the
+    // few masked tiles (partial last tile, window, soft tokens' own keys) and by the rare repeat of a sweep.
+    // (A copy per case made the kernel 45 KB of code instead of 23 KB, for no gain in time.)
+    auto tile_prologue = [&](int k, bf16x8 (&kf)[8]) __attribute__((always_inline)) {
         wait_tile_landed(D == 2 && k + 1 < n_all);
-        bf16x8 kf[8];
         lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
         if (k + D < n_all) {
             wait_frags_read();
             fetch(k + D);
         }
-        int valid[NQT];
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) valid[qt] = kKeyTile;
-        stats_tile<NQT, false, decltype(fixed)::value>(kf, qf, m, z, c, valid, half, k == 0);
     };
-    auto masked_tile = [&](int k, const int (&valid)[NQT], bool fixed) __attribute__((always_inline)) {
-        wait_tile_landed(D == 2 && k + 1 < n_all);
-        bf16x8 kf[8];
-        lds_get_frags(slots + (k & 1) * kSlotBytes, kf, lane);
-        if (k + D < n_all) {
-            wait_frags_read();
-            fetch(k + D);
-        }
-        if (fixed) stats_tile<NQT, true, true>(kf, qf, m, z, c, valid, half);
-        else stats_tile<NQT, true, false>(kf, qf, m, z, c, valid, half);
-    };
-    auto sweep = [&](auto fast) __attribute__((always_inline)) {
-        for (int k = 0; k < n_full; ++k) full_tile(k, fast);
-        int valid[NQT];
-        for (int k = n_full; k < w.n_tiles; ++k) {  // partial last tile of the prompt, tiles that reach into the window
+    // rows of tile k that exist for this lane's query row of each query tile (32 or more: all of them)
+    auto valid_rows = [&](int k, int (&valid)[NQT]) __attribute__((always_inline)) {
+        if (k < w.n_tiles) {
             const int t0 = (w.wave + k * w.n_waves) * kKeyTile;
 #pragma unroll
             for (int qt = 0; qt < NQT; ++qt) valid[qt] = (a.window ? n_common + soft_i[qt] + 1 : w.L) - t0;
-            masked_tile(k, valid, decltype(fast)::value && k > 0);
-        }
-        for (int t = 0; t < n_tail; ++t) {  // soft token t * 32 + j is visible to the row of soft token i iff it is <= i
+        } else {  // soft token t * 32 + j is visible to the row of soft token i iff it is <= i
+            const int t = k - w.n_tiles;
 #pragma unroll
             for (int qt = 0; qt < NQT; ++qt) valid[qt] = soft_i[qt] + 1 - t * kKeyTile;
-            masked_tile(w.n_tiles + t, valid, decltype(fast)::value);
         }
     };
-    sweep(std::true_type{});
-    // A logit more than 2^7 (base 2) above the offset the first tile chose overflows 2^(t - m) to infinity.
-    // That cannot be repaired afterwards, so such a wave (wave-uniform decision) repeats its sweep with the
-    // running maximum.
-    bool overflow = false;
+    // First sweep: the wave's first tile sets each lane's offset m from its logits there, later tiles keep it --
+    // no maximum to track.  A logit more than 2^7 (base 2) above that offset overflows 2^(t - m) to infinity, which
+    // cannot be repaired afterwards, so such a wave (wave-uniform decision) sweeps again with the running maximum.
+    int k = 0;
+    for (; k < n_full; ++k) {
+        bf16x8 kf[8];
+        tile_prologue(k, kf);
+        int valid[NQT];
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) overflow |= !(z[qt] < INFINITY);
-    if (__builtin_expect(__any(overflow), 0)) {
+        for (int qt = 0; qt < NQT; ++qt) valid[qt] = kKeyTile;
+        stats_tile<NQT, false, true>(kf, qf, m, z, c, valid, half, k == 0);
+    }
+    bool repeat = false;  // uniform
+    for (;;) {
+        for (; k < n_all; ++k) {
+            bf16x8 kf[8];
+            tile_prologue(k, kf);
+            int valid[NQT];
+            valid_rows(k, valid);
+            stats_tile<NQT, true, false>(kf, qf, m, z, c, valid, half, !repeat && k > 0);
+        }
+        bool overflow = false;
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) overflow |= !(z[qt] < INFINITY);
+        if (repeat || !__builtin_expect(__any(overflow), 0)) break;
+        repeat = true;
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) { m[qt] = -1.0e30f; z[qt] = 0.0f; }
         wait_frags_read();
         first_page();
         fetch(0);
         if (D == 2 && n_all > 1) fetch(1);
-        sweep(std::false_type{});
+        k = 0;
     }
 
     }  // n_all > 0
@@ -618,28 +619,44 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     }
     // Pass 1 left one (m, Z) partial per workgroup; unless a combine launch has merged them already, this
     // workgroup merges the partials of its head's rows itself: thread t takes row t / 2 and every second
-    // partial (loads issued here, consumed after the query rows are in), pairs meet by shuffle, and the rows'
-    // -beta/c terms pass through LDS.
+    // partial.  Its first 16 loads -- all of them when the sequence left at most 32 partials -- are issued here,
+    // together with the first key tile and, next, the query rows, and consumed once the query rows are in, so
+    // that the start-up pays one memory round trip, not three; pairs meet by shuffle, and the rows' -beta/c terms
+    // pass through LDS.
     const bool fused = !FROM_LSE && a.fuse_combine;  // uniform
-    float cM = -1.0e30f, cZ = 0.f;
-    if (fused && (threadIdx.x >> 1) < NQT * kRowTile) {
+    const bool merges = fused && (threadIdx.x >> 1) < NQT * kRowTile;
+    constexpr int kFirstParts = 16;  // partials per thread requested up front: all of them for up to 32 per row
+    float2 mz[kFirstParts];
+    const int p0 = (int)(threadIdx.x & 1);
+    int n_p = 0;
+    const float2* pp = nullptr;
+    const int64_t pstep = (int64_t)a.h_kv * a.RP;
+    if (merges) {
         const int crow = a.row_tile0 * kRowTile + (int)(threadIdx.x >> 1);
-        const int c0 = a.one_L ? 0 : a.cu_part[w.seq], n_p = a.one_L ? a.n_part : a.cu_part[w.seq + 1] - c0;
-        const float2* pp = a.stats + (((int64_t)w.layer * a.n_part + c0) * a.h_kv + w.g) * a.RP + crow;
-        const int64_t pstep = (int64_t)a.h_kv * a.RP;
-        for (int k0 = (int)(threadIdx.x & 1); k0 < n_p; k0 += 16) {  // 8 independent loads in flight
-            float2 mz[8];
+        const int c0 = a.one_L ? 0 : a.cu_part[w.seq];
+        n_p = a.one_L ? a.n_part : a.cu_part[w.seq + 1] - c0;
+        pp = a.stats + (((int64_t)w.layer * a.n_part + c0) * a.h_kv + w.g) * a.RP + crow;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) mz[u] = k0 + 2 * u < n_p ? pp[(k0 + 2 * u) * pstep] : make_float2(-1.0e30f, 0.f);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const float mm = fmaxf(cM, mz[u].x);
-                cZ = cZ * __builtin_amdgcn_exp2f(cM - mm) + mz[u].y * __builtin_amdgcn_exp2f(mz[u].x - mm);
-                cM = mm;
-            }
-        }
+        for (int u = 0; u < kFirstParts; ++u) mz[u] = p0 + 2 * u < n_p ? pp[(p0 + 2 * u) * pstep] : make_float2(-1.0e30f, 0.f);
     }
     load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
+    float cM = -1.0e30f, cZ = 0.f;
+    auto merge_in = [&](float2 t) __attribute__((always_inline)) {
+        const float mm = fmaxf(cM, t.x);
+        cZ = cZ * __builtin_amdgcn_exp2f(cM - mm) + t.y * __builtin_amdgcn_exp2f(t.x - mm);
+        cM = mm;
+    };
+    if (merges) {  // ascending partial index, the same order whatever their number
+#pragma unroll
+        for (int u = 0; u < kFirstParts; ++u) merge_in(mz[u]);
+        for (int k0 = p0 + 2 * kFirstParts; k0 < n_p; k0 += 16) {  // a sequence that left more than 32 partials
+            float2 more[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) more[u] = k0 + 2 * u < n_p ? pp[(k0 + 2 * u) * pstep] : make_float2(-1.0e30f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) merge_in(more[u]);
+        }
+    }
     if (fused) {
         const float oM = __shfl_xor(cM, 1), oZ = __shfl_xor(cZ, 1);  // the odd neighbour's half; even threads finish the row
         const float mm = fmaxf(cM, oM);
