@@ -10,7 +10,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libjq.so")
 OBJ = os.path.join(PKG, "_build")
-SOURCES = ["jq_api.hip", "jq_score.hip", "jq_pool.hip", "jq_select.hip", "jq_compact.hip"]
+# one translation unit (csrc/jq_lib.hip says why); the other .hip files are its parts
+SOURCES = ["jq_lib.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -310,6 +310,8 @@ __global__ __launch_bounds__(256) void jq_fill_u32_kernel(uint32_t* dst, size_t 
     for (; i < n; i += stride) dst[i] = v;
 }
 
+template __global__ void jq_pool_kernel<true, 7>(PoolArgs);  // placement: see jq_lib.hip
+
 static PoolArgs make_args(const Plan& p, const float* in, float* out, uint32_t* hist, char* ws) {
     PoolArgs a;
     a.in = in; a.out = out; a.hist = hist;

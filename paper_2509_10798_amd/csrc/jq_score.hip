@@ -184,6 +184,18 @@ __device__ __forceinline__ void fetch_tile(__amdgpu_buffer_rsrc_t rsrc, char* sl
     }
 }
 
+// The same with the general addressing whatever `valid` (>= 1) is: no branch, for requests that have to sit in one
+// basic block with other loads.
+__device__ __forceinline__ void fetch_tile_any(__amdgpu_buffer_rsrc_t rsrc, char* slot, uint32_t tile_off,
+                                               uint32_t row_bytes, int valid, int lane) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + (lane >> 4);
+        const uint32_t voff = (uint32_t)min(r, valid - 1) * row_bytes + (((lane & 15) ^ (r & 15)) << 4);
+        lds_dma16(rsrc, slot + 1024 * i, voff, tile_off);
+    }
+}
+
 // MFMA operand fragments of the tile in `slot`: lane l takes key row (l & 31), logical chunks
 // 2 ks + (l >> 5), ks = 0..7.  The 16 lanes of a quarter wave hit 16 distinct physical chunks.
 __device__ __forceinline__ void lds_get_frags(const char* slot, bf16x8 (&kf)[8], int lane) {
@@ -232,6 +244,91 @@ __device__ __forceinline__ void load_q_shared(const ScoreArgs& a, const WaveItem
     for (int qt = 0; qt < NQT; ++qt) lds_get_frags(lds_base + (qt * 2 + 1) * kSlotBytes, qf[qt], lane);
     wait_frags_read();
     __syncthreads();
+}
+
+// ---- the same start-up with the first key tile in flight across it (second pass) ----------------------
+// The compiler cannot tell which LDS bytes a direct-to-LDS load writes, so before any LDS access it generates
+// it waits for every such load that is outstanding -- here that would be the first key tile, whose flight
+// (the first sixteenth of K arriving at the rate of the memory system) is exactly what the start-up should hide
+// behind.  The LDS instructions of the start-up are therefore written out, with their own waits: nothing the
+// compiler generates touches LDS between the request of the first key tile and the first wait_tile_landed().
+// Global loads into registers issued BEFORE the tile's request still get their exact waits from the compiler
+// (loads return in issue order, so waiting for one of them never waits for the younger tile).
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+__device__ __forceinline__ void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void lds_put16(uint32_t addr, u32x4 v) { asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory"); }
+__device__ __forceinline__ void lds_put8(uint32_t addr, uint2 v) {
+    const uint64_t x = (uint64_t)v.x | ((uint64_t)v.y << 32);
+    asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(x) : "memory");
+}
+__device__ __forceinline__ uint2 lds_get8_waited(uint32_t addr) {
+    uint64_t x;
+    asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(x) : "v"(addr) : "memory");
+    return make_uint2((uint32_t)x, (uint32_t)(x >> 32));
+}
+// lds_get_frags with explicit instructions; returns when the fragments are in registers
+__device__ __forceinline__ void lds_get_frags_waited(uint32_t slot, bf16x8 (&kf)[8], int lane) {
+    const uint32_t r = (uint32_t)lane & 31u, hi = (uint32_t)lane >> 5;
+    uint32_t ad[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) ad[ks] = slot + r * 256u + (((2u * ks + hi) ^ (r & 15u)) << 4);
+    u32x4 o0, o1, o2, o3, o4, o5, o6, o7;
+    asm volatile(
+        "ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %10\n\tds_read_b128 %3, %11\n\t"
+        "ds_read_b128 %4, %12\n\tds_read_b128 %5, %13\n\tds_read_b128 %6, %14\n\tds_read_b128 %7, %15\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3), "=&v"(o4), "=&v"(o5), "=&v"(o6), "=&v"(o7)
+        : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "v"(ad[4]), "v"(ad[5]), "v"(ad[6]), "v"(ad[7])
+        : "memory");
+    kf[0] = as_bf16x8(o0); kf[1] = as_bf16x8(o1); kf[2] = as_bf16x8(o2); kf[3] = as_bf16x8(o3);
+    kf[4] = as_bf16x8(o4); kf[5] = as_bf16x8(o5); kf[6] = as_bf16x8(o6); kf[7] = as_bf16x8(o7);
+}
+// Barrier between phases that communicate through the LDS instructions above (each of which has waited for its
+// own completion): no fence, hence no wait the compiler would add for loads in flight.
+__device__ __forceinline__ void bare_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+// Where the query rows that this wave stages live (every wave computes addresses, so that the loads themselves
+// can be issued unconditionally; waves beyond the row tiles take the last tile's and never store them).  Rows past
+// the end take the address of row 0 of the head, in bounds, and are zeroed when staged -- `pad`, bit i: load i is
+// such a row.
+template <int NQT>
+__device__ __forceinline__ void q_rows_where(const ScoreArgs& a, const WaveItem& w, int lane, const u32x4* (&src)[8], uint32_t& pad) {
+    const int wv = min(__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), NQT - 1);
+    const char* qbase = (const char*)a.Q + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q) * a.h_q * kHeadDim * 2;
+    pad = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + (lane >> 4);
+        const int row = (a.row_tile0 + wv) * kRowTile + r;
+        const bool valid = row < a.rows;
+        const int rowc = valid ? row : 0;
+        int it, hh;
+        if (a.group_shift >= 0) { it = rowc >> a.group_shift; hh = rowc & (a.group - 1); }
+        else { it = rowc / a.group; hh = rowc % a.group; }
+        const int c = (lane & 15) ^ (r & 15);
+        src[i] = (const u32x4*)(qbase + ((int64_t)it * a.h_q + (w.g * a.group + hh)) * kHeadDim * 2 + c * 16);
+        pad |= valid ? 0u : 1u << i;
+    }
+}
+// ... and their way through LDS into operand order, as load_q_shared, with the first key tile in flight.
+template <int NQT>
+__device__ __forceinline__ void q_rows_stage(int lane, char* lds_base, const u32x4 (&raw)[8], uint32_t pad, bf16x8 (&qf)[NQT][8]) {
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (wv < NQT) {
+        const uint32_t slot = lds_addr(lds_base + (wv * 2 + 1) * kSlotBytes);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lds_put16(slot + 1024u * i + 16u * lane, (pad >> i) & 1u ? u32x4{0u, 0u, 0u, 0u} : raw[i]);
+        lds_wait_all();
+    }
+    bare_barrier();
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) lds_get_frags_waited(lds_addr(lds_base + (qt * 2 + 1) * kSlotBytes), qf[qt], lane);
+    bare_barrier();
 }
 
 struct KeyStream {
@@ -506,6 +603,10 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     }
 }
 
+// The instance of the headline shape (128 query rows per KV head, dense cache), emitted here so that it lies next
+// to the other kernels of a step in the library's code (see jq_lib.hip).
+template __global__ void jq_stats_kernel<4, false>(ScoreArgs);
+
 // -beta/c as the three truncated bf16 terms that enter the second pass through its extra MFMA step.
 __device__ __forceinline__ uint2 split_bf16x3(float x) {
     const uint32_t hi = __float_as_uint(x) & 0xFFFF0000u;
@@ -601,7 +702,7 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     // of the sequence is what the caches still hold): its k-th tile here is sequence tile tile_of(k).
     auto tile_of = [&](int k) { return w.wave + (w.n_tiles - 1 - k) * w.n_waves; };
     // PAGED: as in the first pass, the table word of the next request (k + 1) is loaded one request ahead
-    int page_next = (PAGED && w.n_tiles > 0) ? tile_page<PAGED>(ks, tile_of(0)) : 0;
+    int page_next = 0;  // set by the start-up's first request
     auto fetch = [&](int k) __attribute__((always_inline)) {
         const int t = tile_of(k);
         const int page = page_next;
@@ -609,37 +710,73 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         fetch_tile(ks.rsrc, slots + (k & 1) * kSlotBytes, tile_offset<PAGED>(ks, t, page), ks.row_bytes,
                    w.L - t * kKeyTile, tl, lane);
     };
-    if (w.n_tiles > 0) fetch(0);
     bf16x8 qf[NQT][8];
     bf16x8 qaug[NQT];
-    if (a.zero) {
-        const uint64_t per = (a.zero_words + gridDim.x - 1) / gridDim.x;
-        const uint64_t z0 = per * blockIdx.x, z1 = z0 + per < a.zero_words ? z0 + per : a.zero_words;
-        for (uint64_t i = z0 + threadIdx.x; i < z1; i += blockDim.x) a.zero[i] = 0u;
-    }
+    // Start-up.  Requested first, into registers: the query rows, the first pass's partial statistics (or the
+    // normalisers themselves); then the first key tile, straight into LDS.  Everything up to the sweep works on the
+    // former while the latter is in flight (see lds_addr() above for why the LDS instructions here are explicit).
+    // The compiler can only count on loads that are certain to have been issued, so every request below is
+    // unconditional -- addresses are clamped, values that turn out not to be needed are dropped -- and all of them
+    // sit in one basic block: then each wait is exactly "everything older than this value", never the key tile.
+    const bool fused = !FROM_LSE && a.fuse_combine;  // uniform
+    constexpr int kFirstParts = 16;  // partials per thread requested up front: all of them for up to 32 per row
+    const int p0 = (int)(threadIdx.x & 1);
     // Pass 1 left one (m, Z) partial per workgroup; unless a combine launch has merged them already, this
     // workgroup merges the partials of its head's rows itself: thread t takes row t / 2 and every second
-    // partial.  Its first 16 loads -- all of them when the sequence left at most 32 partials -- are issued here,
-    // together with the first key tile and, next, the query rows, and consumed once the query rows are in, so
-    // that the start-up pays one memory round trip, not three; pairs meet by shuffle, and the rows' -beta/c terms
-    // pass through LDS.
-    const bool fused = !FROM_LSE && a.fuse_combine;  // uniform
-    const bool merges = fused && (threadIdx.x >> 1) < NQT * kRowTile;
-    constexpr int kFirstParts = 16;  // partials per thread requested up front: all of them for up to 32 per row
-    float2 mz[kFirstParts];
-    const int p0 = (int)(threadIdx.x & 1);
-    int n_p = 0;
-    const float2* pp = nullptr;
+    // partial; pairs meet by shuffle, and the rows' -beta/c terms pass through LDS.
+    const int mrow = min((int)(threadIdx.x >> 1), NQT * kRowTile - 1);
+    const int c0 = (a.one_L || !fused) ? 0 : a.cu_part[w.seq];
+    const int n_p = !fused ? 1 : a.one_L ? a.n_part : a.cu_part[w.seq + 1] - c0;
+    const float2* pp = a.stats + (((int64_t)w.layer * a.n_part + c0) * a.h_kv + w.g) * a.RP + a.row_tile0 * kRowTile + mrow;
     const int64_t pstep = (int64_t)a.h_kv * a.RP;
-    if (merges) {
-        const int crow = a.row_tile0 * kRowTile + (int)(threadIdx.x >> 1);
-        const int c0 = a.one_L ? 0 : a.cu_part[w.seq];
-        n_p = a.one_L ? a.n_part : a.cu_part[w.seq + 1] - c0;
-        pp = a.stats + (((int64_t)w.layer * a.n_part + c0) * a.h_kv + w.g) * a.RP + crow;
+    const u32x4* qsrc[8];
+    uint32_t qpad;
+    q_rows_where<NQT>(a, w, lane, qsrc, qpad);
+    const float* nsrc[NQT];  // FROM_LSE: the lane's rows' normalisers; otherwise the merged -beta/c terms of a combine launch
 #pragma unroll
-        for (int u = 0; u < kFirstParts; ++u) mz[u] = p0 + 2 * u < n_p ? pp[(p0 + 2 * u) * pstep] : make_float2(-1.0e30f, 0.f);
+    for (int qt = 0; qt < NQT; ++qt) {
+        const int row = min((a.row_tile0 + qt) * kRowTile + (lane & 31), a.rows - 1);
+        if (FROM_LSE) {
+            const int i = row / a.group, h = w.g * a.group + row % a.group;
+            nsrc[qt] = a.lse + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q + i) * a.h_q + h;
+        } else {
+            nsrc[qt] = (const float*)(a.aug + ((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP + (a.row_tile0 + qt) * kRowTile + (lane & 31));
+        }
     }
-    load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
+    const int t_first = w.n_tiles > 0 ? tile_of(0) : 0;  // a surplus wave requests the sequence's first tile and drops it
+    const int page_first = PAGED ? tile_page<PAGED>(ks, t_first) : 0;
+    if (PAGED && w.n_tiles > 1) page_next = tile_page<PAGED>(ks, t_first - w.n_waves);
+    const uint32_t off_first = tile_offset<PAGED>(ks, t_first, page_first);
+    const int valid_first = min(kKeyTile, w.L - t_first * kKeyTile);
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 qraw[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qraw[i] = *qsrc[i];
+    float2 mz[kFirstParts];
+#pragma unroll
+    for (int u = 0; u < kFirstParts; ++u) mz[u] = pp[min(p0 + 2 * u, n_p - 1) * pstep];
+    uint2 aug_direct[NQT];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        if (FROM_LSE) aug_direct[qt] = make_uint2(__float_as_uint(*nsrc[qt]), 0u);
+        else aug_direct[qt] = *(const uint2*)nsrc[qt];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_tile_any(ks.rsrc, slots, off_first, ks.row_bytes, valid_first, lane);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < kFirstParts; ++u)
+        if (!fused || p0 + 2 * u >= n_p) mz[u] = make_float2(-1.0e30f, 0.f);
+    const bool merges = fused && (threadIdx.x >> 1) < NQT * kRowTile;
+    if (FROM_LSE) {
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
+            // padded rows get 2^(c*x) = 0
+            aug_direct[qt] = split_bf16x3(row < a.rows ? -__uint_as_float(aug_direct[qt].x) * a.inv_scale : -1.0e30f);
+        }
+    }
+    q_rows_stage<NQT>(lane, &lds[0][0][0], qraw, qpad, qf);
     float cM = -1.0e30f, cZ = 0.f;
     auto merge_in = [&](float2 t) __attribute__((always_inline)) {
         const float mm = fmaxf(cM, t.x);
@@ -657,27 +794,33 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
             for (int u = 0; u < 8; ++u) merge_in(more[u]);
         }
     }
-    if (fused) {
-        const float oM = __shfl_xor(cM, 1), oZ = __shfl_xor(cZ, 1);  // the odd neighbour's half; even threads finish the row
-        const float mm = fmaxf(cM, oM);
-        const float zz = cZ * __builtin_amdgcn_exp2f(cM - mm) + oZ * __builtin_amdgcn_exp2f(oM - mm);
-        const int crow = a.row_tile0 * kRowTile + (int)(threadIdx.x >> 1);
-        uint2* aug_s = (uint2*)&lds[0][1][0];  // the query rows have left this slot (second barrier of load_q_shared)
-        if (!(threadIdx.x & 1) && (threadIdx.x >> 1) < NQT * kRowTile)
-            aug_s[threadIdx.x >> 1] = split_bf16x3(crow < a.rows ? -(mm + __log2f(zz)) / a.c : -1.0e30f);
-        __syncthreads();
-    }
     auto set_aug = [&](int qt, uint2 t) {  // the three bf16 terms sit in k-elements 0..2 of the extra MFMA step (lane half 0)
         u32x4 v = {0u, 0u, 0u, 0u};
         if (half == 0) { v[0] = t.x; v[1] = t.y; }
         qaug[qt] = as_bf16x8(v);
     };
     if (fused) {
-        const uint2* aug_s = (const uint2*)&lds[0][1][0];
+        const float oM = __shfl_xor(cM, 1), oZ = __shfl_xor(cZ, 1);  // the odd neighbour's half; even threads finish the row
+        const float mm = fmaxf(cM, oM);
+        const float zz = cZ * __builtin_amdgcn_exp2f(cM - mm) + oZ * __builtin_amdgcn_exp2f(oM - mm);
+        const int crow = a.row_tile0 * kRowTile + (int)(threadIdx.x >> 1);
+        const uint32_t aug_s = lds_addr(&lds[0][1][0]);  // the query rows have left this slot (second barrier of q_rows_stage)
+        if (!(threadIdx.x & 1) && (threadIdx.x >> 1) < NQT * kRowTile) {
+            lds_put8(aug_s + 8u * (threadIdx.x >> 1), split_bf16x3(crow < a.rows ? -(mm + __log2f(zz)) / a.c : -1.0e30f));
+            lds_wait_all();
+        }
+        bare_barrier();
 #pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) set_aug(qt, aug_s[qt * kRowTile + (lane & 31)]);
-        wait_frags_read();
-        __syncthreads();  // the slot is refilled with a key tile next
+        for (int qt = 0; qt < NQT; ++qt) set_aug(qt, lds_get8_waited(aug_s + 8u * (qt * kRowTile + (lane & 31))));
+        bare_barrier();  // the slot is refilled with a key tile next
+    } else {
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) set_aug(qt, aug_direct[qt]);
+    }
+    if (a.zero) {  // words the selection needs cleared (stores: they only join the loads the sweep's first wait covers)
+        const uint64_t per = (a.zero_words + gridDim.x - 1) / gridDim.x;
+        const uint64_t z0 = per * blockIdx.x, z1 = z0 + per < a.zero_words ? z0 + per : a.zero_words;
+        for (uint64_t i = z0 + threadIdx.x; i < z1; i += blockDim.x) a.zero[i] = 0u;
     }
     if (w.n_tiles == 0) {  // surplus wave of the sequence's last workgroup
         if (DIFF) __syncthreads();  // the workgroup's final merge
@@ -685,22 +828,6 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
     }
     const int D = a.depth;  // uniform
     if (D == 2 && w.n_tiles > 1) fetch(1);
-    if (!fused) {
-#pragma unroll
-        for (int qt = 0; qt < NQT; ++qt) {
-            const int row = (a.row_tile0 + qt) * kRowTile + (lane & 31);
-            if (FROM_LSE) {
-                float x = -1.0e30f;  // padded rows get 2^(c*x) = 0
-                if (row < a.rows) {
-                    const int i = row / a.group, h = w.g * a.group + row % a.group;
-                    x = -a.lse[((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q + i) * a.h_q + h] * a.inv_scale;
-                }
-                set_aug(qt, split_bf16x3(x));
-            } else {
-                set_aug(qt, a.aug[((int64_t)(w.layer * a.n_seq + w.seq) * a.h_kv + w.g) * a.RP + row]);
-            }
-        }
-    }
     u32x4 ones_bits = {0u, 0u, 0u, 0u};
     if (half == 0) { ones_bits[0] = 0x3F803F80u; ones_bits[1] = 0x00003F80u; }  // 1.0 at elements 0..2
     const bf16x8 ones = as_bf16x8(ones_bits);
@@ -783,6 +910,8 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_score_kernel(ScoreArgs
         }
     }
 }
+
+template __global__ void jq_score_kernel<4, false, false, false>(ScoreArgs);  // placement: see jq_lib.hip
 
 // ------------------------------------------------------------------------------------------------
 // host side
