@@ -256,19 +256,19 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
 
     // Requested first: this thread's four level-1 bins, the header of "its" segment (thread t looks after segment
     // t), and the first entries of the wave's first segments; all of that arrives while the
-    // threshold bin is being picked (128 entries of each, two per lane).  The entry loads are unconditional, from clamped and therefore always valid
+    // threshold bin is being picked (128 entries of each, two per lane in one 16-byte load: the CU's load path is
+    // what bounds this phase, and it counts instructions).  The entry loads are unconditional, from clamped and therefore always valid
     // addresses -- a segment's storage holds `head` entries whatever its element count -- so that all of them are in
     // flight together; what lies outside is masked afterwards.
     uint32_t c1[kHistBins / kFinThreads];
 #pragma unroll
     for (int e = 0; e < kHistBins / kFinThreads; ++e) c1[e] = p.hist[kHistBins - 1 - ((kHistBins / kFinThreads) * (int)threadIdx.x + e)];
     const uint4 my_hdr = seg_hdr[min((int)threadIdx.x, n_seg - 1)];
-    uint2 first[kSegBatch], second[kSegBatch];  // entries lane and 64 + lane of the wave's i-th segment
+    uint4 ent[kSegBatch];  // entries 2 * lane and 2 * lane + 1 of the wave's i-th segment: (key, position) twice
 #pragma unroll
     for (int i = 0; i < kSegBatch; ++i) {
         const uint2* sp = segs + (int64_t)min(wave + i * kFinWaves, n_seg - 1) * head;
-        first[i] = sp[lane];
-        second[i] = sp[64 + lane];
+        ent[i] = ((const uint4*)sp)[lane];  // one 16-byte load per lane covers the segment's first 128 entries
     }
     for (int w = 4 * threadIdx.x; w < 2 * words_cap; w += 4 * kFinThreads) *(uint4*)&keep[w] = make_uint4(0u, 0u, 0u, 0u);  // keep, ties
     for (int b = 4 * threadIdx.x; b < 3072 + 96; b += 4 * kFinThreads) *(uint4*)&bins2[b] = make_uint4(0u, 0u, 0u, 0u);  // histograms, tmp, res, cnt
@@ -303,14 +303,15 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         }
     };
     const int my_n = seg_n[min(wave + (lane & (kSegBatch - 1)) * kFinWaves, n_seg - 1)];  // lane i < 16: the wave's i-th segment
-    uint64_t ge_mask[kSegBatch];    // wave-uniform: lanes whose entry of the i-th segment qualifies (first 64 entries)
-    uint32_t n_mine = 0, more = 0;  // more, bit i: the 64th entry of the i-th segment still qualified
+    uint64_t ge_even[kSegBatch], ge_odd[kSegBatch];  // wave-uniform: lanes whose even / odd entry of the i-th segment qualifies
+    uint32_t n_mine = 0, again = 0;                  // again, bit i: the 128th entry of the i-th segment still qualified
 #pragma unroll
     for (int i = 0; i < kSegBatch; ++i) {
         const int n = wave + i * kFinWaves < n_seg ? __builtin_amdgcn_readlane(my_n, i) : 0;  // -1: not from its entries
-        ge_mask[i] = __ballot(lane < n && (first[i].x >> 21) >= b1);
-        n_mine += (uint32_t)__popcll(ge_mask[i]);
-        more |= (uint32_t)(ge_mask[i] >> 63) << i;
+        ge_even[i] = __ballot(2 * lane < n && (ent[i].x >> 21) >= b1);
+        ge_odd[i] = __ballot(2 * lane + 1 < n && (ent[i].z >> 21) >= b1);
+        n_mine += (uint32_t)(__popcll(ge_even[i]) + __popcll(ge_odd[i]));
+        again |= (uint32_t)(ge_odd[i] >> 63) << i;
     }
     if (n_mine) {  // wave-uniform
         uint32_t to = 0;
@@ -318,22 +319,13 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
         to = __builtin_amdgcn_readfirstlane(to);
 #pragma unroll
         for (int i = 0; i < kSegBatch; ++i) {
-            const uint64_t m = ge_mask[i];
-            const uint32_t slot = to + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-            if (((m >> lane) & 1) && slot < (uint32_t)qual_cap) qual[slot] = first[i];
-            to += (uint32_t)__popcll(m);
-        }
-    }
-    // entries 64..127 of the few segments whose 64th entry still qualified (they are in registers already)
-    uint32_t again = 0;  // bit i: the 128th entry qualified as well
-    if (more) {  // wave-uniform
-#pragma unroll
-        for (int i = 0; i < kSegBatch; ++i) {
-            if (!(more & (1u << i))) continue;
-            const int n = __builtin_amdgcn_readlane(my_n, i);
-            const bool ge = 64 + lane < n && (second[i].x >> 21) >= b1;
-            if (ge) put(second[i].x, second[i].y);
-            again |= (uint32_t)(__ballot(ge) >> 63) << i;
+            const uint64_t me = ge_even[i], mo = ge_odd[i];
+            const uint32_t se = to + __builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, 0u));
+            if (((me >> lane) & 1) && se < (uint32_t)qual_cap) qual[se] = make_uint2(ent[i].x, ent[i].y);
+            to += (uint32_t)__popcll(me);
+            const uint32_t so = to + __builtin_amdgcn_mbcnt_hi((uint32_t)(mo >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mo, 0u));
+            if (((mo >> lane) & 1) && so < (uint32_t)qual_cap) qual[so] = make_uint2(ent[i].z, ent[i].w);
+            to += (uint32_t)__popcll(mo);
         }
     }
     // Second visits (a segment whose 128th entry still qualified, a block that is classified from its scores), and
