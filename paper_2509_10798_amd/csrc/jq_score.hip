@@ -207,46 +207,11 @@ __device__ __forceinline__ void lds_get_frags(const char* slot, bf16x8 (&kf)[8],
     }
 }
 
-// Query rows of the workgroup's KV head (row r = i * group + hh  <->  Q[i, g*group + hh]) as MFMA operands
-// of every wave.  Wave qt fetches row tile qt like a key tile -- every load instruction covers four whole
-// 256-byte rows (lane l takes 16 B of row 4i + (l >> 4)), so each cache line is requested once -- and
-// writes it, swizzled, into its own second LDS slot; after a barrier every wave reads all tiles in operand
-// order.  The second barrier frees the slots for key tiles.  Every wave of the workgroup must call this.
-template <int NQT>
-__device__ __forceinline__ void load_q_shared(const ScoreArgs& a, const WaveItem& w, int lane, char* lds_base,
-                                              bf16x8 (&qf)[NQT][8]) {
-    static_assert(NQT <= kScoreWaves, "one wave per query-row tile");
-    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    if (wv < NQT) {
-        const char* qbase = (const char*)a.Q + ((int64_t)(w.layer * a.n_seq + w.seq) * a.n_q) * a.h_q * kHeadDim * 2;
-        char* slot = lds_base + (wv * 2 + 1) * kSlotBytes;
-        u32x4 raw[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = 4 * i + (lane >> 4);
-            const int row = (a.row_tile0 + wv) * kRowTile + r;
-            const bool valid = row < a.rows;
-            int it = 0, hh = 0;
-            if (valid) {
-                if (a.group_shift >= 0) { it = row >> a.group_shift; hh = row & (a.group - 1); }
-                else { it = row / a.group; hh = row % a.group; }
-            }
-            const int c = (lane & 15) ^ (r & 15);  // logical chunk; it lands at physical chunk (lane & 15)
-            u32x4 v = *(const u32x4*)(qbase + ((int64_t)it * a.h_q + (w.g * a.group + hh)) * kHeadDim * 2 + c * 16);
-            if (!valid) v = u32x4{0u, 0u, 0u, 0u};  // rows past the end: row 0 of the head was read (in bounds), then zeroed
-            raw[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(slot + 1024 * i + 16 * lane) = raw[i];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) lds_get_frags(lds_base + (qt * 2 + 1) * kSlotBytes, qf[qt], lane);
-    wait_frags_read();
-    __syncthreads();
-}
-
-// ---- the same start-up with the first key tile in flight across it (second pass) ----------------------
+// ---- start-up: the query rows as MFMA operands of every wave, with the first key tile in flight ---------
+// Query rows of the workgroup's KV head (row r = i * group + hh  <->  Q[i, g*group + hh]): wave qt fetches row
+// tile qt like a key tile -- every load instruction covers four whole 256-byte rows (lane l takes 16 B of row
+// 4i + (l >> 4)), so each cache line is requested once -- and writes it, swizzled, into its own second LDS slot;
+// after a barrier every wave reads all tiles in operand order; a second barrier frees the slots for key tiles.
 // The compiler cannot tell which LDS bytes a direct-to-LDS load writes, so before any LDS access it generates
 // it waits for every such load that is outstanding -- here that would be the first key tile, whose flight
 // (the first sixteenth of K arriving at the rate of the memory system) is exactly what the start-up should hide
@@ -315,9 +280,11 @@ __device__ __forceinline__ void q_rows_where(const ScoreArgs& a, const WaveItem&
         pad |= valid ? 0u : 1u << i;
     }
 }
-// ... and their way through LDS into operand order, as load_q_shared, with the first key tile in flight.
+// ... and their way through LDS into operand order, with the first key tile in flight.  Every wave of the
+// workgroup must call this (two barriers).
 template <int NQT>
 __device__ __forceinline__ void q_rows_stage(int lane, char* lds_base, const u32x4 (&raw)[8], uint32_t pad, bf16x8 (&qf)[NQT][8]) {
+    static_assert(NQT <= kScoreWaves, "one wave per query-row tile");
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (wv < NQT) {
         const uint32_t slot = lds_addr(lds_base + (wv * 2 + 1) * kSlotBytes);
@@ -492,10 +459,28 @@ __global__ __launch_bounds__(kScoreWaves * 64, 2) void jq_stats_kernel(ScoreArgs
     // the workgroup's query rows into operand order.  From then on the wave's tiles alternate between its two
     // slots, and the next tile is requested as soon as the current one's fragments are in registers (with
     // a.depth == 2 the tile after that one is in flight as well).
-    first_page();
-    if (n_all > 0) fetch(0);
+    // As in the second pass the query rows are requested first, into registers, the key tile after them, and the
+    // rows pass through LDS while the tile is in flight (explicit LDS instructions, every request unconditional in
+    // one basic block: see lds_addr()).  A wave without tiles requests the sequence's first tile and drops it.
     bf16x8 qf[NQT][8];
-    load_q_shared<NQT>(a, w, lane, &lds[0][0][0], qf);
+    {
+        const u32x4* qsrc[8];
+        uint32_t qpad;
+        q_rows_where<NQT>(a, w, lane, qsrc, qpad);
+        const int t_first = w.n_tiles > 0 ? w.wave : 0;
+        const int page_first = PAGED ? tile_page<PAGED>(ks, t_first) : 0;
+        if (PAGED && w.n_tiles > 1) page_next = tile_page<PAGED>(ks, t_first + w.n_waves);
+        const uint32_t off_first = tile_offset<PAGED>(ks, t_first, page_first);
+        const int valid_first = min(kKeyTile, w.L - t_first * kKeyTile);
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 qraw[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) qraw[i] = *qsrc[i];
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_tile_any(ks.rsrc, slots, off_first, ks.row_bytes, valid_first, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        q_rows_stage<NQT>(lane, &lds[0][0][0], qraw, qpad, qf);
+    }
     const float c = a.c;
     float m[NQT], z[NQT];
 #pragma unroll
