@@ -141,6 +141,24 @@ struct Knobs {
 };
 const Knobs& knobs();
 
+// Stores of a kernel's bulk OUTPUT (pooled scores, block heads, kept positions and rows): nothing in the same
+// kernel reads them back, the next kernel does.  Left in L2 as dirty lines they are written back when the kernel
+// ends, and the next kernel cannot start before that: the gap between two dependent kernels grows with what the
+// first one wrote (2.45 / 2.98 / 3.32 us after 4 / 16 / 64 MB, whatever the second kernel's shape).  Stored
+// non-temporally they are on their way out while the kernel still runs.  Measured with the builds side by side in
+// one process: kept rows -1.1 us per step (the next step's first kernel starts sooner), pooling's outputs -0.4 us
+// more; for the second pass's scores it makes no difference, so they stay plain stores.  Agent-scope stores (sc1)
+// did the same for pooling and nothing for the kept rows.
+typedef uint32_t jq_u32x4 __attribute__((ext_vector_type(4)));
+template <class T>
+__device__ __forceinline__ void store_stream(T* p, T v) {  // T: float or int32_t
+    __builtin_nontemporal_store(v, p);
+}
+__device__ __forceinline__ void store_stream16(void* p, uint4 v) {
+    const jq_u32x4 x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, (jq_u32x4*)p);
+}
+
 // Workgroup barrier that orders LDS traffic only: global loads and stores that are still outstanding stay in
 // flight across it (a plain __syncthreads() waits for all of them first).  For workgroups that communicate
 // through LDS alone.

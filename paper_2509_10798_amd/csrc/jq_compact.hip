@@ -42,8 +42,8 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_kernel(CompactArgs
     const int64_t dst = ((kv_row(a.pm_out, a.tab.cu_bud, a.TB, layer, s, (int)(tb - a.tab.cu_bud[s])) * a.h_kv + g) * kHeadDim) * 2 + part * 16;
     const u32x4 kv = *(const u32x4*)(a.K + src);
     const u32x4 vv = *(const u32x4*)(a.V + src);
-    *(u32x4*)(a.K_out + dst) = kv;
-    *(u32x4*)(a.V_out + dst) = vv;
+    __builtin_nontemporal_store(kv, (u32x4*)(a.K_out + dst));  // bulk output: see store_stream()
+    __builtin_nontemporal_store(vv, (u32x4*)(a.V_out + dst));
 }
 
 hipError_t launch_compact(const Plan& p, const void* K, const void* V, const int32_t* idx, void* K_out, void* V_out,
@@ -110,8 +110,8 @@ __global__ __launch_bounds__(kCompactThreads) void jq_compact_inplace_kernel(Inp
         const int64_t dst = ((dst_row * a.h_kv + g) * kHeadDim) * 2 + part * 16;
         const u32x4 kv = staged ? *(const u32x4*)(a.stage + stg) : *(const u32x4*)(a.K + src);
         const u32x4 vv = staged ? *(const u32x4*)(a.stage + v_stage + stg) : *(const u32x4*)(a.V + src);
-        *(u32x4*)(a.K + dst) = kv;
-        *(u32x4*)(a.V + dst) = vv;
+        __builtin_nontemporal_store(kv, (u32x4*)(a.K + dst));  // bulk output: see store_stream()
+        __builtin_nontemporal_store(vv, (u32x4*)(a.V + dst));
     }
 }
 

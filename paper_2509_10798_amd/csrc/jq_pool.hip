@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
         }
         if (POOL) {
             if (((row + p0) & 3) == 0 && j0 + 3 < cnt) {
-                *(float4*)&a.out[row + p0 + j0] = make_float4(v[0], v[1], v[2], v[3]);
+                store_stream16(&a.out[row + p0 + j0], make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
             } else {
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
@@ -227,10 +227,10 @@ __global__ __launch_bounds__(kPoolThreads) void jq_pool_kernel(PoolArgs a) {
     if ((uint32_t)j0 < min(head, n_win)) {
         const uint4* src = (const uint4*)&sorted[j0];
         uint4* dst = (uint4*)(a.seg + seg_id * head + j0);
-        dst[0] = src[0];
-        dst[1] = src[1];
+        store_stream16(dst, src[0]);
+        store_stream16(dst + 1, src[1]);
     }
-    if (threadIdx.x == 0) a.seg_hdr[seg_id] = make_uint4(base, n_win, n_win >= head ? sorted[head - 1].x : 0u, 0u);
+    if (threadIdx.x == 0) store_stream16(&a.seg_hdr[seg_id], make_uint4(base, n_win, n_win >= head ? sorted[head - 1].x : 0u, 0u));
 }
 
 // Forward value of the training objective (paper Section 4.2, Eq. 3-5): mean squared difference of two averaged

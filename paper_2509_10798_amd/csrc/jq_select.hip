@@ -115,8 +115,8 @@ struct Problem {
     uint32_t* hist;
     const int32_t* pos_in; int32_t* pos_out;  // this problem's slices of the position tables, or null
     __device__ void emit(uint32_t slot, int row) const {
-        out[slot] = row;
-        if (pos_out) pos_out[slot] = pos_in[row];
+        store_stream(&out[slot], (int32_t)row);
+        if (pos_out) store_stream(&pos_out[slot], pos_in[row]);
     }
 };
 
@@ -453,8 +453,8 @@ __global__ __launch_bounds__(kFinThreads) void jq_select_finalize_kernel(SelectA
             const int64_t dst = ((kv_row_from(a.pm_out, p.bud0, a.TB, p.layer, p.s, (int)(o0 + rr)) * a.h_kv + p.g) * kHeadDim) * 2 + part * 16;
             const uint4 kv = *(const uint4*)(a.K + src);
             const uint4 vv = *(const uint4*)(a.V + src);
-            *(uint4*)(a.K_out + dst) = kv;
-            *(uint4*)(a.V_out + dst) = vv;
+            store_stream16(a.K_out + dst, kv);
+            store_stream16(a.V_out + dst, vv);
         }
     };
     const bool want_rows = a.K_out != nullptr || a.stage != nullptr;  // uniform
