@@ -304,3 +304,46 @@ def test_evict_paged_inplace_writes_the_pruned_cache_into_the_same_pools(where):
         for r in range(ps):
             if (pg, r) not in written:
                 assert np.array_equal(Kq_h[:, pg, r], Kp_h[:, pg, r]), (pg, r)
+
+
+def test_evict_paged_inplace_with_supplied_normalisers_and_forced_positions():
+    # one pass over the pools (normalisers supplied), sinks and a local window always kept, per-layer budgets:
+    # the same kept rows as the ordinary paged call, on the sequences' own first pages
+    torch = torch_()
+    ps = 32
+    w = make_workload(1, seq_lens=[1100, 260], budget=[96, 40], n_layers=2)
+    Q, K, V = w.assemble()
+    Kp_, Vp_, tab_ = page_out(K, V, w.seq_lens, ps, seed=5, spare_pages=3)
+    pages = jq.Pages(page_size=ps, n_pages=Kp_.shape[1], block_table=torch.from_numpy(tab_).cuda())
+    Kp, Vp = to_dev_bf16(Kp_), to_dev_bf16(Vp_)
+    lb = torch.tensor([[96, 40], [50, 17]], dtype=torch.int32, device="cuda")
+    sh = jq.Shape(n_layers=2, seq_lens=w.seq_lens, n_q=w.n_q, h_q=w.h_q, h_kv=w.h_kv, pool_k=w.pool_k, budgets=w.budgets,
+                  keep_first=4, keep_last=8, layer_budgets=lb)
+    lse = torch.full((2, 2, w.n_q, w.h_q), 12.0, dtype=torch.float32, device="cuda")   # above every logit of this workload
+    Qd = to_dev_bf16(Q)
+    Ko = torch.zeros((2, sh.TB, w.h_kv, w.d), dtype=torch.bfloat16, device="cuda"); Vo = torch.zeros_like(Ko)
+    idx = torch.full((2, w.h_kv, sh.TB), -1, dtype=torch.int32, device="cuda")
+    _, _, _, pooled = jq.evict_paged(sh, pages, Qd, Kp, Vp, lse=lse, K_out=Ko, V_out=Vo, idx_out=idx)
+    table = pages.block_table.cpu().numpy()
+    n_out = [-(-b // ps) for b in w.budgets]
+    out_table = np.zeros((2, max(n_out)), dtype=np.int32)
+    for s_ in range(2):
+        out_table[s_, :n_out[s_]] = table[s_, :n_out[s_]]
+    out_pages = jq.Pages(page_size=ps, n_pages=pages.n_pages, block_table=torch.from_numpy(out_table).cuda())
+    Kq, Vq = Kp.clone(), Vp.clone()
+    idx2 = torch.full_like(idx, -1)
+    _, _, _, pooled2 = jq.evict_paged_inplace(sh, pages, out_pages, Qd, Kq, Vq, lse=lse, idx_out=idx2)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(pooled, pooled2)
+    Kq_h, Vq_h, Ko_h, Vo_h = from_dev_bf16(Kq), from_dev_bf16(Vq), from_dev_bf16(Ko), from_dev_bf16(Vo)
+    idx_h, lb_h, cb = idx.cpu().numpy(), lb.cpu().numpy(), w.cu_budgets
+    for layer in range(2):
+        for s_ in range(2):
+            B, L = int(lb_h[layer, s_]), w.seq_lens[s_]
+            kept = idx_h[layer, :, cb[s_]:cb[s_] + B]
+            assert (kept[:, :4] == np.arange(4)).all() and (kept[:, -8:] == np.arange(L - 8, L)).all()   # sinks and window
+            assert (idx_h[layer, :, cb[s_] + B:cb[s_ + 1]] == -1).all()                                   # unused slots untouched
+            for b in range(B):
+                pg, r = int(out_table[s_, b // ps]), b % ps
+                np.testing.assert_array_equal(Kq_h[layer, pg, r], Ko_h[layer, cb[s_] + b])
+                np.testing.assert_array_equal(Vq_h[layer, pg, r], Vo_h[layer, cb[s_] + b])
